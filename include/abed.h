@@ -1,0 +1,191 @@
+/*
+ * libabed: 2-D convolution with algorithm-based error detection (ABED) fused
+ * in, for AMD gfx950.  C ABI, no C++ or framework types in any signature.
+ *
+ * The method (Hari, Sullivan, Tsai, Keckler, "Making Convolutions Resilient via
+ * Algorithm-Based Error Detection Techniques"):
+ *   FC, filter checksum (Sec. 3.1): a checksum filter wsum = sum_k w[k] is
+ *     convolved with the input; the extra output fmap must equal sum_k y[.,k].
+ *   IC option 1, batch checksum (Sec. 3.2): a checksum image xsum = sum_n x[n]
+ *     is convolved with the filters; the extra batch entry must equal sum_n y[n].
+ *   Both meet in a corner value conv(xsum, wsum) (row+column checksums, Sec. 2.1).
+ *   int8 (Sec. 4.1): checksums are generated in int32 and stored as int8 digit
+ *     tensors (balanced base 256); digit fmaps are recombined by shifts of
+ *     8 bits per digit; all reductions and comparisons are made mod 2^32
+ *     (the modular fallback named at the end of Sec. 4.1), equality is exact.
+ *   fp16 (Sec. 7): checksums are stored as a hi/lo pair of fp16 tensors,
+ *     accumulation is fp32, comparison is against a threshold.
+ *   Variants (Sec. 4.3): how much of the checking is fused into the
+ *     convolution kernel; the check is always made on the accumulators
+ *     (ConvOut) before the epilog.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library
+ *     never allocates, frees or synchronises.  Descriptor/epilogue/injection
+ *     structs and the layout struct are HOST pointers, read during the call.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and the call returns without waiting.
+ *   - Layouts: x[N][H][W][C], w[K][R][S][C] (R = filter height, S = width),
+ *     y[N][P][Q][K]; P = (H + 2 pad_h - R)/stride_h + 1, Q likewise.
+ *     Cross-correlation, dilation 1, one group, zero padding.
+ *   - Every call returns an abed_status_t; nothing is thrown.
+ */
+#ifndef ABED_H
+#define ABED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ABED_OK = 0,
+    ABED_EINVAL = 1,        /* null / negative / inconsistent argument               */
+    ABED_EUNSUPPORTED = 2,  /* valid convolution outside the implemented shape set    */
+    ABED_EWORKSPACE = 3,    /* workspace smaller than abed_get_layout() reports        */
+    ABED_EHIP = 4,          /* a HIP call failed (see abed_last_hip_error)             */
+    ABED_ERANGE = 5         /* a checksum would need more than four digits (Sec. 4.1)  */
+} abed_status_t;
+
+/* Implementation options (Sec. 4.3).  All checked variants give the same
+ * outputs and the same flags on a fault-free run. */
+typedef enum {
+    ABED_NONE = 0,                     /* unchecked convolution (the baseline)                         */
+    ABED_UNFUSED = 1,                  /* one kernel per task: ICG, conv, checksum convs, verify, epilog */
+    ABED_FUSED_WRITE = 2,              /* one augmented conv kernel writes ConvOut and the checksum fmaps;
+                                          a verify kernel reads them back                              */
+    ABED_FUSED_PARTIAL_REDUCTION = 3,  /* the conv kernel reduces inside each tile and writes partial
+                                          sums; a small finish kernel compares                         */
+    ABED_FUSED_OCG = 4,                /* the conv kernel reduces, compares and sets the flags itself  */
+    ABED_FUSED_IOCG = 5,               /* as 4, and also emits the next layer's batch checksum from
+                                          the epilog's output                                          */
+    ABED_DUPLICATE = 6                 /* unchecked convolution twice + element-wise compare           */
+} abed_variant_t;
+
+typedef enum { ABED_INT8 = 0, ABED_FP16 = 1 } abed_dtype_t;
+
+typedef struct {
+    int32_t N, H, W, C, K, R, S;
+    int32_t stride_h, stride_w, pad_h, pad_w;
+} abed_conv_desc_t;
+
+/* Epilog of Sec. 4.3 for the int8 path: ConvOut -> fp32, * scale[k], + bias[k]
+ * (two separately rounded fp32 operations), ReLU if relu != 0, round to
+ * nearest even, clamp to [-128,127].  scale and bias are device pointers to K
+ * floats.  With a NULL epilogue the raw int32 ConvOut is the output. */
+typedef struct {
+    const float *scale;
+    const float *bias;
+    int32_t relu;
+} abed_epilogue_t;
+
+/* Fault injection for tests (Sec. 5.4 "Resilience Evaluation").  One bit of one
+ * element is flipped:
+ *   site 1 (ACC): accumulator of output element `index` (flat index into
+ *     y[N][P][Q][K]) after the convolution loop, before the reductions and the store;
+ *   site 2 (STORED): the stored ConvOut element `index`, after the convolution
+ *     kernel and before any kernel that reads ConvOut back (only the variants that
+ *     verify from memory, 1 and 2, can see it; int32 ConvOut only).
+ * Flips in x, w, wchk or xchk need no library support: the caller owns those buffers. */
+typedef struct {
+    int32_t site;
+    int64_t index;
+    int32_t bit;
+} abed_inject_t;
+
+/* What abed_get_layout reports for one (convolution, dtype, variant). */
+typedef struct {
+    int32_t tile_m;        /* output rows (n,p,q) per tile = tile_pixels * n_padded          */
+    int32_t tile_n;        /* output channels per tile                                       */
+    int32_t tile_pixels;   /* output pixels per tile; a tile holds them for ALL images       */
+    int32_t n_padded;      /* batch size the kernel pads N to inside a tile                  */
+    int32_t grid_m;        /* ceil(P*Q / tile_pixels)                                        */
+    int32_t grid_n;        /* ceil(K / tile_n)                                               */
+    int32_t d_f, d_i;      /* checksum tensors per filter / batch checksum                   */
+    int64_t n_flag_words;  /* grid_m * grid_n uint32 words                                   */
+    int64_t workspace_bytes;
+    int64_t wchk_bytes;    /* d_f * R*S*C elements                                           */
+    int64_t xchk_bytes;    /* d_i * H*W*C elements                                           */
+    int64_t xchk_next_bytes; /* d_i * P*Q*K elements (variant 5)                             */
+} abed_layout_t;
+
+/* Flag word of tile (tm, tn) is flags[tm * grid_n + tn].  Tile tm covers output
+ * pixels [tm*tile_pixels, (tm+1)*tile_pixels) (pixel index p*Q + q) of every
+ * image; tile column tn covers channels [tn*tile_n, (tn+1)*tile_n).
+ *   bit 0: FC mismatch (Sec. 3.1) in an output row (n,p,q) of tile-row tm
+ *          (reported on tn = 0 when K spans several tile columns);
+ *   bit 1: IC mismatch (Sec. 3.2 option 1) at a (p,q,k) of this tile;
+ *   bit 2: corner mismatch at a pixel of tile-row tm: sum_n of the FC fmap or
+ *          sum_k of the IC fmap differs from conv(xsum, wsum) (reported on tn = 0).
+ * Every word is written on every checked call. */
+#define ABED_FLAG_FC 1u
+#define ABED_FLAG_IC 2u
+#define ABED_FLAG_CORNER 4u
+
+/* Host only.  Fills *out; ABED_EINVAL / ABED_EUNSUPPORTED / ABED_ERANGE as above. */
+abed_status_t abed_get_layout(const abed_conv_desc_t *desc, int32_t dtype, int32_t variant,
+                              abed_layout_t *out);
+
+/* Offline step (Sec. 3.1, Sec. 4.1, Sec. 4.2): wsum = sum_k w[k] in int32, split
+ * into d_f int8 digit filters wchk[d_f][R][S][C].  fp16: wsum in fp32, stored as
+ * hi = fp16(wsum), lo = fp16(wsum - hi): wchk[2][R][S][C]. */
+abed_status_t abed_filter_prepare_int8(const abed_conv_desc_t *desc, const int8_t *w, int8_t *wchk,
+                                       void *stream);
+abed_status_t abed_filter_prepare_fp16(const abed_conv_desc_t *desc, const void *w, void *wchk,
+                                       void *stream);
+
+/* Online input checksum generation, ICG (Sec. 3.2 option 1, Sec. 4.3): xsum =
+ * sum_n x[n] in int32 (fp32), split into d_i digit images xchk[d_i][H][W][C]. */
+abed_status_t abed_input_checksum_int8(const abed_conv_desc_t *desc, const int8_t *x, int8_t *xchk,
+                                       void *stream);
+abed_status_t abed_input_checksum_fp16(const abed_conv_desc_t *desc, const void *x, void *xchk,
+                                       void *stream);
+
+/* Zero the part of a workspace that the library expects to be zero on first
+ * use (arrival counters).  Call once after allocating a workspace. */
+abed_status_t abed_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/* Checked int8 convolution (int32 accumulation; Sec. 3.1, 3.2, 4.1, 4.3).
+ *   x, w        inputs, int8.
+ *   wchk        from abed_filter_prepare_int8 (ignored for variants 0 and 6; may be NULL then).
+ *   xchk        digit images of the batch checksum.  For checked variants the caller
+ *               provides the buffer (xchk_bytes); if compute_xchk != 0 the call first
+ *               runs the ICG kernel into it (counted as part of the variant), else it
+ *               uses the contents as given (a previous layer's xchk_next, or a test's).
+ *   y           int32[N][P][Q][K] if epilogue == NULL, else int8[N][P][Q][K].
+ *   flags       n_flag_words words (checked variants), else may be NULL.
+ *   xchk_next   variant 5 with an epilogue: int8[d_i][P][Q][K], the batch checksum
+ *               digits of the int8 output; else NULL.
+ *   workspace   workspace_bytes of scratch, 256-byte aligned.
+ *   y2          variant 6 only: second output buffer of the same size as y; flags[0]
+ *               is set to 1 if the two runs differ.
+ * Errors: ABED_EINVAL (null pointer that is needed, bad descriptor),
+ * ABED_EUNSUPPORTED (C not a multiple of 16, N > 256, K or C*R*S beyond limits),
+ * ABED_EWORKSPACE, ABED_EHIP. */
+abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+                             const int8_t *wchk, int8_t *xchk, int32_t compute_xchk,
+                             void *y, const abed_epilogue_t *epilogue, int32_t variant,
+                             uint32_t *flags, int8_t *xchk_next,
+                             void *workspace, size_t workspace_bytes,
+                             const abed_inject_t *inject, void *y2, void *stream);
+
+/* Checked fp16 convolution (fp32 accumulation; Sec. 7).  As above with fp16
+ * data; y is fp16 (out_fp32 == 0) or fp32.  A check fails when
+ * |s - c| > rtol * max(|s|, |c|) + atol, s the reduction of the real
+ * accumulators and c the checksum-path value (NaN counts as a failure). */
+abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const void *w,
+                             const void *wchk, void *xchk, int32_t compute_xchk,
+                             void *y, int32_t out_fp32, int32_t variant, float rtol, float atol,
+                             uint32_t *flags, void *workspace, size_t workspace_bytes,
+                             const abed_inject_t *inject, void *y2, void *stream);
+
+const char *abed_status_string(abed_status_t status);
+/* Text of the last HIP error seen by this thread's most recent failing call. */
+const char *abed_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABED_H */

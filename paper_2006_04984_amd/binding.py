@@ -1,0 +1,137 @@
+"""ctypes binding for libabed.so: argument marshalling only.  Every function has
+the name and meaning of the C entry point it calls (include/abed.h); tensors
+are torch tensors on the GPU, used for their device pointers only."""
+import ctypes
+import enum
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+
+class AbedError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("libabed: %s (status %d)" % (text, status))
+        self.status = status
+
+
+class Variant(enum.IntEnum):
+    NONE = 0
+    UNFUSED = 1
+    FUSED_WRITE = 2
+    FUSED_PARTIAL_REDUCTION = 3
+    FUSED_OCG = 4
+    FUSED_IOCG = 5
+    DUPLICATE = 6
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w")]
+
+
+class _Epilogue(ctypes.Structure):
+    _fields_ = [("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p), ("relu", ctypes.c_int32)]
+
+
+class _Inject(ctypes.Structure):
+    _fields_ = [("site", ctypes.c_int32), ("index", ctypes.c_int64), ("bit", ctypes.c_int32)]
+
+
+class Layout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("tile_m", "tile_n", "tile_pixels", "n_padded", "grid_m", "grid_n", "d_f", "d_i")] + \
+               [(n, ctypes.c_int64) for n in
+                ("n_flag_words", "workspace_bytes", "wchk_bytes", "xchk_bytes", "xchk_next_bytes")]
+
+
+EXPORTS = ["abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_fp16",
+           "abed_input_checksum_int8", "abed_input_checksum_fp16", "abed_workspace_init",
+           "abed_conv_int8", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error"]
+
+
+def lib_path():
+    return os.path.join(_HERE, "libabed.so")
+
+
+def lib():
+    """Open libabed.so (built by `python -m paper_2006_04984_amd.build`); fails loudly if absent."""
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise FileNotFoundError("%s not built: run python -m paper_2006_04984_amd.build" % path)
+        L = ctypes.CDLL(path)
+        for name in EXPORTS:
+            getattr(L, name)
+        L.abed_status_string.restype = ctypes.c_char_p
+        L.abed_status_string.argtypes = [ctypes.c_int]
+        L.abed_last_hip_error.restype = ctypes.c_char_p
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        L.abed_get_layout.argtypes = [ctypes.POINTER(ConvDesc), i32, i32, ctypes.POINTER(Layout)]
+        L.abed_filter_prepare_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+        L.abed_input_checksum_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+        L.abed_workspace_init.argtypes = [vp, ctypes.c_size_t, vp]
+        L.abed_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
+                                     vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp, vp]
+        _LIB = L
+    return _LIB
+
+
+def _check(status):
+    if status != 0:
+        L = lib()
+        text = L.abed_status_string(status).decode()
+        if status == 4:
+            text += ": " + L.abed_last_hip_error().decode()
+        raise AbedError(status, text)
+
+
+def _p(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    return ctypes.c_void_p(stream if isinstance(stream, int) else stream.cuda_stream)
+
+
+def desc_from_shape(s):
+    return ConvDesc(s.N, s.H, s.W, s.C, s.K, s.R, s.S, s.stride_h, s.stride_w, s.pad_h, s.pad_w)
+
+
+def get_layout(desc, dtype=0, variant=Variant.FUSED_OCG):
+    out = Layout()
+    _check(lib().abed_get_layout(ctypes.byref(desc), int(dtype), int(variant), ctypes.byref(out)))
+    return out
+
+
+def filter_prepare_int8(desc, w, wchk, stream=None):
+    _check(lib().abed_filter_prepare_int8(ctypes.byref(desc), _p(w), _p(wchk), _stream(stream)))
+
+
+def input_checksum_int8(desc, x, xchk, stream=None):
+    _check(lib().abed_input_checksum_int8(ctypes.byref(desc), _p(x), _p(xchk), _stream(stream)))
+
+
+def workspace_init(workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().abed_workspace_init(_p(workspace), nbytes, _stream(stream)))
+
+
+def conv_int8(desc, x, w, wchk, xchk, compute_xchk, y, variant, flags=None, epilogue=None, xchk_next=None,
+              workspace=None, inject=None, y2=None, stream=None):
+    """abed_conv_int8.  epilogue = (scale, bias, relu) tensors/bool or None;
+    inject = (site, index, bit) or None."""
+    epi = None
+    if epilogue is not None:
+        epi = ctypes.byref(_Epilogue(epilogue[0].data_ptr(), epilogue[1].data_ptr(), int(bool(epilogue[2]))))
+    inj = None
+    if inject is not None:
+        inj = ctypes.byref(_Inject(int(inject[0]), int(inject[1]), int(inject[2])))
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().abed_conv_int8(ctypes.byref(desc), _p(x), _p(w), _p(wchk), _p(xchk), int(bool(compute_xchk)),
+                                _p(y), epi, int(variant), _p(flags), _p(xchk_next), _p(workspace), nbytes,
+                                inj, _p(y2), _stream(stream)))

@@ -1,0 +1,44 @@
+"""Builds libabed.so (HIP, gfx950 only) in-tree: python -m paper_2006_04984_amd.build"""
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+BUILD = os.path.join(os.path.dirname(HERE), "_build")
+LIB = os.path.join(HERE, "libabed.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+
+UNITS = [("abed_api.hip", [], "abed_api.o"),
+         ("conv_dispatch.hip", [], "conv_dispatch.o")] + \
+        [("conv_inst.hip", ["-DINST_WK=%d" % wk], "conv_wk%d.o" % wk) for wk in (1, 4, 8, 16)]
+
+
+def _compile(unit):
+    src, defs, obj = unit
+    cmd = [HIPCC] + FLAGS + defs + ["-c", os.path.join(CSRC, src), "-o", os.path.join(BUILD, obj)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed: %s\n%s" % (" ".join(cmd), err))
+    return err
+
+
+def build(jobs=8, verbose=False):
+    os.makedirs(BUILD, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        for msg in ex.map(_compile, UNITS):
+            if verbose and msg.strip():
+                print(msg, file=sys.stderr)
+    objs = [os.path.join(BUILD, u[2]) for u in UNITS]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    subprocess.check_call(cmd)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,371 @@
+// Host side of libabed: argument checks, tile plan, workspace carving and kernel
+// launches for the variants of Sec. 4.3.  See include/abed.h for the contract.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/abed.h"
+#include "aux_kernels.h"
+#include "conv_launch.h"
+
+using namespace abed;
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+abed_status_t hip_fail(hipError_t e, const char *what)
+{
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+    return ABED_EHIP;
+}
+
+#define HIP_TRY(expr)                                            \
+    do {                                                         \
+        hipError_t e_ = (expr);                                  \
+        if (e_ != hipSuccess) return hip_fail(e_, #expr);        \
+    } while (0)
+
+#define LAUNCH_CHECK(name)                                       \
+    do {                                                         \
+        hipError_t e_ = hipGetLastError();                       \
+        if (e_ != hipSuccess) return hip_fail(e_, name);         \
+    } while (0)
+
+int digits_for_count(long long count)
+{
+    // a sum of `count` int8 values lies in [-128 count, 127 count]; d balanced base-256
+    // digits cover [-128 (256^d - 1)/255, 127 (256^d - 1)/255]  (Sec. 4.1)
+    int d = 1;
+    long long reach = 1;   // (256^d - 1) / 255
+    while (count > reach) { reach = reach * 256 + 1; ++d; }
+    return d;
+}
+
+struct Plan {
+    int P, Q, PQ, crs;
+    int n_eff, tp, tm_used, wm, wk, tile_k, grid_m, grid_n, d_f, d_i;
+    // workspace offsets in bytes (-1 = unused)
+    long long off_count, off_convout, off_yf, off_yi, off_yfi, off_rs, off_cs, ws_bytes;
+};
+
+long long align256(long long v) { return (v + 255) & ~255LL; }
+
+abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool int8_out, Plan &pl)
+{
+    if (!d) return ABED_EINVAL;
+    if (d->N < 1 || d->H < 1 || d->W < 1 || d->C < 1 || d->K < 1 || d->R < 1 || d->S < 1 ||
+        d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0)
+        return ABED_EINVAL;
+    if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return ABED_EINVAL;
+    if (variant < ABED_NONE || variant > ABED_DUPLICATE) return ABED_EINVAL;
+    if (dtype != ABED_INT8 && dtype != ABED_FP16) return ABED_EINVAL;
+    if (dtype == ABED_FP16) return ABED_EUNSUPPORTED;
+    const int elems16 = 16;   // elements per 16-byte chunk
+    if (d->C % elems16 != 0) return ABED_EUNSUPPORTED;
+    if (d->N > 256) return ABED_EUNSUPPORTED;
+    const long long crs = (long long)d->C * d->R * d->S;
+    if (crs > 65536) return ABED_EUNSUPPORTED;   // int32 accumulators are exact up to C*R*S = 64K (Sec. 4.1)
+    if ((long long)d->N * d->H * d->W * d->C >= (1LL << 31)) return ABED_EUNSUPPORTED;
+    pl.P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
+    pl.Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+    pl.PQ = pl.P * pl.Q;
+    pl.crs = (int)crs;
+    if ((long long)d->N * pl.PQ * d->K >= (1LL << 31)) return ABED_EUNSUPPORTED;
+    pl.d_f = digits_for_count(d->K);
+    pl.d_i = digits_for_count(d->N);
+    if (pl.d_f > 4 || pl.d_i > 4) return ABED_ERANGE;
+    if (pl.d_i > 2) return ABED_EUNSUPPORTED;
+
+    const bool checked = variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG;
+    int n_eff;
+    if (d->N < 16) { n_eff = 2; while (n_eff < d->N) n_eff *= 2; }
+    else n_eff = (d->N + 15) / 16 * 16;
+    pl.n_eff = n_eff;
+    int tp = 256 / n_eff;
+    if (checked && tp > 8) tp = 8;        // 16 checksum-row slots = 8 pixels x 2 digit images
+    if (tp > pl.PQ) tp = pl.PQ;           // never more pixel slots than pixels
+    if (tp < 1) tp = 1;
+    pl.tp = tp;
+    pl.tm_used = tp * n_eff;
+    pl.wm = pl.tm_used <= 64 ? 1 : (pl.tm_used <= 128 ? 2 : 4);
+    pl.wk = d->K <= 64 ? 4 : (d->K <= 128 ? 8 : 16);
+    pl.tile_k = 16 * pl.wk;
+    pl.grid_m = (pl.PQ + tp - 1) / tp;
+    pl.grid_n = (d->K + pl.tile_k - 1) / pl.tile_k;
+
+    // workspace
+    long long off = 0;
+    auto take = [&](long long bytes) { long long o = off; off = align256(off + bytes); return o; };
+    pl.off_count = take((long long)pl.grid_m * 4);
+    pl.off_convout = pl.off_yf = pl.off_yi = pl.off_yfi = pl.off_rs = pl.off_cs = -1;
+    const long long npqk = (long long)d->N * pl.PQ * d->K;
+    const int tm = 64 * pl.wm;
+    if (variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE) {
+        if (int8_out) pl.off_convout = take(npqk * 4);
+        pl.off_yf = take((long long)d->N * pl.PQ * pl.d_f * 4);
+        pl.off_yi = take((long long)pl.d_i * pl.PQ * d->K * 4);
+        pl.off_yfi = take((long long)pl.d_i * pl.PQ * pl.d_f * 4);
+    } else if (variant == ABED_FUSED_PARTIAL_REDUCTION || variant == ABED_FUSED_OCG || variant == ABED_FUSED_IOCG) {
+        pl.off_rs = take((long long)pl.grid_n * pl.grid_m * tm * 4);
+        pl.off_yf = take((long long)pl.grid_m * tm * 4);
+        pl.off_yfi = take((long long)pl.grid_m * (pl.grid_n + 1) * 8 * 4);
+        if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
+            pl.off_cs = take((long long)pl.grid_m * 8 * (d->K + 16) * 4);
+            pl.off_yi = take((long long)pl.grid_m * 8 * (d->K + 16) * 4);
+        }
+    }
+    pl.ws_bytes = off;
+    return ABED_OK;
+}
+
+void fill_params(ConvParams &cp, const abed_conv_desc_t *d, const Plan &pl)
+{
+    memset(&cp, 0, sizeof(cp));
+    cp.N = d->N; cp.H = d->H; cp.W = d->W; cp.C = d->C; cp.K = d->K; cp.R = d->R; cp.S = d->S;
+    cp.sh = d->stride_h; cp.sw = d->stride_w; cp.ph = d->pad_h; cp.pw = d->pad_w;
+    cp.P = pl.P; cp.Q = pl.Q; cp.crs = pl.crs; cp.nsteps = (pl.crs + 63) / 64;
+    cp.n_eff = pl.n_eff; cp.tp = pl.tp; cp.tm_used = pl.tm_used;
+    cp.d_f = pl.d_f; cp.d_i = pl.d_i; cp.grid_m = pl.grid_m; cp.grid_n = pl.grid_n;
+}
+
+// An unchecked convolution of arbitrary (small) operands with its own plan: used by the
+// unfused variant for the checksum convolutions.
+abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_t *w, int32_t *y, hipStream_t st)
+{
+    Plan pl;
+    abed_status_t s = make_plan(d, ABED_INT8, ABED_NONE, false, pl);
+    if (s != ABED_OK) return s;
+    if (d->K <= 16) { pl.wk = 1; pl.tile_k = 16; pl.grid_n = 1; }
+    ConvParams cp;
+    fill_params(cp, d, pl);
+    cp.x = x; cp.w = w; cp.y = y; cp.mode = MODE_PLAIN;
+    if (!launch_conv_i8(pl.wm, pl.wk, false, cp, pl.grid_m * pl.grid_n, st)) return ABED_EUNSUPPORTED;
+    LAUNCH_CHECK("conv_i8_kernel (checksum convolution)");
+    return ABED_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *abed_status_string(abed_status_t s)
+{
+    switch (s) {
+    case ABED_OK: return "ok";
+    case ABED_EINVAL: return "invalid argument";
+    case ABED_EUNSUPPORTED: return "unsupported shape or option";
+    case ABED_EWORKSPACE: return "workspace too small";
+    case ABED_EHIP: return "HIP error";
+    case ABED_ERANGE: return "checksum needs more than four digits";
+    }
+    return "unknown status";
+}
+
+const char *abed_last_hip_error(void) { return g_hip_error; }
+
+abed_status_t abed_get_layout(const abed_conv_desc_t *desc, int32_t dtype, int32_t variant, abed_layout_t *out)
+{
+    if (!out) return ABED_EINVAL;
+    Plan pl;
+    // the workspace is sized for the int8-output case, which needs the most
+    abed_status_t s = make_plan(desc, dtype, variant, true, pl);
+    if (s != ABED_OK) return s;
+    memset(out, 0, sizeof(*out));
+    out->tile_m = pl.tm_used;
+    out->tile_n = pl.tile_k;
+    out->tile_pixels = pl.tp;
+    out->n_padded = pl.n_eff;
+    out->grid_m = pl.grid_m;
+    out->grid_n = pl.grid_n;
+    out->d_f = pl.d_f;
+    out->d_i = pl.d_i;
+    out->n_flag_words = (long long)pl.grid_m * pl.grid_n;
+    out->workspace_bytes = pl.ws_bytes;
+    out->wchk_bytes = (long long)pl.d_f * pl.crs;
+    out->xchk_bytes = (long long)pl.d_i * desc->H * desc->W * desc->C;
+    out->xchk_next_bytes = (long long)pl.d_i * pl.PQ * desc->K;
+    return ABED_OK;
+}
+
+abed_status_t abed_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace) return workspace_bytes == 0 ? ABED_OK : ABED_EINVAL;
+    const long long words = (long long)(workspace_bytes / 4);
+    if (words == 0) return ABED_OK;
+    fill_u32_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>((uint32_t *)workspace, words, 0u);
+    LAUNCH_CHECK("fill_u32_kernel");
+    return ABED_OK;
+}
+
+abed_status_t abed_filter_prepare_int8(const abed_conv_desc_t *desc, const int8_t *w, int8_t *wchk, void *stream)
+{
+    Plan pl;
+    abed_status_t s = make_plan(desc, ABED_INT8, ABED_NONE, false, pl);
+    if (s != ABED_OK) return s;
+    if (!w || !wchk) return ABED_EINVAL;
+    filter_checksum_i8_kernel<<<dim3((pl.crs + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(w, wchk, desc->K, pl.crs, pl.d_f);
+    LAUNCH_CHECK("filter_checksum_i8_kernel");
+    return ABED_OK;
+}
+
+abed_status_t abed_input_checksum_int8(const abed_conv_desc_t *desc, const int8_t *x, int8_t *xchk, void *stream)
+{
+    Plan pl;
+    abed_status_t s = make_plan(desc, ABED_INT8, ABED_NONE, false, pl);
+    if (s != ABED_OK) return s;
+    if (!x || !xchk) return ABED_EINVAL;
+    const long long hwc = (long long)desc->H * desc->W * desc->C;
+    const long long chunks = hwc / 16;
+    batch_checksum_i8_kernel<<<dim3((unsigned)((chunks + 63) / 64)), dim3(256), 0, (hipStream_t)stream>>>(x, xchk, desc->N, hwc, pl.d_i);
+    LAUNCH_CHECK("batch_checksum_i8_kernel");
+    return ABED_OK;
+}
+
+abed_status_t abed_filter_prepare_fp16(const abed_conv_desc_t *, const void *, void *, void *) { return ABED_EUNSUPPORTED; }
+abed_status_t abed_input_checksum_fp16(const abed_conv_desc_t *, const void *, void *, void *) { return ABED_EUNSUPPORTED; }
+
+abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+                             const int8_t *wchk, int8_t *xchk, int32_t compute_xchk,
+                             void *y, const abed_epilogue_t *epi, int32_t variant,
+                             uint32_t *flags, int8_t *xchk_next,
+                             void *workspace, size_t workspace_bytes,
+                             const abed_inject_t *inject, void *y2, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const bool int8_out = epi != nullptr;
+    Plan pl;
+    abed_status_t s = make_plan(desc, ABED_INT8, variant, int8_out, pl);
+    if (s != ABED_OK) return s;
+    if (!x || !w || !y) return ABED_EINVAL;
+    if (int8_out && (!epi->scale || !epi->bias)) return ABED_EINVAL;
+    const bool checked = variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG;
+    if (checked && (!wchk || !xchk || !flags)) return ABED_EINVAL;
+    if (variant == ABED_DUPLICATE && (!y2 || !flags)) return ABED_EINVAL;
+    if (variant == ABED_FUSED_IOCG && int8_out && !xchk_next) return ABED_EINVAL;
+    if (pl.ws_bytes > 0 && checked && (!workspace || (long long)workspace_bytes < pl.ws_bytes)) return ABED_EWORKSPACE;
+    if (inject && inject->site != 0) {
+        if (inject->site != 1 && inject->site != 2) return ABED_EINVAL;
+        if (inject->index < 0 || inject->index >= (long long)desc->N * pl.PQ * desc->K || inject->bit < 0 || inject->bit > 31)
+            return ABED_EINVAL;
+        if (inject->site == 2 && !(variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE || (!int8_out))) return ABED_EUNSUPPORTED;
+    }
+    char *ws = (char *)workspace;
+    auto wsp = [&](long long off) { return off < 0 ? (int32_t *)nullptr : (int32_t *)(ws + off); };
+
+    ConvParams cp;
+    fill_params(cp, desc, pl);
+    cp.x = x; cp.w = w; cp.wchk = wchk; cp.xchk = xchk; cp.y = y;
+    cp.flags = flags; cp.xchk_next = xchk_next;
+    if (int8_out) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
+    if (inject && inject->site == 1) {
+        const long long k = inject->index % desc->K, row = inject->index / desc->K;   // row = n * PQ + pix
+        const long long n = row / pl.PQ, pix = row % pl.PQ;
+        cp.inj_on = 1;
+        cp.inj_row = (int)(pix * pl.n_eff + n);
+        cp.inj_k = (int)k;
+        cp.inj_mask = 1u << inject->bit;
+    }
+    const int grid = pl.grid_m * pl.grid_n;
+    const long long npqk = (long long)desc->N * pl.PQ * desc->K;
+    const bool stored_flip = inject && inject->site == 2;
+
+    if (checked && compute_xchk) {
+        s = abed_input_checksum_int8(desc, x, xchk, stream);
+        if (s != ABED_OK) return s;
+    }
+
+    switch (variant) {
+    case ABED_NONE:
+        cp.mode = MODE_PLAIN;
+        if (!launch_conv_i8(pl.wm, pl.wk, false, cp, grid, st)) return ABED_EUNSUPPORTED;
+        LAUNCH_CHECK("conv_i8_kernel");
+        if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)y, inject->index, 1u << inject->bit);
+        return ABED_OK;
+
+    case ABED_DUPLICATE: {
+        cp.mode = MODE_PLAIN;
+        fill_u32_kernel<<<1, 64, 0, st>>>(flags, 1, 0u);
+        if (!launch_conv_i8(pl.wm, pl.wk, false, cp, grid, st)) return ABED_EUNSUPPORTED;
+        ConvParams cp2 = cp;
+        cp2.y = y2;
+        cp2.inj_on = 0;
+        launch_conv_i8(pl.wm, pl.wk, false, cp2, grid, st);
+        LAUNCH_CHECK("conv_i8_kernel (duplicate)");
+        if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)y, inject->index, 1u << inject->bit);
+        const long long bytes = npqk * (int8_out ? 1 : 4);
+        compare_kernel<<<dim3((unsigned)((bytes / 16 + 256) / 256)), dim3(256), 0, st>>>(y, y2, bytes, flags);
+        LAUNCH_CHECK("compare_kernel");
+        return ABED_OK;
+    }
+
+    case ABED_UNFUSED:
+    case ABED_FUSED_WRITE: {
+        int32_t *convout = int8_out ? wsp(pl.off_convout) : (int32_t *)y;
+        int32_t *yf = wsp(pl.off_yf), *yi = wsp(pl.off_yi), *yfi = wsp(pl.off_yfi);
+        cp.y = convout;
+        cp.out_int8 = 0;
+        if (variant == ABED_UNFUSED) {
+            // one kernel per task (Sec. 4.3): the convolution, then the three checksum convolutions
+            cp.mode = MODE_PLAIN;
+            if (!launch_conv_i8(pl.wm, pl.wk, false, cp, grid, st)) return ABED_EUNSUPPORTED;
+            LAUNCH_CHECK("conv_i8_kernel");
+            abed_conv_desc_t df = *desc; df.K = pl.d_f;               // x * checksum filters
+            if ((s = plain_conv(&df, x, wchk, yf, st)) != ABED_OK) return s;
+            abed_conv_desc_t di = *desc; di.N = pl.d_i;               // checksum images * w
+            if ((s = plain_conv(&di, xchk, w, yi, st)) != ABED_OK) return s;
+            abed_conv_desc_t dfi = di; dfi.K = pl.d_f;                // checksum images * checksum filters
+            if ((s = plain_conv(&dfi, xchk, wchk, yfi, st)) != ABED_OK) return s;
+        } else {
+            cp.mode = MODE_WRITE;
+            cp.ws_yf = yf; cp.ws_yi = yi; cp.ws_yfi = yfi;
+            if (!launch_conv_i8(pl.wm, pl.wk, true, cp, grid, st)) return ABED_EUNSUPPORTED;
+            LAUNCH_CHECK("conv_i8_kernel (augmented, write)");
+        }
+        if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)convout, inject->index, 1u << inject->bit);
+        VerifyParams vp;
+        vp.y = convout; vp.yf = yf; vp.yi = yi; vp.yfi = yfi; vp.flags = flags;
+        vp.N = desc->N; vp.PQ = pl.PQ; vp.K = desc->K; vp.d_f = pl.d_f; vp.d_i = pl.d_i;
+        vp.tp = pl.tp; vp.tile_n = pl.tile_k; vp.grid_n = pl.grid_n;
+        const size_t shm = ((size_t)pl.tp * desc->K + pl.tp + pl.grid_n) * 4;
+        verify_i8_kernel<<<dim3(pl.grid_m), dim3(256), shm, st>>>(vp);
+        LAUNCH_CHECK("verify_i8_kernel");
+        if (int8_out) {
+            epilog_i8_kernel<<<dim3((unsigned)((npqk / 4 + 256) / 256)), dim3(256), 0, st>>>(convout, (int8_t *)y, epi->scale, epi->bias, epi->relu, npqk, desc->K);
+            LAUNCH_CHECK("epilog_i8_kernel");
+        }
+        return ABED_OK;
+    }
+
+    case ABED_FUSED_PARTIAL_REDUCTION:
+    case ABED_FUSED_OCG:
+    case ABED_FUSED_IOCG: {
+        cp.mode = variant == ABED_FUSED_PARTIAL_REDUCTION ? MODE_PARTIAL : (variant == ABED_FUSED_OCG ? MODE_CHECK : MODE_CHECK_NEXT);
+        cp.ws_count = (uint32_t *)wsp(pl.off_count);
+        cp.ws_rs = wsp(pl.off_rs); cp.ws_yf = wsp(pl.off_yf); cp.ws_yfi = wsp(pl.off_yfi);
+        cp.ws_cs = wsp(pl.off_cs); cp.ws_yi = wsp(pl.off_yi);
+        if (!launch_conv_i8(pl.wm, pl.wk, true, cp, grid, st)) return ABED_EUNSUPPORTED;
+        LAUNCH_CHECK("conv_i8_kernel (augmented)");
+        if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)y, inject->index, 1u << inject->bit);
+        if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
+            FinishParams fp;
+            fp.rs = cp.ws_rs; fp.yf = cp.ws_yf; fp.cs = cp.ws_cs; fp.yi = cp.ws_yi; fp.yfi = cp.ws_yfi; fp.flags = flags;
+            fp.K = desc->K; fp.tm = 64 * pl.wm; fp.tp = pl.tp; fp.tile_n = pl.tile_k; fp.grid_m = pl.grid_m; fp.grid_n = pl.grid_n; fp.d_f = pl.d_f;
+            finish_i8_kernel<<<dim3(pl.grid_m), dim3(256), (size_t)pl.grid_n * 4, st>>>(fp);
+            LAUNCH_CHECK("finish_i8_kernel");
+        }
+        return ABED_OK;
+    }
+    }
+    return ABED_EINVAL;
+}
+
+abed_status_t abed_conv_fp16(const abed_conv_desc_t *, const void *, const void *, const void *, void *, int32_t,
+                             void *, int32_t, int32_t, float, float, uint32_t *, void *, size_t,
+                             const abed_inject_t *, void *, void *)
+{
+    return ABED_EUNSUPPORTED;
+}
+
+}  // extern "C"

@@ -1,0 +1,76 @@
+"""Host-side tests of the C-ABI boundary that need no GPU: the library loads,
+exports every symbol include/abed.h declares, validates arguments and reports
+tile layouts consistently."""
+import os
+import re
+
+import pytest
+
+import paper_2006_04984_amd as abed
+from paper_2006_04984_amd import ConvDesc, Variant, AbedError
+from synth import CONFIG1, CONFIG2, CONFIG3, resnet50_layers
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(abed.lib_path()):
+        from paper_2006_04984_amd import build
+        build.build()
+    return abed.lib()
+
+
+def test_exports_match_header(L):
+    text = open(os.path.join(ROOT, "include", "abed.h")).read()
+    declared = set(re.findall(r"\b(abed_[a-z0-9_]+)\s*\(", text))
+    assert declared, "no declarations found"
+    for name in declared:
+        assert hasattr(L, name), name
+    from paper_2006_04984_amd.binding import EXPORTS
+    assert declared == set(EXPORTS)
+
+
+def test_status_strings(L):
+    for s in range(6):
+        assert L.abed_status_string(s)
+
+
+@pytest.mark.parametrize("bad", [dict(N=0), dict(C=-1), dict(stride_h=0), dict(pad_w=-1), dict(R=40)])
+def test_invalid_descriptor(L, bad):
+    d = abed.desc_from_shape(CONFIG1[0])
+    for k, v in bad.items():
+        setattr(d, k, v)
+    with pytest.raises(AbedError) as e:
+        abed.get_layout(d)
+    assert e.value.status == 1
+
+
+def test_unsupported_descriptor(L):
+    d = abed.desc_from_shape(CONFIG1[0])
+    d.C = 17
+    with pytest.raises(AbedError) as e:
+        abed.get_layout(d)
+    assert e.value.status == 2
+    d = abed.desc_from_shape(CONFIG1[0])
+    d.N = 300
+    with pytest.raises(AbedError) as e:
+        abed.get_layout(d)
+    assert e.value.status == 2
+
+
+@pytest.mark.parametrize("s", CONFIG1 + CONFIG2 + CONFIG3 + resnet50_layers(128)[1:], ids=lambda s: s.name)
+def test_layout_consistency(L, s):
+    d = abed.desc_from_shape(s)
+    for v in Variant:
+        lay = abed.get_layout(d, 0, v)
+        assert lay.tile_m == lay.tile_pixels * lay.n_padded
+        assert lay.n_padded >= s.N
+        assert lay.grid_m * lay.tile_pixels >= s.P * s.Q > (lay.grid_m - 1) * lay.tile_pixels
+        assert lay.grid_n * lay.tile_n >= s.K > (lay.grid_n - 1) * lay.tile_n
+        assert lay.n_flag_words == lay.grid_m * lay.grid_n
+        assert lay.d_f == (2 if s.K <= 257 else 3) and lay.d_i == (2 if s.N > 1 else 1)
+        assert lay.wchk_bytes == lay.d_f * s.R * s.S * s.C
+        assert lay.xchk_bytes == lay.d_i * s.H * s.W * s.C
+        if 1 <= v <= 5:
+            assert lay.tile_pixels <= 8
