@@ -95,30 +95,35 @@ typedef struct {
     int32_t bit;
 } abed_inject_t;
 
-/* What abed_get_layout reports for one (convolution, dtype, variant). */
+/* What abed_get_layout reports for one (convolution, dtype, variant).
+ * A tile is tile_pixels consecutive output pixels (pixel index p*Q + q) x tile_batch
+ * batch entries x tile_n filters.  For the checked variants the batch entries are
+ * the N images followed by the d_i checksum images, and the filters are the K
+ * filters (padded to a multiple of 16) followed by one block of 16 checksum filters. */
 typedef struct {
-    int32_t tile_m;        /* output rows (n,p,q) per tile = tile_pixels * n_padded          */
-    int32_t tile_n;        /* output channels per tile                                       */
-    int32_t tile_pixels;   /* output pixels per tile; a tile holds them for ALL images       */
-    int32_t n_padded;      /* batch size the kernel pads N to inside a tile                  */
+    int32_t tile_pixels;   /* 16                                                             */
+    int32_t tile_batch;    /* batch entries per tile                                         */
+    int32_t tile_n;        /* filters per tile (a multiple of 16)                            */
     int32_t grid_m;        /* ceil(P*Q / tile_pixels)                                        */
-    int32_t grid_n;        /* ceil(K / tile_n)                                               */
+    int32_t grid_b;        /* ceil(batch entries / tile_batch)                               */
+    int32_t grid_n;        /* ceil(filter blocks * 16 / tile_n)                              */
     int32_t d_f, d_i;      /* checksum tensors per filter / batch checksum                   */
-    int64_t n_flag_words;  /* grid_m * grid_n uint32 words                                   */
+    int64_t n_flag_words;  /* grid_m * grid_b * grid_n uint32 words                          */
     int64_t workspace_bytes;
     int64_t wchk_bytes;    /* d_f * R*S*C elements                                           */
     int64_t xchk_bytes;    /* d_i * H*W*C elements                                           */
     int64_t xchk_next_bytes; /* d_i * P*Q*K elements (variant 5)                             */
 } abed_layout_t;
 
-/* Flag word of tile (tm, tn) is flags[tm * grid_n + tn].  Tile tm covers output
- * pixels [tm*tile_pixels, (tm+1)*tile_pixels) (pixel index p*Q + q) of every
- * image; tile column tn covers channels [tn*tile_n, (tn+1)*tile_n).
- *   bit 0: FC mismatch (Sec. 3.1) in an output row (n,p,q) of tile-row tm
- *          (reported on tn = 0 when K spans several tile columns);
- *   bit 1: IC mismatch (Sec. 3.2 option 1) at a (p,q,k) of this tile;
- *   bit 2: corner mismatch at a pixel of tile-row tm: sum_n of the FC fmap or
- *          sum_k of the IC fmap differs from conv(xsum, wsum) (reported on tn = 0).
+/* Flag word of tile (tm, tb, tn) is flags[(tm * grid_b + tb) * grid_n + tn].
+ *   bit 0: FC mismatch (Sec. 3.1) in an output row (n,p,q): pixel in group tm, image n in
+ *          batch tile tb = n / tile_batch; reported on tn = 0;
+ *   bit 1: IC mismatch (Sec. 3.2 option 1) at a (p,q,k): pixel in group tm, channel k in
+ *          filter tile tn = k / tile_n; reported on tb = 0;
+ *   bit 2: the checksums disagree with each other at a pixel of group tm (the corner of
+ *          the row+column scheme: the filter-sum of a checksum-image fmap or the batch-sum
+ *          of a checksum-filter fmap differs from the fmap of checksum image x checksum
+ *          filter); reported on some word of group tm.
  * Every word is written on every checked call. */
 #define ABED_FLAG_FC 1u
 #define ABED_FLAG_IC 2u
@@ -162,7 +167,7 @@ abed_status_t abed_workspace_init(void *workspace, size_t workspace_bytes, void 
  *   y2          variant 6 only: second output buffer of the same size as y; flags[0]
  *               is set to 1 if the two runs differ.
  * Errors: ABED_EINVAL (null pointer that is needed, bad descriptor),
- * ABED_EUNSUPPORTED (C not a multiple of 16, N > 256, K or C*R*S beyond limits),
+ * ABED_EUNSUPPORTED (C not a multiple of 16, C*R*S > 65536, tensors of 2^31 elements or more),
  * ABED_EWORKSPACE, ABED_EHIP. */
 abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
                              const int8_t *wchk, int8_t *xchk, int32_t compute_xchk,

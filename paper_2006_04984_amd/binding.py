@@ -40,7 +40,7 @@ class _Inject(ctypes.Structure):
 
 class Layout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("tile_m", "tile_n", "tile_pixels", "n_padded", "grid_m", "grid_n", "d_f", "d_i")] + \
+                ("tile_pixels", "tile_batch", "tile_n", "grid_m", "grid_b", "grid_n", "d_f", "d_i")] + \
                [(n, ctypes.c_int64) for n in
                 ("n_flag_words", "workspace_bytes", "wchk_bytes", "xchk_bytes", "xchk_next_bytes")]
 

@@ -15,7 +15,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 
 UNITS = [("abed_api.hip", [], "abed_api.o"),
          ("conv_dispatch.hip", [], "conv_dispatch.o")] + \
-        [("conv_inst.hip", ["-DINST_WK=%d" % wk], "conv_wk%d.o" % wk) for wk in (1, 4, 8, 16)]
+        [("conv_inst.hip", ["-DINST_WK=%d" % wk], "conv_wk%d.o" % wk) for wk in (1, 4, 5, 8, 9)]
 
 
 def _compile(unit):

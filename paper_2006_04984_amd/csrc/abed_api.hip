@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "../../include/abed.h"
@@ -45,12 +46,49 @@ int digits_for_count(long long count)
 
 struct Plan {
     int P, Q, PQ, crs;
-    int n_eff, tp, tm_used, wm, wk, tile_k, grid_m, grid_n, d_f, d_i;
+    int d_f, d_i;
+    int n_entries, kblk, n_fblk;          // batch entries, real filter blocks, filter blocks incl. the digit block
+    int wm, wk, mb;                       // entries per wave, filter blocks per tile, entries per tile
+    int grid_m, grid_b, grid_n;
     // workspace offsets in bytes (-1 = unused)
-    long long off_count, off_convout, off_yf, off_yi, off_yfi, off_rs, off_cs, ws_bytes;
+    long long off_cnt_fc, off_cnt_ic, off_convout, off_yf, off_yi, off_yfi, off_fc, off_ic, off_nx, ws_bytes;
 };
 
 long long align256(long long v) { return (v + 255) & ~255LL; }
+
+int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+}
+
+// Tile shape: WK filter blocks x 4*WM batch entries x 16 pixels per workgroup.  Small problems
+// get small tiles so that the grid still covers the 256 compute units a few times over.
+void choose_tile(Plan &pl)
+{
+    const int pgs = (pl.PQ + 15) / 16;
+    int wk;
+    if (pl.n_fblk <= 1) wk = 1;
+    else if (pl.n_fblk <= 4) wk = 4;
+    else if (pl.n_fblk == 5) wk = 5;
+    else if (pl.n_fblk % 8 == 0 || pl.n_fblk <= 8) wk = 8;
+    else wk = 9;
+    const int nwm = (int)(sizeof(kWmList) / sizeof(kWmList[0]));
+    int wm = kWmList[0];
+    const long long want = 1024;          // workgroups to aim for
+    for (int i = nwm - 1; i >= 0; --i) {
+        const int cand = kWmList[i];
+        if (i > 0 && 4 * kWmList[i - 1] >= pl.n_entries) continue;   // a smaller tile already holds the whole batch
+        const long long wgs = (long long)pgs * ((pl.n_entries + 4 * cand - 1) / (4 * cand)) * ((pl.n_fblk + wk - 1) / wk);
+        if (wgs >= want || i == 0) { wm = cand; break; }
+    }
+    wm = env_int("ABED_TILE_WM", wm);
+    wk = env_int("ABED_TILE_WK", wk);
+    pl.wm = wm; pl.wk = wk; pl.mb = 4 * wm;
+    pl.grid_m = pgs;
+    pl.grid_b = (pl.n_entries + pl.mb - 1) / pl.mb;
+    pl.grid_n = (pl.n_fblk + wk - 1) / wk;
+}
 
 abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool int8_out, Plan &pl)
 {
@@ -62,11 +100,9 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     if (variant < ABED_NONE || variant > ABED_DUPLICATE) return ABED_EINVAL;
     if (dtype != ABED_INT8 && dtype != ABED_FP16) return ABED_EINVAL;
     if (dtype == ABED_FP16) return ABED_EUNSUPPORTED;
-    const int elems16 = 16;   // elements per 16-byte chunk
-    if (d->C % elems16 != 0) return ABED_EUNSUPPORTED;
-    if (d->N > 256) return ABED_EUNSUPPORTED;
+    if (d->C % 16 != 0) return ABED_EUNSUPPORTED;          // 16-byte chunks of one filter tap
     const long long crs = (long long)d->C * d->R * d->S;
-    if (crs > 65536) return ABED_EUNSUPPORTED;   // int32 accumulators are exact up to C*R*S = 64K (Sec. 4.1)
+    if (crs > 65536) return ABED_EUNSUPPORTED;             // int32 accumulators are exact up to C*R*S = 64K (Sec. 4.1)
     if ((long long)d->N * d->H * d->W * d->C >= (1LL << 31)) return ABED_EUNSUPPORTED;
     pl.P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
     pl.Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
@@ -76,45 +112,32 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     pl.d_f = digits_for_count(d->K);
     pl.d_i = digits_for_count(d->N);
     if (pl.d_f > 4 || pl.d_i > 4) return ABED_ERANGE;
-    if (pl.d_i > 2) return ABED_EUNSUPPORTED;
 
+    // Variants 1..5 report flags on the tile grid of the augmented problem (N + d_i batch
+    // entries, one extra filter block); the unchecked kernels get the plain problem's grid.
     const bool checked = variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG;
-    int n_eff;
-    if (d->N < 16) { n_eff = 2; while (n_eff < d->N) n_eff *= 2; }
-    else n_eff = (d->N + 15) / 16 * 16;
-    pl.n_eff = n_eff;
-    int tp = 256 / n_eff;
-    if (checked && tp > 8) tp = 8;        // 16 checksum-row slots = 8 pixels x 2 digit images
-    if (tp > pl.PQ) tp = pl.PQ;           // never more pixel slots than pixels
-    if (tp < 1) tp = 1;
-    pl.tp = tp;
-    pl.tm_used = tp * n_eff;
-    pl.wm = pl.tm_used <= 64 ? 1 : (pl.tm_used <= 128 ? 2 : 4);
-    pl.wk = d->K <= 64 ? 4 : (d->K <= 128 ? 8 : 16);
-    pl.tile_k = 16 * pl.wk;
-    pl.grid_m = (pl.PQ + tp - 1) / tp;
-    pl.grid_n = (d->K + pl.tile_k - 1) / pl.tile_k;
+    pl.kblk = (d->K + 15) / 16;
+    pl.n_entries = d->N + (checked ? pl.d_i : 0);
+    pl.n_fblk = pl.kblk + (checked ? 1 : 0);
+    choose_tile(pl);
 
-    // workspace
+    // workspace: the two counter arrays come first and must be zero before the first call
     long long off = 0;
     auto take = [&](long long bytes) { long long o = off; off = align256(off + bytes); return o; };
-    pl.off_count = take((long long)pl.grid_m * 4);
-    pl.off_convout = pl.off_yf = pl.off_yi = pl.off_yfi = pl.off_rs = pl.off_cs = -1;
+    pl.off_cnt_fc = take((long long)pl.grid_m * pl.grid_b * 4);
+    pl.off_cnt_ic = take((long long)pl.grid_m * pl.grid_n * 4);
+    pl.off_convout = pl.off_yf = pl.off_yi = pl.off_yfi = pl.off_fc = pl.off_ic = pl.off_nx = -1;
     const long long npqk = (long long)d->N * pl.PQ * d->K;
-    const int tm = 64 * pl.wm;
     if (variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE) {
         if (int8_out) pl.off_convout = take(npqk * 4);
         pl.off_yf = take((long long)d->N * pl.PQ * pl.d_f * 4);
         pl.off_yi = take((long long)pl.d_i * pl.PQ * d->K * 4);
         pl.off_yfi = take((long long)pl.d_i * pl.PQ * pl.d_f * 4);
     } else if (variant == ABED_FUSED_PARTIAL_REDUCTION || variant == ABED_FUSED_OCG || variant == ABED_FUSED_IOCG) {
-        pl.off_rs = take((long long)pl.grid_n * pl.grid_m * tm * 4);
-        pl.off_yf = take((long long)pl.grid_m * tm * 4);
-        pl.off_yfi = take((long long)pl.grid_m * (pl.grid_n + 1) * 8 * 4);
-        if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
-            pl.off_cs = take((long long)pl.grid_m * 8 * (d->K + 16) * 4);
-            pl.off_yi = take((long long)pl.grid_m * 8 * (d->K + 16) * 4);
-        }
+        const long long tiles = (long long)pl.grid_m * pl.grid_b * pl.grid_n;
+        pl.off_fc = take(tiles * pl.mb * 16 * 4);
+        pl.off_ic = take(tiles * pl.wk * 256 * 4);
+        if (variant == ABED_FUSED_IOCG) pl.off_nx = take(tiles * pl.wk * 256 * 4);
     }
     pl.ws_bytes = off;
     return ABED_OK;
@@ -126,23 +149,39 @@ void fill_params(ConvParams &cp, const abed_conv_desc_t *d, const Plan &pl)
     cp.N = d->N; cp.H = d->H; cp.W = d->W; cp.C = d->C; cp.K = d->K; cp.R = d->R; cp.S = d->S;
     cp.sh = d->stride_h; cp.sw = d->stride_w; cp.ph = d->pad_h; cp.pw = d->pad_w;
     cp.P = pl.P; cp.Q = pl.Q; cp.crs = pl.crs; cp.nsteps = (pl.crs + 63) / 64;
-    cp.n_eff = pl.n_eff; cp.tp = pl.tp; cp.tm_used = pl.tm_used;
-    cp.d_f = pl.d_f; cp.d_i = pl.d_i; cp.grid_m = pl.grid_m; cp.grid_n = pl.grid_n;
+    cp.n_entries = pl.n_entries; cp.n_fblk = pl.n_fblk; cp.kblk = pl.kblk;
+    cp.d_f = pl.d_f; cp.d_i = pl.d_i;
+    cp.grid_m = pl.grid_m; cp.grid_b = pl.grid_b; cp.grid_n = pl.grid_n;
 }
 
-// An unchecked convolution of arbitrary (small) operands with its own plan: used by the
-// unfused variant for the checksum convolutions.
-abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_t *w, int32_t *y, hipStream_t st)
+void set_injection(ConvParams &cp, const abed_conv_desc_t *d, const Plan &pl, const abed_inject_t *inject)
+{
+    if (!inject || inject->site != 1) return;
+    const long long k = inject->index % d->K, row = inject->index / d->K;   // row = n * PQ + pix
+    const long long n = row / pl.PQ, pix = row % pl.PQ;
+    const int fb = (int)(k / 16), i = (int)(k % 16);
+    cp.inj_on = 1;
+    cp.inj_pg = (int)(pix / 16); cp.inj_nt = (int)(n / pl.mb); cp.inj_mb = (int)(n % pl.mb);
+    cp.inj_kt = fb / pl.wk; cp.inj_kb = fb % pl.wk;
+    cp.inj_lane = (i / 4) * 16 + (int)(pix % 16); cp.inj_v = i % 4;
+    cp.inj_mask = 1u << inject->bit;
+}
+
+// An unchecked convolution with its own tile plan (the baseline, and the checksum
+// convolutions of the unfused variant).
+abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_t *w, void *y,
+                         const abed_epilogue_t *epi, const abed_inject_t *inject, hipStream_t st)
 {
     Plan pl;
     abed_status_t s = make_plan(d, ABED_INT8, ABED_NONE, false, pl);
     if (s != ABED_OK) return s;
-    if (d->K <= 16) { pl.wk = 1; pl.tile_k = 16; pl.grid_n = 1; }
     ConvParams cp;
     fill_params(cp, d, pl);
     cp.x = x; cp.w = w; cp.y = y; cp.mode = MODE_PLAIN;
-    if (!launch_conv_i8(pl.wm, pl.wk, false, cp, pl.grid_m * pl.grid_n, st)) return ABED_EUNSUPPORTED;
-    LAUNCH_CHECK("conv_i8_kernel (checksum convolution)");
+    if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
+    set_injection(cp, d, pl, inject);
+    if (!launch_conv_i8(pl.wm, pl.wk, cp, pl.grid_m * pl.grid_b * pl.grid_n, st)) return ABED_EUNSUPPORTED;
+    LAUNCH_CHECK("conv_i8_kernel (unchecked)");
     return ABED_OK;
 }
 
@@ -173,15 +212,15 @@ abed_status_t abed_get_layout(const abed_conv_desc_t *desc, int32_t dtype, int32
     abed_status_t s = make_plan(desc, dtype, variant, true, pl);
     if (s != ABED_OK) return s;
     memset(out, 0, sizeof(*out));
-    out->tile_m = pl.tm_used;
-    out->tile_n = pl.tile_k;
-    out->tile_pixels = pl.tp;
-    out->n_padded = pl.n_eff;
+    out->tile_pixels = 16;
+    out->tile_batch = pl.mb;
+    out->tile_n = 16 * pl.wk;
     out->grid_m = pl.grid_m;
+    out->grid_b = pl.grid_b;
     out->grid_n = pl.grid_n;
     out->d_f = pl.d_f;
     out->d_i = pl.d_i;
-    out->n_flag_words = (long long)pl.grid_m * pl.grid_n;
+    out->n_flag_words = (long long)pl.grid_m * pl.grid_b * pl.grid_n;
     out->workspace_bytes = pl.ws_bytes;
     out->wchk_bytes = (long long)pl.d_f * pl.crs;
     out->xchk_bytes = (long long)pl.d_i * desc->H * desc->W * desc->C;
@@ -244,30 +283,15 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     if (checked && (!wchk || !xchk || !flags)) return ABED_EINVAL;
     if (variant == ABED_DUPLICATE && (!y2 || !flags)) return ABED_EINVAL;
     if (variant == ABED_FUSED_IOCG && int8_out && !xchk_next) return ABED_EINVAL;
-    if (pl.ws_bytes > 0 && checked && (!workspace || (long long)workspace_bytes < pl.ws_bytes)) return ABED_EWORKSPACE;
+    if (checked && (!workspace || (long long)workspace_bytes < pl.ws_bytes)) return ABED_EWORKSPACE;
     if (inject && inject->site != 0) {
         if (inject->site != 1 && inject->site != 2) return ABED_EINVAL;
         if (inject->index < 0 || inject->index >= (long long)desc->N * pl.PQ * desc->K || inject->bit < 0 || inject->bit > 31)
             return ABED_EINVAL;
-        if (inject->site == 2 && !(variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE || (!int8_out))) return ABED_EUNSUPPORTED;
+        if (inject->site == 2 && int8_out && !(variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE)) return ABED_EUNSUPPORTED;
     }
     char *ws = (char *)workspace;
     auto wsp = [&](long long off) { return off < 0 ? (int32_t *)nullptr : (int32_t *)(ws + off); };
-
-    ConvParams cp;
-    fill_params(cp, desc, pl);
-    cp.x = x; cp.w = w; cp.wchk = wchk; cp.xchk = xchk; cp.y = y;
-    cp.flags = flags; cp.xchk_next = xchk_next;
-    if (int8_out) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
-    if (inject && inject->site == 1) {
-        const long long k = inject->index % desc->K, row = inject->index / desc->K;   // row = n * PQ + pix
-        const long long n = row / pl.PQ, pix = row % pl.PQ;
-        cp.inj_on = 1;
-        cp.inj_row = (int)(pix * pl.n_eff + n);
-        cp.inj_k = (int)k;
-        cp.inj_mask = 1u << inject->bit;
-    }
-    const int grid = pl.grid_m * pl.grid_n;
     const long long npqk = (long long)desc->N * pl.PQ * desc->K;
     const bool stored_flip = inject && inject->site == 2;
 
@@ -276,23 +300,15 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
         if (s != ABED_OK) return s;
     }
 
-    switch (variant) {
-    case ABED_NONE:
-        cp.mode = MODE_PLAIN;
-        if (!launch_conv_i8(pl.wm, pl.wk, false, cp, grid, st)) return ABED_EUNSUPPORTED;
-        LAUNCH_CHECK("conv_i8_kernel");
+    if (variant == ABED_NONE) {
+        if ((s = plain_conv(desc, x, w, y, epi, inject, st)) != ABED_OK) return s;
         if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)y, inject->index, 1u << inject->bit);
         return ABED_OK;
-
-    case ABED_DUPLICATE: {
-        cp.mode = MODE_PLAIN;
+    }
+    if (variant == ABED_DUPLICATE) {
         fill_u32_kernel<<<1, 64, 0, st>>>(flags, 1, 0u);
-        if (!launch_conv_i8(pl.wm, pl.wk, false, cp, grid, st)) return ABED_EUNSUPPORTED;
-        ConvParams cp2 = cp;
-        cp2.y = y2;
-        cp2.inj_on = 0;
-        launch_conv_i8(pl.wm, pl.wk, false, cp2, grid, st);
-        LAUNCH_CHECK("conv_i8_kernel (duplicate)");
+        if ((s = plain_conv(desc, x, w, y, epi, inject, st)) != ABED_OK) return s;
+        if ((s = plain_conv(desc, x, w, y2, epi, nullptr, st)) != ABED_OK) return s;
         if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)y, inject->index, 1u << inject->bit);
         const long long bytes = npqk * (int8_out ? 1 : 4);
         compare_kernel<<<dim3((unsigned)((bytes / 16 + 256) / 256)), dim3(256), 0, st>>>(y, y2, bytes, flags);
@@ -300,35 +316,46 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
         return ABED_OK;
     }
 
-    case ABED_UNFUSED:
-    case ABED_FUSED_WRITE: {
+    ConvParams cp;
+    fill_params(cp, desc, pl);
+    cp.x = x; cp.w = w; cp.wchk = wchk; cp.xchk = xchk; cp.y = y;
+    cp.flags = flags; cp.xchk_next = xchk_next;
+    if (int8_out) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
+    set_injection(cp, desc, pl, inject);
+    const int grid = pl.grid_m * pl.grid_b * pl.grid_n;
+
+    if (variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE) {
         int32_t *convout = int8_out ? wsp(pl.off_convout) : (int32_t *)y;
         int32_t *yf = wsp(pl.off_yf), *yi = wsp(pl.off_yi), *yfi = wsp(pl.off_yfi);
-        cp.y = convout;
-        cp.out_int8 = 0;
         if (variant == ABED_UNFUSED) {
             // one kernel per task (Sec. 4.3): the convolution, then the three checksum convolutions
-            cp.mode = MODE_PLAIN;
-            if (!launch_conv_i8(pl.wm, pl.wk, false, cp, grid, st)) return ABED_EUNSUPPORTED;
-            LAUNCH_CHECK("conv_i8_kernel");
+            if ((s = plain_conv(desc, x, w, convout, nullptr, inject, st)) != ABED_OK) return s;
             abed_conv_desc_t df = *desc; df.K = pl.d_f;               // x * checksum filters
-            if ((s = plain_conv(&df, x, wchk, yf, st)) != ABED_OK) return s;
+            if ((s = plain_conv(&df, x, wchk, yf, nullptr, nullptr, st)) != ABED_OK) return s;
             abed_conv_desc_t di = *desc; di.N = pl.d_i;               // checksum images * w
-            if ((s = plain_conv(&di, xchk, w, yi, st)) != ABED_OK) return s;
+            if ((s = plain_conv(&di, xchk, w, yi, nullptr, nullptr, st)) != ABED_OK) return s;
             abed_conv_desc_t dfi = di; dfi.K = pl.d_f;                // checksum images * checksum filters
-            if ((s = plain_conv(&dfi, xchk, wchk, yfi, st)) != ABED_OK) return s;
+            if ((s = plain_conv(&dfi, xchk, wchk, yfi, nullptr, nullptr, st)) != ABED_OK) return s;
         } else {
+            cp.y = convout;
+            cp.out_int8 = 0;
             cp.mode = MODE_WRITE;
             cp.ws_yf = yf; cp.ws_yi = yi; cp.ws_yfi = yfi;
-            if (!launch_conv_i8(pl.wm, pl.wk, true, cp, grid, st)) return ABED_EUNSUPPORTED;
+            if (!launch_conv_i8(pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
             LAUNCH_CHECK("conv_i8_kernel (augmented, write)");
         }
         if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)convout, inject->index, 1u << inject->bit);
         VerifyParams vp;
         vp.y = convout; vp.yf = yf; vp.yi = yi; vp.yfi = yfi; vp.flags = flags;
         vp.N = desc->N; vp.PQ = pl.PQ; vp.K = desc->K; vp.d_f = pl.d_f; vp.d_i = pl.d_i;
-        vp.tp = pl.tp; vp.tile_n = pl.tile_k; vp.grid_n = pl.grid_n;
-        const size_t shm = ((size_t)pl.tp * desc->K + pl.tp + pl.grid_n) * 4;
+        vp.tile_batch = pl.mb; vp.tile_n = 16 * pl.wk; vp.grid_b = pl.grid_b; vp.grid_n = pl.grid_n;
+        const size_t shm = ((size_t)16 * desc->K + 16 + (size_t)pl.grid_b * pl.grid_n) * 4;
+        if (shm > 160 * 1024) return ABED_EUNSUPPORTED;
+        static bool attr_set = false;
+        if (!attr_set) {
+            HIP_TRY(hipFuncSetAttribute((const void *)verify_i8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+            attr_set = true;
+        }
         verify_i8_kernel<<<dim3(pl.grid_m), dim3(256), shm, st>>>(vp);
         LAUNCH_CHECK("verify_i8_kernel");
         if (int8_out) {
@@ -338,27 +365,22 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
         return ABED_OK;
     }
 
-    case ABED_FUSED_PARTIAL_REDUCTION:
-    case ABED_FUSED_OCG:
-    case ABED_FUSED_IOCG: {
-        cp.mode = variant == ABED_FUSED_PARTIAL_REDUCTION ? MODE_PARTIAL : (variant == ABED_FUSED_OCG ? MODE_CHECK : MODE_CHECK_NEXT);
-        cp.ws_count = (uint32_t *)wsp(pl.off_count);
-        cp.ws_rs = wsp(pl.off_rs); cp.ws_yf = wsp(pl.off_yf); cp.ws_yfi = wsp(pl.off_yfi);
-        cp.ws_cs = wsp(pl.off_cs); cp.ws_yi = wsp(pl.off_yi);
-        if (!launch_conv_i8(pl.wm, pl.wk, true, cp, grid, st)) return ABED_EUNSUPPORTED;
-        LAUNCH_CHECK("conv_i8_kernel (augmented)");
-        if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)y, inject->index, 1u << inject->bit);
-        if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
-            FinishParams fp;
-            fp.rs = cp.ws_rs; fp.yf = cp.ws_yf; fp.cs = cp.ws_cs; fp.yi = cp.ws_yi; fp.yfi = cp.ws_yfi; fp.flags = flags;
-            fp.K = desc->K; fp.tm = 64 * pl.wm; fp.tp = pl.tp; fp.tile_n = pl.tile_k; fp.grid_m = pl.grid_m; fp.grid_n = pl.grid_n; fp.d_f = pl.d_f;
-            finish_i8_kernel<<<dim3(pl.grid_m), dim3(256), (size_t)pl.grid_n * 4, st>>>(fp);
-            LAUNCH_CHECK("finish_i8_kernel");
-        }
-        return ABED_OK;
+    // variants 3, 4, 5
+    cp.mode = variant == ABED_FUSED_PARTIAL_REDUCTION ? MODE_PARTIAL : (variant == ABED_FUSED_OCG ? MODE_CHECK : MODE_CHECK_NEXT);
+    cp.cnt_fc = (uint32_t *)wsp(pl.off_cnt_fc);
+    cp.cnt_ic = (uint32_t *)wsp(pl.off_cnt_ic);
+    cp.ws_fc = wsp(pl.off_fc); cp.ws_ic = wsp(pl.off_ic); cp.ws_nx = wsp(pl.off_nx);
+    if (!launch_conv_i8(pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
+    LAUNCH_CHECK("conv_i8_kernel (augmented)");
+    if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)y, inject->index, 1u << inject->bit);
+    if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
+        FinishParams fp;
+        fp.fc = cp.ws_fc; fp.ic = cp.ws_ic; fp.flags = flags;
+        fp.N = desc->N; fp.kblk = pl.kblk; fp.tile_batch = pl.mb; fp.wk = pl.wk; fp.grid_b = pl.grid_b; fp.grid_n = pl.grid_n;
+        finish_i8_kernel<<<dim3(pl.grid_m), dim3(256), (size_t)pl.grid_b * pl.grid_n * 4, st>>>(fp);
+        LAUNCH_CHECK("finish_i8_kernel");
     }
-    }
-    return ABED_EINVAL;
+    return ABED_OK;
 }
 
 abed_status_t abed_conv_fp16(const abed_conv_desc_t *, const void *, const void *, const void *, void *, int32_t,

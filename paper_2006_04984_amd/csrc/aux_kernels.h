@@ -77,27 +77,30 @@ struct VerifyParams {
     const int32_t *yf;    // [N][PQ][d_f]   digit fmaps of the checksum filters
     const int32_t *yi;    // [d_i][PQ][K]   digit fmaps of the checksum images
     const int32_t *yfi;   // [d_i][PQ][d_f]
-    uint32_t *flags;
-    int N, PQ, K, d_f, d_i, tp, tile_n, grid_n;
+    uint32_t *flags;      // [grid_m][grid_b][grid_n]
+    int N, PQ, K, d_f, d_i, tile_batch, tile_n, grid_b, grid_n;
 };
 
 // Variants that verify from memory (Sec. 4.3, unfused option): read ConvOut back,
 // reduce over filters and over the batch, compare with the checksum fmaps.
-// One workgroup per tile-row (tp pixels, all images, all filters).
+// One workgroup per group of 16 pixels (all images, all filters).
+// Bit 0 goes to word (batch tile of the image, 0), bit 1 to word (0, filter tile of the
+// channel), bit 2 to word (0, 0) of the pixel group.
 __global__ __launch_bounds__(256) void verify_i8_kernel(const VerifyParams p)
 {
     extern __shared__ int vs[];
-    int *cs = vs;                       // [tp][K]   sum over images
-    int *syf = cs + p.tp * p.K;         // [tp]      sum over images of the FC fmap
-    int *fl = syf + p.tp;               // [grid_n]
+    int *cs = vs;                       // [16][K]   sum over images
+    int *syf = cs + 16 * p.K;           // [16]      sum over images of the FC fmap
+    int *fl = syf + 16;                 // [grid_b][grid_n]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int mt = blockIdx.x;
-    for (int i = tid; i < p.tp * p.K + p.tp + p.grid_n; i += 256) vs[i] = 0;
+    const int pg = blockIdx.x;
+    const int nwords = p.grid_b * p.grid_n;
+    for (int i = tid; i < 16 * p.K + 16 + nwords; i += 256) vs[i] = 0;
     __syncthreads();
-    const int rows = p.tp * p.N;
+    const int rows = 16 * p.N;
     for (int r = wave; r < rows; r += 4) {
-        const int t = r / p.N, n = r - t * p.N;
-        const int pix = mt * p.tp + t;
+        const int n = r >> 4, t = r & 15;
+        const int pix = pg * 16 + t;
         if (pix >= p.PQ) continue;
         const int32_t *row = p.y + ((long long)n * p.PQ + pix) * p.K;
         unsigned s = 0;
@@ -110,22 +113,22 @@ __global__ __launch_bounds__(256) void verify_i8_kernel(const VerifyParams p)
         if (lane == 0) {
             unsigned c = 0;
             for (int d = 0; d < p.d_f; ++d) c += (unsigned)p.yf[((long long)n * p.PQ + pix) * p.d_f + d] << (8 * d);
-            if (s != c) atomicOr(reinterpret_cast<unsigned *>(&fl[0]), 1u);
+            if (s != c) atomicOr(reinterpret_cast<unsigned *>(&fl[(n / p.tile_batch) * p.grid_n]), 1u);
             atomicAdd(&syf[t], (int)c);
         }
     }
     __syncthreads();
-    for (int i = tid; i < p.tp * p.K; i += 256) {
+    for (int i = tid; i < 16 * p.K; i += 256) {
         const int t = i / p.K, k = i - t * p.K;
-        const int pix = mt * p.tp + t;
+        const int pix = pg * 16 + t;
         if (pix >= p.PQ) continue;
         unsigned c = 0;
         for (int j = 0; j < p.d_i; ++j) c += (unsigned)p.yi[((long long)j * p.PQ + pix) * p.K + k] << (8 * j);
         if ((unsigned)cs[i] != c) atomicOr(reinterpret_cast<unsigned *>(&fl[k / p.tile_n]), 2u);
     }
     // corner: sum_n yf and sum_k yi against conv(xsum, wsum)
-    for (int t = wave; t < p.tp; t += 4) {
-        const int pix = mt * p.tp + t;
+    for (int t = wave; t < 16; t += 4) {
+        const int pix = pg * 16 + t;
         if (pix >= p.PQ) continue;
         unsigned sk = 0;
         for (int k = lane; k < p.K; k += 64)
@@ -139,52 +142,39 @@ __global__ __launch_bounds__(256) void verify_i8_kernel(const VerifyParams p)
         }
     }
     __syncthreads();
-    for (int i = tid; i < p.grid_n; i += 256) p.flags[(long long)mt * p.grid_n + i] = (uint32_t)fl[i];
+    for (int i = tid; i < nwords; i += 256) p.flags[(long long)pg * nwords + i] = (uint32_t)fl[i];
 }
 
 struct FinishParams {
-    const int32_t *rs;    // [grid_n][grid_m][tm]
-    const int32_t *yf;    // [grid_m][tm]
-    const int32_t *cs;    // [grid_m][8][K + 16]
-    const int32_t *yi;    // [grid_m][8][K + 16]
-    const int32_t *yfi;   // [grid_m][grid_n + 1][8]
-    uint32_t *flags;
-    int K, tm, tp, tile_n, grid_m, grid_n, d_f;
+    const int32_t *fc;    // FC residual partials [grid_m][grid_b][grid_n][mb16]
+    const int32_t *ic;    // IC residual partials [grid_m][grid_n][grid_b][wk256]
+    uint32_t *flags;      // [grid_m][grid_b][grid_n]
+    int N, kblk, tile_batch, wk, grid_b, grid_n;
 };
 
-// Partial-reduction variant: sum the per-tile partial sums across tile columns and compare.
+// Partial-reduction variant: add the per-tile residuals across tiles and test for zero.
+// One workgroup per pixel group.
 __global__ __launch_bounds__(256) void finish_i8_kernel(const FinishParams p)
 {
-    extern __shared__ int fs[];   // [grid_n]
-    const int tid = threadIdx.x, mt = blockIdx.x;
-    for (int i = tid; i < p.grid_n; i += 256) fs[i] = 0;
+    extern __shared__ int fs[];   // [grid_b][grid_n]
+    const int tid = threadIdx.x, pg = blockIdx.x;
+    const int nwords = p.grid_b * p.grid_n, mb16 = p.tile_batch * 16, wk256 = p.wk * 256;
+    for (int i = tid; i < nwords; i += 256) fs[i] = 0;
     __syncthreads();
-    for (int r = tid; r < p.tm; r += 256) {
+    for (int i = tid; i < p.grid_b * mb16; i += 256) {
+        const int nt = i / mb16, r = i - nt * mb16;
         unsigned s = 0;
-        for (int kt = 0; kt < p.grid_n; ++kt) s += (unsigned)p.rs[((long long)kt * p.grid_m + mt) * p.tm + r];
-        if (s != (unsigned)p.yf[(long long)mt * p.tm + r]) atomicOr(reinterpret_cast<unsigned *>(&fs[0]), 1u);
+        for (int kt = 0; kt < p.grid_n; ++kt) s += (unsigned)p.fc[(((long long)pg * p.grid_b + nt) * p.grid_n + kt) * mb16 + r];
+        if (s != 0) atomicOr(reinterpret_cast<unsigned *>(&fs[nt * p.grid_n]), (nt * p.tile_batch + (r >> 4) < p.N) ? 1u : 4u);
     }
-    const int KA = p.K + 16;
-    for (int i = tid; i < p.tp * p.K; i += 256) {
-        const int t = i / p.K, k = i - t * p.K;
-        const long long o = ((long long)mt * 8 + t) * KA + k;
-        if (p.cs[o] != p.yi[o]) atomicOr(reinterpret_cast<unsigned *>(&fs[k / p.tile_n]), 2u);
-    }
-    if (tid < p.tp) {
-        const int t = tid;
+    for (int i = tid; i < p.grid_n * wk256; i += 256) {
+        const int kt = i / wk256, r = i - kt * wk256;
         unsigned s = 0;
-        for (int kt = 0; kt < p.grid_n; ++kt) s += (unsigned)p.yfi[((long long)mt * (p.grid_n + 1) + kt) * 8 + t];
-        const unsigned yfi = (unsigned)p.yfi[((long long)mt * (p.grid_n + 1) + p.grid_n) * 8 + t];
-        unsigned a = 0, b = 0;
-        for (int d = 0; d < 4; ++d) {
-            const long long o = ((long long)mt * 8 + t) * KA + p.K + d;
-            a += (unsigned)p.cs[o] << (8 * d);
-            b += (unsigned)p.yi[o] << (8 * d);
-        }
-        if (s != yfi || a != b) atomicOr(reinterpret_cast<unsigned *>(&fs[0]), 4u);
+        for (int nt = 0; nt < p.grid_b; ++nt) s += (unsigned)p.ic[(((long long)pg * p.grid_n + kt) * p.grid_b + nt) * wk256 + r];
+        if (s != 0) atomicOr(reinterpret_cast<unsigned *>(&fs[kt]), (kt * p.wk + (r >> 8) < p.kblk) ? 2u : 4u);
     }
     __syncthreads();
-    for (int i = tid; i < p.grid_n; i += 256) p.flags[(long long)mt * p.grid_n + i] = (uint32_t)fs[i];
+    for (int i = tid; i < nwords; i += 256) p.flags[(long long)pg * nwords + i] = (uint32_t)fs[i];
 }
 
 // Separate epilog (Sec. 4.3): ConvOut int32 -> int8, 4 elements per thread.

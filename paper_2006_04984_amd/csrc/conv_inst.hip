@@ -1,4 +1,4 @@
-// One translation unit per filter-block count WK (set with -DINST_WK=1|4|8|16).
+// One translation unit per filter-block count WK (set with -DINST_WK=<n>).
 #include "conv_launch.h"
 
 #ifndef INST_WK
@@ -10,30 +10,20 @@
 
 namespace abed {
 
-template <int WM, bool AUG>
+template <int WM>
 static void go(const ConvParams &p, int grid, hipStream_t st)
 {
-    conv_i8_kernel<WM, INST_WK, AUG><<<dim3(grid), dim3(256), 0, st>>>(p);
+    conv_i8_kernel<WM, INST_WK, kStages><<<dim3(grid), dim3(256), 0, st>>>(p);
 }
 
-bool CAT(launch_conv_i8_wk, INST_WK)(int wm, bool aug, const ConvParams &p, int grid, hipStream_t st)
+bool CAT(launch_conv_i8_wk, INST_WK)(int wm, const ConvParams &p, int grid, hipStream_t st)
 {
-#if INST_WK >= 4
-    if (aug) {
-        switch (wm) {
-        case 1: go<1, true>(p, grid, st); return true;
-        case 2: go<2, true>(p, grid, st); return true;
-        case 4: go<4, true>(p, grid, st); return true;
-        }
-        return false;
-    }
-#else
-    if (aug) return false;
-#endif
     switch (wm) {
-    case 1: go<1, false>(p, grid, st); return true;
-    case 2: go<2, false>(p, grid, st); return true;
-    case 4: go<4, false>(p, grid, st); return true;
+    case 1: go<1>(p, grid, st); return true;
+    case 2: go<2>(p, grid, st); return true;
+    case 3: go<3>(p, grid, st); return true;
+    case 5: go<5>(p, grid, st); return true;
+    case 9: go<9>(p, grid, st); return true;
     }
     return false;
 }

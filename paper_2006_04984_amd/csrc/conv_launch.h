@@ -1,5 +1,5 @@
 // Dispatch from a run-time tile plan to the compiled instantiations of the
-// convolution kernel.  Each filter-block count is compiled in its own
+// convolution kernel.  Each filter-block count WK is compiled in its own
 // translation unit (conv_inst.hip with -DINST_WK=<n>) so the build runs in parallel.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -7,12 +7,18 @@
 
 namespace abed {
 
-// Returns false if (wm, wk, aug) is not a compiled configuration.
-bool launch_conv_i8(int wm, int wk, bool aug, const ConvParams &p, int grid, hipStream_t st);
+// compiled tile shapes: WM (batch entries per wave), WK (filter blocks per tile)
+static const int kWmList[] = {1, 2, 3, 5, 9};
+static const int kWkList[] = {1, 4, 5, 8, 9};
+constexpr int kStages = 3;
 
-bool launch_conv_i8_wk1(int wm, bool aug, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_i8_wk4(int wm, bool aug, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_i8_wk8(int wm, bool aug, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_i8_wk16(int wm, bool aug, const ConvParams &p, int grid, hipStream_t st);
+// Returns false if (wm, wk) is not a compiled configuration.
+bool launch_conv_i8(int wm, int wk, const ConvParams &p, int grid, hipStream_t st);
+
+bool launch_conv_i8_wk1(int wm, const ConvParams &p, int grid, hipStream_t st);
+bool launch_conv_i8_wk4(int wm, const ConvParams &p, int grid, hipStream_t st);
+bool launch_conv_i8_wk5(int wm, const ConvParams &p, int grid, hipStream_t st);
+bool launch_conv_i8_wk8(int wm, const ConvParams &p, int grid, hipStream_t st);
+bool launch_conv_i8_wk9(int wm, const ConvParams &p, int grid, hipStream_t st);
 
 }  // namespace abed

@@ -45,25 +45,32 @@ class GpuConv:
                        flags=self.flags, epilogue=epi, xchk_next=self.xchk_next if epi is not None else None,
                        workspace=self.ws, inject=inject, y2=self.y2)
         torch.cuda.synchronize()
-        return self.y.cpu().numpy(), self.flags.cpu().numpy().view(np.uint32)[: self.lay.n_flag_words].reshape(
-            max(1, self.lay.grid_m), -1) if self.lay.n_flag_words else None
+        return self.y.cpu().numpy(), self.flags.cpu().numpy().view(np.uint32)[: self.lay.n_flag_words]
 
 
 def fold_flags(res, shape, lay):
-    """Oracle mismatch maps -> expected flag words [grid_m][grid_n]."""
+    """Oracle mismatch maps -> expected flag words [grid_m][grid_b][grid_n] for bits 0 and 1,
+    and the per-pixel-group corner bit [grid_m] (bit 2 may sit on any word of the group)."""
     s = shape
-    out = np.zeros((lay.grid_m, lay.grid_n), dtype=np.uint32)
+    out = np.zeros((lay.grid_m, lay.grid_b, lay.grid_n), dtype=np.uint32)
+    corner = np.zeros((lay.grid_m,), dtype=bool)
     PQ = s.P * s.Q
-    fc = res["fc_bad"].reshape(s.N, PQ).any(axis=0)
+    fc = res["fc_bad"].reshape(s.N, PQ)
     ic = res["ic_bad"].reshape(PQ, s.K)
     co = res["corner_bad"].reshape(PQ)
     for tm in range(lay.grid_m):
         lo, hi = tm * lay.tile_pixels, min(PQ, (tm + 1) * lay.tile_pixels)
-        if fc[lo:hi].any():
-            out[tm, 0] |= 1
-        if co[lo:hi].any():
-            out[tm, 0] |= 4
+        corner[tm] = co[lo:hi].any()
+        for tb in range(lay.grid_b):
+            if fc[tb * lay.tile_batch:(tb + 1) * lay.tile_batch, lo:hi].any():
+                out[tm, tb, 0] |= 1
         for tn in range(lay.grid_n):
             if ic[lo:hi, tn * lay.tile_n:(tn + 1) * lay.tile_n].any():
-                out[tm, tn] |= 2
-    return out
+                out[tm, 0, tn] |= 2
+    return out, corner
+
+
+def flags_match(flags, res, shape, lay):
+    exp, corner = fold_flags(res, shape, lay)
+    f = flags.reshape(lay.grid_m, lay.grid_b, lay.grid_n)
+    return np.array_equal(f & 3, exp) and np.array_equal(((f & 4) != 0).any(axis=(1, 2)), corner) and not (f & ~np.uint32(7)).any()

@@ -53,7 +53,7 @@ def test_unsupported_descriptor(L):
         abed.get_layout(d)
     assert e.value.status == 2
     d = abed.desc_from_shape(CONFIG1[0])
-    d.N = 300
+    d.C, d.R, d.S = 4096, 5, 5                      # C*R*S > 64K: int32 accumulation no longer exact
     with pytest.raises(AbedError) as e:
         abed.get_layout(d)
     assert e.value.status == 2
@@ -64,13 +64,14 @@ def test_layout_consistency(L, s):
     d = abed.desc_from_shape(s)
     for v in Variant:
         lay = abed.get_layout(d, 0, v)
-        assert lay.tile_m == lay.tile_pixels * lay.n_padded
-        assert lay.n_padded >= s.N
-        assert lay.grid_m * lay.tile_pixels >= s.P * s.Q > (lay.grid_m - 1) * lay.tile_pixels
-        assert lay.grid_n * lay.tile_n >= s.K > (lay.grid_n - 1) * lay.tile_n
-        assert lay.n_flag_words == lay.grid_m * lay.grid_n
+        checked = 1 <= v <= 5
+        entries = s.N + (lay.d_i if checked else 0)
+        fblocks = (s.K + 15) // 16 + (1 if checked else 0)
+        assert lay.tile_pixels == 16 and lay.tile_n % 16 == 0 and lay.tile_batch % 4 == 0
+        assert lay.grid_m == (s.P * s.Q + 15) // 16
+        assert lay.grid_b * lay.tile_batch >= entries > (lay.grid_b - 1) * lay.tile_batch
+        assert lay.grid_n * lay.tile_n >= fblocks * 16 > (lay.grid_n - 1) * lay.tile_n
+        assert lay.n_flag_words == lay.grid_m * lay.grid_b * lay.grid_n
         assert lay.d_f == (2 if s.K <= 257 else 3) and lay.d_i == (2 if s.N > 1 else 1)
         assert lay.wchk_bytes == lay.d_f * s.R * s.S * s.C
         assert lay.xchk_bytes == lay.d_i * s.H * s.W * s.C
-        if 1 <= v <= 5:
-            assert lay.tile_pixels <= 8
