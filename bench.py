@@ -77,7 +77,31 @@ def main():
         abed.conv_int8(L.desc, L.x, L.w, L.wchk, L.xchk, compute_xchk, L.y, L.variant, flags=L.flags,
                        workspace=L.ws, y2=L.y2)
 
-    def time_steps(fn, steps, warmup):
+    stream = torch.cuda.Stream()
+
+    def time_steps(fn, steps, warmup, per_graph=10):
+        """K steps, launched as replays of a HIP graph that holds `per_graph` steps (the launches of a
+        step are tiny next to the host's cost of issuing them one by one).  Returns seconds per step."""
+        if steps % per_graph:
+            per_graph = 1
+        with torch.cuda.stream(stream):
+            for _ in range(max(1, warmup // 2)):
+                fn()                                  # eager warm-up (also one-time function attributes)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for _ in range(per_graph):
+                    fn()
+            for _ in range(max(1, warmup // per_graph)):
+                graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps // per_graph):
+                graph.replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps
+
+    def time_eager(fn, steps, warmup):
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
@@ -87,17 +111,25 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
-    def event_time(fn, reps):
-        """Average duration of fn's launches on torch's current stream (the stream the library launches on)."""
+    def event_time(fn, reps=20, replays=10):
+        """Average duration of one call of fn (its kernel launches), from HIP events on the stream the
+        library launches on, around replays of a graph of `reps` calls."""
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        fn()
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
+        with torch.cuda.stream(stream):
             fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e-3 / reps
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for _ in range(reps):
+                    fn()
+            graph.replay()
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for _ in range(replays):
+                graph.replay()
+            e1.record(stream)
+            torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / (reps * replays)
 
     sets = {}
     wanted = [Variant.FUSED_OCG, Variant.NONE, Variant.DUPLICATE]
@@ -118,8 +150,9 @@ def main():
     # the other variants: same protocol, fewer steps for the slow ones
     t_var = {Variant.FUSED_OCG: t_checked}
     for v in wanted[1:]:
-        t_var[v] = time_steps(step_of(v), max(20, args.steps // 2), max(5, args.warmup // 2))
+        t_var[v] = time_steps(step_of(v), max(20, args.steps // 2 // 10 * 10), max(10, args.warmup // 2))
     t_unchecked = t_var[Variant.NONE]
+    t_checked_eager = time_eager(step_of(Variant.FUSED_OCG), max(20, args.steps // 4), 5)
     t_dup = t_var[Variant.DUPLICATE]
 
     # ---- per-layer kernel durations with events on the launch stream ----
@@ -127,15 +160,16 @@ def main():
     for i, s in enumerate(layers):
         Lc, Ln = sets[Variant.FUSED_OCG][i], sets[Variant.NONE][i]
         run_layer(Lc, True)
-        t_conv_chk = event_time(lambda: run_layer(Lc, False), 100)       # augmented conv kernel alone
-        t_all_chk = event_time(lambda: run_layer(Lc, True), 100)         # ICG + augmented conv
-        t_conv_plain = event_time(lambda: run_layer(Ln, False), 100)
+        t_conv_chk = event_time(lambda: run_layer(Lc, False))       # augmented conv kernel alone
+        t_all_chk = event_time(lambda: run_layer(Lc, True))         # ICG + augmented conv
+        t_conv_plain = event_time(lambda: run_layer(Ln, False))
         per_layer.append(dict(layer=s.name, gop=s.ops / 1e9, unchecked_us=t_conv_plain * 1e6,
                               checked_conv_us=t_conv_chk * 1e6, checked_total_us=t_all_chk * 1e6,
                               unchecked_tops=s.ops / t_conv_plain / 1e12, checked_tops=s.ops / t_all_chk / 1e12,
                               overhead_pct=100.0 * (t_all_chk / t_conv_plain - 1.0),
-                              min_bytes_i32=s.min_bytes(1, 1, 4), tile=[Lc.lay.tile_m, Lc.lay.tile_n],
-                              grid=[Lc.lay.grid_m, Lc.lay.grid_n]))
+                              min_bytes_i32=s.min_bytes(1, 1, 4),
+                              tile=[Lc.lay.tile_pixels, Lc.lay.tile_batch, Lc.lay.tile_n],
+                              grid=[Lc.lay.grid_m, Lc.lay.grid_b, Lc.lay.grid_n]))
     dom = max(per_layer, key=lambda r: r["checked_conv_us"])
     dom_shape = layers[[r["layer"] for r in per_layer].index(dom["layer"])]
     achieved = dom_shape.ops / (dom["checked_conv_us"] * 1e-6) / 1e12
@@ -146,7 +180,8 @@ def main():
 
     out = dict(metric="checked conv TOPS (int8) and ABED overhead % vs unchecked and vs duplication",
                value=total_ops / t_checked / 1e12, unit="TOPS", n_gpus=1, steps=args.steps, warmup=args.warmup,
-               ms_per_step=t_checked * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None,
+               ms_per_step=t_checked * 1e3, ms_per_step_eager_launch=t_checked_eager * 1e3,
+               launch="HIP graph replay of 10 steps (8 kernel launches per step)", higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="int8 (int32 accumulate)", data="synthetic",
                config=dict(workload="configs[1]: four ResNet-50-shaped int8 3x3 layers, N=32, s1 p1, "
                                     "C=K=64@56, 128@28, 256@14, 512@7; variant FusedOCG (ICG + augmented conv), int32 ConvOut",

@@ -69,6 +69,7 @@ struct ConvParams {
     // accumulator fault injection (tests): tile coordinates of the element
     int inj_on, inj_pg, inj_nt, inj_kt, inj_mb, inj_kb, inj_lane, inj_v;
     uint32_t inj_mask;
+    int dbg;
 };
 
 // 64 bytes of zeros: the source of every masked 16-byte chunk
@@ -99,6 +100,23 @@ __device__ __forceinline__ int requant(int acc, float sc, float bi, int relu)
     if (relu) t = fmaxf(t, 0.f);
     t = fminf(fmaxf(rintf(t), -128.f), 127.f);
     return (int)t;
+}
+
+// Residual partials that another workgroup will read: written through to device-coherent
+// memory and read back past the non-coherent caches (relaxed device-scope atomics), so that no
+// cache write-back fence is needed; ordering comes from waiting for the stores to complete
+// before the arrival counter is bumped.
+__device__ __forceinline__ void st_dev(int *p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ int ld_dev(const int *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_dev4(int *p, i32x4 v)
+{
+    st_dev(p, v[0]); st_dev(p + 1, v[1]); st_dev(p + 2, v[2]); st_dev(p + 3, v[3]);
+}
+__device__ __forceinline__ i32x4 ld_dev4(const int *p)
+{
+    i32x4 v;
+    v[0] = ld_dev(p); v[1] = ld_dev(p + 1); v[2] = ld_dev(p + 2); v[3] = ld_dev(p + 3);
+    return v;
 }
 
 // balanced base-256 digit (same rule as the ICG kernel)
@@ -214,7 +232,8 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s) issue(s);
     int stage = 0;
-    for (int step = 0; step < p.nsteps; ++step) {
+    if (p.dbg & 4) return;
+    for (int step = 0; step < ((p.dbg & 2) ? 0 : p.nsteps); ++step) {
         ABED_WAIT_VMCNT((NST - 2) * L);          // this wave's loads of `step` have landed
         __builtin_amdgcn_s_barrier();            // everyone's have, and everyone is done with step-1
         {
@@ -283,11 +302,12 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
             if (checking && fc_local) {
                 if (r != 0) my_flag |= (e < p.N) ? 1u : 4u;
             } else if (lg == 0) {
-                p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + kt) * (MB * 16) + (wave * WM + i) * 16 + lj] = (int)r;
+                st_dev(&p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + kt) * (MB * 16) + (wave * WM + i) * 16 + lj], (int)r);
             }
         }
     }
 
+    if (p.dbg & 1) return;
     // (3) stores; checksum rows and columns are trimmed from y (end of Sec. 4.3)
     int nx[WK][4];   // batch sums of the int8 outputs (variant 5)
     const bool want_next = p.mode == MODE_CHECK_NEXT && p.out_int8 && p.xchk_next != nullptr;
@@ -352,7 +372,7 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
             }
         }
     }
-    if (!aug || p.mode == MODE_WRITE) return;
+    if (!aug || p.mode == MODE_WRITE || (p.dbg & 8)) return;
 
     // (4) IC residual of every (pixel, filter) of the tile (Sec. 3.2 option 1): sum over this
     // wave's entries in registers, then over the 4 waves through LDS.  A second pass does the
@@ -394,7 +414,7 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
                 if (checking && ic_local) {
                     if ((c[0] | c[1] | c[2] | c[3]) != 0) my_flag |= (fb < p.kblk) ? 2u : 4u;
                 } else {
-                    *reinterpret_cast<i32x4 *>(p.ws_ic + part) = c;
+                    st_dev4(p.ws_ic + part, c);
                 }
             } else if (fb < p.kblk) {
                 if (ic_local) {
@@ -414,7 +434,7 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
                         }
                     }
                 } else {
-                    *reinterpret_cast<i32x4 *>(p.ws_nx + part) = c;
+                    st_dev4(p.ws_nx + part, c);
                 }
             }
         }
@@ -427,28 +447,31 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
     if (my_flag) atomicOr(reinterpret_cast<unsigned *>(&e_misc[0]), my_flag);
     __syncthreads();
     const long long word = ((long long)pg * p.grid_b + nt) * p.grid_n + kt;
-    if (tid == 0) p.flags[word] = (uint32_t)e_misc[0];
-    if (fc_local && ic_local) return;
-    __threadfence();
+    if (tid == 0) __hip_atomic_store(&p.flags[word], (uint32_t)e_misc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((fc_local && ic_local) || (p.dbg & 16)) return;
+    // all partial stores of this workgroup have completed (they are write-through) ...
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
+    // ... before its arrival is counted
     if (tid == 0) {
-        if (!fc_local) e_misc[1] = atomicAdd(&p.cnt_fc[pg * p.grid_b + nt], 1u) == (unsigned)(p.grid_n - 1);
-        if (!ic_local) e_misc[2] = atomicAdd(&p.cnt_ic[pg * p.grid_n + kt], 1u) == (unsigned)(p.grid_b - 1);
+        if (!fc_local)
+            e_misc[1] = __hip_atomic_fetch_add(&p.cnt_fc[pg * p.grid_b + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_n - 1);
+        if (!ic_local)
+            e_misc[2] = __hip_atomic_fetch_add(&p.cnt_ic[pg * p.grid_n + kt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_b - 1);
     }
     __syncthreads();
     const bool last_fc = e_misc[1] != 0, last_ic = e_misc[2] != 0;
     if (!last_fc && !last_ic) return;
-    __threadfence();
     if (last_fc) {
         uint32_t late = 0;
         for (int r = tid; r < MB * 16; r += 256) {
             unsigned s = 0;
             for (int c = 0; c < p.grid_n; ++c)
-                s += (unsigned)p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + c) * (MB * 16) + r];
+                s += (unsigned)ld_dev(&p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + c) * (MB * 16) + r]);
             if (s != 0) late |= (nt * MB + (r >> 4) < p.N) ? 1u : 4u;
         }
-        if (late) atomicOr(&p.flags[((long long)pg * p.grid_b + nt) * p.grid_n], late);
-        if (tid == 0) p.cnt_fc[pg * p.grid_b + nt] = 0;       // ready for the next call
+        if (late) __hip_atomic_fetch_or(&p.flags[((long long)pg * p.grid_b + nt) * p.grid_n], late, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_store(&p.cnt_fc[pg * p.grid_b + nt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
     }
     if (last_ic) {
         uint32_t late = 0;
@@ -458,8 +481,8 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
             i32x4 s = zero4, sn = zero4;
             for (int b = 0; b < p.grid_b; ++b) {
                 const long long part = ((((long long)pg * p.grid_n + kt) * p.grid_b + b) * WK + kb) * 256 + ln * 4;
-                s += *reinterpret_cast<const i32x4 *>(p.ws_ic + part);
-                if (want_next) sn += *reinterpret_cast<const i32x4 *>(p.ws_nx + part);
+                s += ld_dev4(p.ws_ic + part);
+                if (want_next) sn += ld_dev4(p.ws_nx + part);
             }
             if ((s[0] | s[1] | s[2] | s[3]) != 0) late |= (fb < p.kblk) ? 2u : 4u;
             if (want_next && fb < p.kblk) {
@@ -475,8 +498,8 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
                 }
             }
         }
-        if (late) atomicOr(&p.flags[((long long)pg * p.grid_b) * p.grid_n + kt], late);
-        if (tid == 0) p.cnt_ic[pg * p.grid_n + kt] = 0;
+        if (late) __hip_atomic_fetch_or(&p.flags[((long long)pg * p.grid_b) * p.grid_n + kt], late, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_store(&p.cnt_ic[pg * p.grid_n + kt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
