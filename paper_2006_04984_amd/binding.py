@@ -74,6 +74,11 @@ def lib():
         L.abed_workspace_init.argtypes = [vp, ctypes.c_size_t, vp]
         L.abed_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
                                      vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp, vp]
+        f32 = ctypes.c_float
+        L.abed_filter_prepare_fp16.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+        L.abed_input_checksum_fp16.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+        L.abed_conv_fp16.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, i32, i32, f32, f32,
+                                     vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp, vp]
         _LIB = L
     return _LIB
 
@@ -135,3 +140,23 @@ def conv_int8(desc, x, w, wchk, xchk, compute_xchk, y, variant, flags=None, epil
     _check(lib().abed_conv_int8(ctypes.byref(desc), _p(x), _p(w), _p(wchk), _p(xchk), int(bool(compute_xchk)),
                                 _p(y), epi, int(variant), _p(flags), _p(xchk_next), _p(workspace), nbytes,
                                 inj, _p(y2), _stream(stream)))
+
+
+def filter_prepare_fp16(desc, w, wchk, stream=None):
+    _check(lib().abed_filter_prepare_fp16(ctypes.byref(desc), _p(w), _p(wchk), _stream(stream)))
+
+
+def input_checksum_fp16(desc, x, xchk, stream=None):
+    _check(lib().abed_input_checksum_fp16(ctypes.byref(desc), _p(x), _p(xchk), _stream(stream)))
+
+
+def conv_fp16(desc, x, w, wchk, xchk, compute_xchk, y, variant, rtol=1e-3, atol=0.0, flags=None, out_fp32=False,
+              workspace=None, inject=None, y2=None, stream=None):
+    """abed_conv_fp16.  inject = (site, index, bit) or None."""
+    inj = None
+    if inject is not None:
+        inj = ctypes.byref(_Inject(int(inject[0]), int(inject[1]), int(inject[2])))
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().abed_conv_fp16(ctypes.byref(desc), _p(x), _p(w), _p(wchk), _p(xchk), int(bool(compute_xchk)),
+                                _p(y), int(bool(out_fp32)), int(variant), float(rtol), float(atol), _p(flags),
+                                _p(workspace), nbytes, inj, _p(y2), _stream(stream)))

@@ -46,6 +46,7 @@ int digits_for_count(long long count)
 
 struct Plan {
     int P, Q, PQ, crs;
+    int esize;                            // bytes per element: 1 (int8) or 2 (fp16)
     int d_f, d_i;
     int n_entries, kblk, n_fblk;          // batch entries, real filter blocks, filter blocks incl. the digit block
     int wm, wk, mb;                       // entries per wave, filter blocks per tile, entries per tile
@@ -99,8 +100,10 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return ABED_EINVAL;
     if (variant < ABED_NONE || variant > ABED_DUPLICATE) return ABED_EINVAL;
     if (dtype != ABED_INT8 && dtype != ABED_FP16) return ABED_EINVAL;
-    if (dtype == ABED_FP16) return ABED_EUNSUPPORTED;
-    if (d->C % 16 != 0) return ABED_EUNSUPPORTED;          // 16-byte chunks of one filter tap
+    const bool f16 = dtype == ABED_FP16;
+    pl.esize = f16 ? 2 : 1;
+    if ((d->C * pl.esize) % 16 != 0) return ABED_EUNSUPPORTED;   // 16-byte chunks of one filter tap
+    if (f16 && !(variant == ABED_NONE || variant == ABED_FUSED_OCG || variant == ABED_DUPLICATE)) return ABED_EUNSUPPORTED;
     const long long crs = (long long)d->C * d->R * d->S;
     if (crs > 65536) return ABED_EUNSUPPORTED;             // int32 accumulators are exact up to C*R*S = 64K (Sec. 4.1)
     if ((long long)d->N * d->H * d->W * d->C >= (1LL << 31)) return ABED_EUNSUPPORTED;
@@ -109,8 +112,8 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     pl.PQ = pl.P * pl.Q;
     pl.crs = (int)crs;
     if ((long long)d->N * pl.PQ * d->K >= (1LL << 31)) return ABED_EUNSUPPORTED;
-    pl.d_f = digits_for_count(d->K);
-    pl.d_i = digits_for_count(d->N);
+    pl.d_f = f16 ? 2 : digits_for_count(d->K);             // fp16: the hi/lo pair (Sec. 7)
+    pl.d_i = f16 ? 2 : digits_for_count(d->N);
     if (pl.d_f > 4 || pl.d_i > 4) return ABED_ERANGE;
 
     // Variants 1..5 report flags on the tile grid of the augmented problem (N + d_i batch
@@ -135,8 +138,8 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
         pl.off_yfi = take((long long)pl.d_i * pl.PQ * pl.d_f * 4);
     } else if (variant == ABED_FUSED_PARTIAL_REDUCTION || variant == ABED_FUSED_OCG || variant == ABED_FUSED_IOCG) {
         const long long tiles = (long long)pl.grid_m * pl.grid_b * pl.grid_n;
-        pl.off_fc = take(tiles * pl.mb * 16 * 4);
-        pl.off_ic = take(tiles * pl.wk * 256 * 4);
+        pl.off_fc = take(tiles * pl.mb * 16 * 4 * (f16 ? 2 : 1));     // fp16 keeps sum and checksum value apart
+        pl.off_ic = take(tiles * pl.wk * 256 * 4 * (f16 ? 2 : 1));
         if (variant == ABED_FUSED_IOCG) pl.off_nx = take(tiles * pl.wk * 256 * 4);
     }
     pl.ws_bytes = off;
@@ -148,7 +151,8 @@ void fill_params(ConvParams &cp, const abed_conv_desc_t *d, const Plan &pl)
     memset(&cp, 0, sizeof(cp));
     cp.N = d->N; cp.H = d->H; cp.W = d->W; cp.C = d->C; cp.K = d->K; cp.R = d->R; cp.S = d->S;
     cp.sh = d->stride_h; cp.sw = d->stride_w; cp.ph = d->pad_h; cp.pw = d->pad_w;
-    cp.P = pl.P; cp.Q = pl.Q; cp.crs = pl.crs; cp.nsteps = (pl.crs + 63) / 64;
+    cp.P = pl.P; cp.Q = pl.Q;
+    cp.cb = d->C * pl.esize; cp.crsb = pl.crs * pl.esize; cp.nsteps = (cp.crsb + 63) / 64;
     cp.n_entries = pl.n_entries; cp.n_fblk = pl.n_fblk; cp.kblk = pl.kblk;
     cp.d_f = pl.d_f; cp.d_i = pl.d_i;
     cp.grid_m = pl.grid_m; cp.grid_b = pl.grid_b; cp.grid_n = pl.grid_n;
@@ -181,8 +185,8 @@ abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_
     cp.x = x; cp.w = w; cp.y = y; cp.mode = MODE_PLAIN;
     if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
     set_injection(cp, d, pl, inject);
-    if (!launch_conv_i8(pl.wm, pl.wk, cp, pl.grid_m * pl.grid_b * pl.grid_n, st)) return ABED_EUNSUPPORTED;
-    LAUNCH_CHECK("conv_i8_kernel (unchecked)");
+    if (!launch_conv(false, pl.wm, pl.wk, cp, pl.grid_m * pl.grid_b * pl.grid_n, st)) return ABED_EUNSUPPORTED;
+    LAUNCH_CHECK("conv_kernel (unchecked)");
     return ABED_OK;
 }
 
@@ -223,8 +227,8 @@ abed_status_t abed_get_layout(const abed_conv_desc_t *desc, int32_t dtype, int32
     out->d_i = pl.d_i;
     out->n_flag_words = (long long)pl.grid_m * pl.grid_b * pl.grid_n;
     out->workspace_bytes = pl.ws_bytes;
-    out->wchk_bytes = (long long)pl.d_f * pl.crs;
-    out->xchk_bytes = (long long)pl.d_i * desc->H * desc->W * desc->C;
+    out->wchk_bytes = (long long)pl.d_f * pl.crs * pl.esize;
+    out->xchk_bytes = (long long)pl.d_i * desc->H * desc->W * desc->C * pl.esize;
     out->xchk_next_bytes = (long long)pl.d_i * pl.PQ * desc->K;
     return ABED_OK;
 }
@@ -263,8 +267,29 @@ abed_status_t abed_input_checksum_int8(const abed_conv_desc_t *desc, const int8_
     return ABED_OK;
 }
 
-abed_status_t abed_filter_prepare_fp16(const abed_conv_desc_t *, const void *, void *, void *) { return ABED_EUNSUPPORTED; }
-abed_status_t abed_input_checksum_fp16(const abed_conv_desc_t *, const void *, void *, void *) { return ABED_EUNSUPPORTED; }
+abed_status_t abed_filter_prepare_fp16(const abed_conv_desc_t *desc, const void *w, void *wchk, void *stream)
+{
+    Plan pl;
+    abed_status_t s = make_plan(desc, ABED_FP16, ABED_NONE, false, pl);
+    if (s != ABED_OK) return s;
+    if (!w || !wchk) return ABED_EINVAL;
+    filter_checksum_f16_kernel<<<dim3((pl.crs + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>((const _Float16 *)w, (_Float16 *)wchk, desc->K, pl.crs);
+    LAUNCH_CHECK("filter_checksum_f16_kernel");
+    return ABED_OK;
+}
+
+abed_status_t abed_input_checksum_fp16(const abed_conv_desc_t *desc, const void *x, void *xchk, void *stream)
+{
+    Plan pl;
+    abed_status_t s = make_plan(desc, ABED_FP16, ABED_NONE, false, pl);
+    if (s != ABED_OK) return s;
+    if (!x || !xchk) return ABED_EINVAL;
+    const long long hwc = (long long)desc->H * desc->W * desc->C;
+    const long long chunks = hwc / 8;
+    batch_checksum_f16_kernel<<<dim3((unsigned)((chunks + 63) / 64)), dim3(256), 0, (hipStream_t)stream>>>((const _Float16 *)x, (_Float16 *)xchk, desc->N, hwc);
+    LAUNCH_CHECK("batch_checksum_f16_kernel");
+    return ABED_OK;
+}
 
 abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
                              const int8_t *wchk, int8_t *xchk, int32_t compute_xchk,
@@ -342,7 +367,7 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
             cp.out_int8 = 0;
             cp.mode = MODE_WRITE;
             cp.ws_yf = yf; cp.ws_yi = yi; cp.ws_yfi = yfi;
-            if (!launch_conv_i8(pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
+            if (!launch_conv(false, pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
             LAUNCH_CHECK("conv_i8_kernel (augmented, write)");
         }
         if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)convout, inject->index, 1u << inject->bit);
@@ -371,7 +396,7 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     cp.cnt_fc = (uint32_t *)wsp(pl.off_cnt_fc);
     cp.cnt_ic = (uint32_t *)wsp(pl.off_cnt_ic);
     cp.ws_fc = wsp(pl.off_fc); cp.ws_ic = wsp(pl.off_ic); cp.ws_nx = wsp(pl.off_nx);
-    if (!launch_conv_i8(pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
+    if (!launch_conv(false, pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("conv_i8_kernel (augmented)");
     if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)y, inject->index, 1u << inject->bit);
     if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
@@ -384,11 +409,59 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     return ABED_OK;
 }
 
-abed_status_t abed_conv_fp16(const abed_conv_desc_t *, const void *, const void *, const void *, void *, int32_t,
-                             void *, int32_t, int32_t, float, float, uint32_t *, void *, size_t,
-                             const abed_inject_t *, void *, void *)
+abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const void *w,
+                             const void *wchk, void *xchk, int32_t compute_xchk,
+                             void *y, int32_t out_fp32, int32_t variant, float rtol, float atol,
+                             uint32_t *flags, void *workspace, size_t workspace_bytes,
+                             const abed_inject_t *inject, void *y2, void *stream)
 {
-    return ABED_EUNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    Plan pl;
+    abed_status_t s = make_plan(desc, ABED_FP16, variant, false, pl);
+    if (s != ABED_OK) return s;
+    if (!x || !w || !y) return ABED_EINVAL;
+    const bool checked = variant == ABED_FUSED_OCG;
+    if (checked && (!wchk || !xchk || !flags)) return ABED_EINVAL;
+    if (checked && !(rtol >= 0.f && atol >= 0.f)) return ABED_EINVAL;
+    if (variant == ABED_DUPLICATE && (!y2 || !flags)) return ABED_EINVAL;
+    if (checked && (!workspace || (long long)workspace_bytes < pl.ws_bytes)) return ABED_EWORKSPACE;
+    if (inject && inject->site != 0) {
+        if (inject->site != 1) return ABED_EUNSUPPORTED;
+        if (inject->index < 0 || inject->index >= (long long)desc->N * pl.PQ * desc->K || inject->bit < 0 || inject->bit > 15)
+            return ABED_EINVAL;
+    }
+    char *ws = (char *)workspace;
+    auto wsp = [&](long long off) { return off < 0 ? (int32_t *)nullptr : (int32_t *)(ws + off); };
+    if (checked && compute_xchk) {
+        s = abed_input_checksum_fp16(desc, x, xchk, stream);
+        if (s != ABED_OK) return s;
+    }
+    ConvParams cp;
+    fill_params(cp, desc, pl);
+    cp.x = (const int8_t *)x; cp.w = (const int8_t *)w; cp.wchk = (const int8_t *)wchk; cp.xchk = (const int8_t *)xchk;
+    cp.y = y; cp.flags = flags; cp.out_fp32 = out_fp32 ? 1 : 0; cp.rtol = rtol; cp.atol = atol;
+    set_injection(cp, desc, pl, inject);
+    const int grid = pl.grid_m * pl.grid_b * pl.grid_n;
+    if (variant == ABED_NONE || variant == ABED_DUPLICATE) {
+        cp.mode = MODE_PLAIN;
+        if (variant == ABED_DUPLICATE) fill_u32_kernel<<<1, 64, 0, st>>>(flags, 1, 0u);
+        if (!launch_conv(true, pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
+        if (variant == ABED_DUPLICATE) {
+            cp.y = y2; cp.inj_on = 0;
+            launch_conv(true, pl.wm, pl.wk, cp, grid, st);
+            const long long bytes = (long long)desc->N * pl.PQ * desc->K * (out_fp32 ? 4 : 2);
+            compare_kernel<<<dim3((unsigned)((bytes / 16 + 256) / 256)), dim3(256), 0, st>>>(y, y2, bytes, flags);
+        }
+        LAUNCH_CHECK("conv_kernel (fp16, unchecked)");
+        return ABED_OK;
+    }
+    cp.mode = MODE_CHECK;
+    cp.cnt_fc = (uint32_t *)wsp(pl.off_cnt_fc);
+    cp.cnt_ic = (uint32_t *)wsp(pl.off_cnt_ic);
+    cp.ws_fc = wsp(pl.off_fc); cp.ws_ic = wsp(pl.off_ic);
+    if (!launch_conv(true, pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
+    LAUNCH_CHECK("conv_kernel (fp16, augmented)");
+    return ABED_OK;
 }
 
 }  // extern "C"

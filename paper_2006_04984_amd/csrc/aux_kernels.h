@@ -72,6 +72,55 @@ __global__ __launch_bounds__(256) void batch_checksum_i8_kernel(const int8_t *x,
     }
 }
 
+// fp16 (Sec. 7): the offline filter checksum is summed in double and stored as a hi/lo pair
+// of fp16 filters, hi = fp16(wsum), lo = fp16(wsum - hi).
+__global__ void filter_checksum_f16_kernel(const _Float16 *w, _Float16 *wchk, int K, int crs)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= crs) return;
+    double s = 0.0;
+    for (int k = 0; k < K; ++k) s += (double)w[(long long)k * crs + e];
+    const _Float16 hi = (_Float16)s;
+    wchk[e] = hi;
+    wchk[(long long)crs + e] = (_Float16)(s - (double)hi);
+}
+
+// Online batch checksum for fp16 inputs: fp32 accumulation (the higher-precision accumulator of
+// Sec. 7), 8 elements per group of 4 lanes, result stored as a hi/lo pair of fp16 images.
+__global__ __launch_bounds__(256) void batch_checksum_f16_kernel(const _Float16 *x, _Float16 *xchk, int N, long long hwc)
+{
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    const long long chunk = (long long)blockIdx.x * 64 + (threadIdx.x >> 2);
+    const int part = threadIdx.x & 3;
+    const long long e0 = chunk * 8;
+    const bool live = e0 < hwc;
+    float s[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s[i] = 0.f;
+    if (live) {
+        for (int n = part; n < N; n += 4) {
+            const h8 v = *reinterpret_cast<const h8 *>(x + n * hwc + e0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s[i] += (float)v[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        s[i] += __shfl_xor(s[i], 1, 64);
+        s[i] += __shfl_xor(s[i], 2, 64);
+    }
+    if (live && part == 0) {
+        h8 hi, lo;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            hi[i] = (_Float16)s[i];
+            lo[i] = (_Float16)(s[i] - (float)hi[i]);
+        }
+        *reinterpret_cast<h8 *>(xchk + e0) = hi;
+        *reinterpret_cast<h8 *>(xchk + hwc + e0) = lo;
+    }
+}
+
 struct VerifyParams {
     const int32_t *y;     // ConvOut [N][PQ][K]
     const int32_t *yf;    // [N][PQ][d_f]   digit fmaps of the checksum filters

@@ -11,19 +11,20 @@
 namespace abed {
 
 template <int WM>
-static void go(const ConvParams &p, int grid, hipStream_t st)
+static void go(bool f16, const ConvParams &p, int grid, hipStream_t st)
 {
-    conv_i8_kernel<WM, INST_WK, kStages><<<dim3(grid), dim3(256), 0, st>>>(p);
+    if (f16) conv_kernel<true, WM, INST_WK, kStages><<<dim3(grid), dim3(256), 0, st>>>(p);
+    else conv_kernel<false, WM, INST_WK, kStages><<<dim3(grid), dim3(256), 0, st>>>(p);
 }
 
-bool CAT(launch_conv_i8_wk, INST_WK)(int wm, const ConvParams &p, int grid, hipStream_t st)
+bool CAT(launch_conv_wk, INST_WK)(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st)
 {
     switch (wm) {
-    case 1: go<1>(p, grid, st); return true;
-    case 2: go<2>(p, grid, st); return true;
-    case 3: go<3>(p, grid, st); return true;
-    case 5: go<5>(p, grid, st); return true;
-    case 9: go<9>(p, grid, st); return true;
+    case 1: go<1>(f16, p, grid, st); return true;
+    case 2: go<2>(f16, p, grid, st); return true;
+    case 3: go<3>(f16, p, grid, st); return true;
+    case 5: go<5>(f16, p, grid, st); return true;
+    case 9: go<9>(f16, p, grid, st); return true;
     }
     return false;
 }

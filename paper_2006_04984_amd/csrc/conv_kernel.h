@@ -29,10 +29,13 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace abed {
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 enum Mode : int {
     MODE_PLAIN = 0,     // no checks (n_entries = N, no digit block)
@@ -57,8 +60,9 @@ struct ConvParams {
     uint32_t *cnt_fc;            // arrival counters [grid_m][grid_b]
     uint32_t *cnt_ic;            // arrival counters [grid_m][grid_n]
     int N, H, W, C, K, R, S, sh, sw, ph, pw, P, Q;
-    int crs;          // C*R*S
-    int nsteps;       // ceil(crs / 64)
+    int cb;           // bytes of one filter tap: C * element size
+    int crsb;         // bytes of one filter: C*R*S * element size
+    int nsteps;       // ceil(crsb / 64)
     int n_entries;    // N, or N + d_i when checked
     int n_fblk;       // ceil(K/16), or that + 1 when checked
     int kblk;         // ceil(K/16): index of the digit block
@@ -70,6 +74,8 @@ struct ConvParams {
     int inj_on, inj_pg, inj_nt, inj_kt, inj_mb, inj_kb, inj_lane, inj_v;
     uint32_t inj_mask;
     int dbg;
+    int out_fp32;      // fp16 path: 1 = fp32 output
+    float rtol, atol;  // fp16 path: threshold of the checks
 };
 
 // 64 bytes of zeros: the source of every masked 16-byte chunk
@@ -127,14 +133,18 @@ __device__ __forceinline__ int next_digit(int &s)
     return d;
 }
 
-template <int WM, int WK, int NST>
-__global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
+// F16 = false: int8 data, int32 accumulators, exact checks mod 2^32.
+// F16 = true: fp16 data, fp32 accumulators, threshold checks (Sec. 7); the two checksum tensors
+// per side are the hi/lo pair, recombined by addition.
+template <bool F16, int WM, int WK, int NST>
+__global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
 {
+    using acc_t = typename std::conditional<F16, f32x4, i32x4>::type;
     constexpr int MB = 4 * WM;                 // batch entries per tile
     constexpr int NB = WK + MB;                // 1 KB blocks per stage: filter blocks, then entry blocks
     constexpr int L = (NB + 3) / 4;            // direct-to-LDS loads per wave and step
     constexpr int STAGE = NB * 1024;
-    constexpr int EPI_BYTES = 4 * WK * 1024 + 64;
+    constexpr int EPI_BYTES = (F16 ? 8 : 4) * WK * 1024 + 64;
     constexpr int LDS_BYTES = (NST * STAGE > EPI_BYTES) ? NST * STAGE : EPI_BYTES;
     static_assert((NST - 1) * L <= 63, "vmcnt is a 6-bit counter");
     __shared__ __attribute__((aligned(1024))) int8_t lds[LDS_BYTES];
@@ -152,7 +162,7 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
     const int nt = bid % p.grid_b;
     const int pg = bid / p.grid_b;
     const int PQ = p.P * p.Q;
-    const long long HWC = (long long)p.H * p.W * p.C;
+    const long long HWC = (long long)p.H * p.W * p.cb;      // bytes of one image
 
     // ---------------- loader set-up ----------------
     // In a 1 KB block lane l fills row l>>2, chunk position l&3.
@@ -168,7 +178,7 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
             const int pp = pix / p.Q, qq = pix - pp * p.Q;
             h0 = pp * p.sh - p.ph;
             w0 = qq * p.sw - p.pw;
-            pix_off = ((long long)h0 * p.W + w0) * p.C;
+            pix_off = ((long long)h0 * p.W + w0) * p.cb;
         }
     }
     // the L blocks this wave loads each step: block b = wave + 4 i (clamped: a duplicate load is harmless)
@@ -183,8 +193,8 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
         if (b < WK) {
             const int fb = kt * WK + b;                       // global filter block
             const int f = fb * 16 + ld_row;
-            if (fb < p.kblk) { if (f < p.K) blk_base[i] = p.w + (long long)f * p.crs; }
-            else if (fb == p.kblk && fb < p.n_fblk) { if (ld_row < p.d_f) blk_base[i] = p.wchk + (long long)ld_row * p.crs; }
+            if (fb < p.kblk) { if (f < p.K) blk_base[i] = p.w + (long long)f * p.crsb; }
+            else if (fb == p.kblk && fb < p.n_fblk) { if (ld_row < p.d_f) blk_base[i] = p.wchk + (long long)ld_row * p.crsb; }
         } else {
             const int e = nt * MB + (b - WK);
             if (e < p.N) blk_base[i] = p.x + e * HWC;
@@ -193,14 +203,14 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
     }
 
     // position of this lane's chunk on the crs axis
-    int crs_pos = ld_chunk * 16;
+    int crs_pos = ld_chunk * 16;                // byte position
     int tap_r = 0, tap_s = 0, ch = crs_pos;
-    while (ch >= p.C) { ch -= p.C; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
+    while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
 
     auto issue = [&](int stage) {
-        const bool in_crs = crs_pos < p.crs;
+        const bool in_crs = crs_pos < p.crsb;
         const bool inb = in_crs && (unsigned)(h0 + tap_r) < (unsigned)p.H && (unsigned)(w0 + tap_s) < (unsigned)p.W;
-        const long long tap_off = pix_off + ((long long)tap_r * p.W + tap_s) * p.C + ch;
+        const long long tap_off = pix_off + ((long long)tap_r * p.W + tap_s) * p.cb + ch;
         int8_t *sbase = lds + stage * STAGE;
 #pragma unroll
         for (int i = 0; i < L; ++i) {
@@ -215,12 +225,12 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
         }
         crs_pos += 64;
         ch += 64;
-        while (ch >= p.C) { ch -= p.C; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
+        while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
     };
 
     // ---------------- accumulators ----------------
-    i32x4 acc[WM][WK];
-    const i32x4 zero4 = {0, 0, 0, 0};
+    acc_t acc[WM][WK];
+    const acc_t zero4 = {0, 0, 0, 0};
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -252,14 +262,181 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
             const i32x4 a = *reinterpret_cast<const i32x4 *>(ldsK + lds_off(kb * 16 + lj, lg));
 #pragma unroll
             for (int i = 0; i < WM; ++i)
-                acc[i][kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bfr[i], acc[i][kb], 0, 0, 0);
+                if constexpr (F16)
+                    acc[i][kb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, bfr[i]), acc[i][kb], 0, 0, 0);
+                else
+                    acc[i][kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bfr[i], acc[i][kb], 0, 0, 0);
         }
         if (++stage == NST) stage = 0;
     }
     ABED_WAIT_VMCNT(0);                          // drain the run-ahead loads before LDS is reused
     __builtin_amdgcn_s_barrier();
 
-    // ---------------- epilogue ----------------
+    if constexpr (F16) {
+        // ---------------- epilogue, fp16 data (Sec. 7) ----------------
+        const int pix = pg * 16 + lj;
+        const bool pvalid = pix < PQ;
+        float *e_ic = reinterpret_cast<float *>(lds);            // [2][4 waves][WK][64 lanes][4]: sums, checksum values
+        int *e_misc = reinterpret_cast<int *>(e_ic + 8 * WK * 256);
+        if (tid < 16) e_misc[tid] = 0;
+        uint32_t my_flag = 0;
+        const bool fc_local = p.grid_n == 1, ic_local = p.grid_b == 1;
+        const bool checking = p.mode == MODE_CHECK;
+        auto bad = [&](float sum, float chk) {
+            return !(fabsf(sum - chk) <= p.rtol * fmaxf(fabsf(sum), fabsf(chk)) + p.atol);   // NaN counts as a mismatch
+        };
+        // (1) fault injection: one bit of the value rounded to fp16; the corrupted value takes the
+        // accumulator's place in the reductions and in the store
+        if (p.inj_on && pg == p.inj_pg && nt == p.inj_nt && kt == p.inj_kt) {
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int kb = 0; kb < WK; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (wave * WM + i == p.inj_mb && kb == p.inj_kb && v == p.inj_v && lane == p.inj_lane) {
+                            const _Float16 h = (_Float16)acc[i][kb][v];
+                            const unsigned short bits = __builtin_bit_cast(unsigned short, h) ^ (unsigned short)p.inj_mask;
+                            acc[i][kb][v] = (float)__builtin_bit_cast(_Float16, bits);
+                        }
+        }
+        // (2) FC: sum over the real filters of every row against hi + lo of the checksum-filter fmaps
+        if (aug) {
+#pragma unroll
+            for (int i = 0; i < WM; ++i) {
+                const int e = nt * MB + wave * WM + i;
+                float sum = 0.f, chk = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < WK; ++kb) {
+                    const int fb = kt * WK + kb;
+                    const float t = (acc[i][kb][0] + acc[i][kb][1]) + (acc[i][kb][2] + acc[i][kb][3]);
+                    if (fb < p.kblk) sum += t;
+                    else if (fb == p.kblk) chk += t;      // rows 2..15 of the checksum block are zero filters
+                }
+                sum += __shfl_xor(sum, 16, 64); sum += __shfl_xor(sum, 32, 64);
+                chk += __shfl_xor(chk, 16, 64); chk += __shfl_xor(chk, 32, 64);
+                if (checking && fc_local) {
+                    if (bad(sum, chk)) my_flag |= (e < p.N) ? 1u : 4u;
+                } else if (lg == 0) {
+                    int *dst = &p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + kt) * (2 * MB * 16) + (wave * WM + i) * 16 + lj];
+                    st_dev(dst, __builtin_bit_cast(int, sum));
+                    st_dev(dst + MB * 16, __builtin_bit_cast(int, chk));
+                }
+            }
+        }
+        if (p.dbg & 1) return;
+        // (3) stores (checksum rows and columns are trimmed)
+#pragma unroll
+        for (int kb = 0; kb < WK; ++kb) {
+            const int fb = kt * WK + kb;
+            const int k = fb * 16 + lg * 4;
+            if (fb >= p.kblk) continue;
+#pragma unroll
+            for (int i = 0; i < WM; ++i) {
+                const int e = nt * MB + wave * WM + i;
+                if (!pvalid || e >= p.N) continue;
+                const long long o = ((long long)e * PQ + pix) * p.K + k;
+                if (p.out_fp32) {
+                    float *dst = reinterpret_cast<float *>(p.y) + o;
+                    if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<f32x4 *>(dst) = acc[i][kb];
+                    else
+                        for (int v = 0; v < 4; ++v)
+                            if (k + v < p.K) dst[v] = acc[i][kb][v];
+                } else {
+                    _Float16 *dst = reinterpret_cast<_Float16 *>(p.y) + o;
+                    typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+                    const f16x4 h = {(_Float16)acc[i][kb][0], (_Float16)acc[i][kb][1], (_Float16)acc[i][kb][2], (_Float16)acc[i][kb][3]};
+                    if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<f16x4 *>(dst) = h;
+                    else
+                        for (int v = 0; v < 4; ++v)
+                            if (k + v < p.K) dst[v] = h[v];
+                }
+            }
+        }
+        if (!aug || (p.dbg & 8)) return;
+        // (4) IC: sum over the real images of every (pixel, filter) against hi + lo of the checksum-image fmaps
+#pragma unroll
+        for (int kb = 0; kb < WK; ++kb) {
+            f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < WM; ++i) {
+                const int e = nt * MB + wave * WM + i;
+                if (e < p.N) sum += acc[i][kb];
+                else if (e < p.n_entries) chk += acc[i][kb];
+            }
+            *reinterpret_cast<f32x4 *>(e_ic + ((wave * WK + kb) * 64 + lane) * 4) = sum;
+            *reinterpret_cast<f32x4 *>(e_ic + 4 * WK * 256 + ((wave * WK + kb) * 64 + lane) * 4) = chk;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int c4 = 0; c4 < (WK + 3) / 4; ++c4) {
+            const int kb = 4 * c4 + wave;
+            if (kb >= WK) continue;
+            f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                sum += *reinterpret_cast<const f32x4 *>(e_ic + ((w * WK + kb) * 64 + lane) * 4);
+                chk += *reinterpret_cast<const f32x4 *>(e_ic + 4 * WK * 256 + ((w * WK + kb) * 64 + lane) * 4);
+            }
+            const int fb = kt * WK + kb;
+            if (checking && ic_local) {
+                if (bad(sum[0], chk[0]) || bad(sum[1], chk[1]) || bad(sum[2], chk[2]) || bad(sum[3], chk[3]))
+                    my_flag |= (fb < p.kblk) ? 2u : 4u;
+            } else {
+                int *dst = p.ws_ic + ((((long long)pg * p.grid_n + kt) * p.grid_b + nt) * 2 * WK + kb) * 256 + lane * 4;
+                st_dev4(dst, __builtin_bit_cast(i32x4, sum));
+                st_dev4(dst + WK * 256, __builtin_bit_cast(i32x4, chk));
+            }
+        }
+        if (!checking) return;
+        // (5) flags; sums that span several tiles are finished by the workgroup that arrives last
+        if (my_flag) atomicOr(reinterpret_cast<unsigned *>(&e_misc[0]), my_flag);
+        __syncthreads();
+        const long long word = ((long long)pg * p.grid_b + nt) * p.grid_n + kt;
+        if (tid == 0) __hip_atomic_store(&p.flags[word], (uint32_t)e_misc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (fc_local && ic_local) return;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (tid == 0) {
+            if (!fc_local)
+                e_misc[1] = __hip_atomic_fetch_add(&p.cnt_fc[pg * p.grid_b + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_n - 1);
+            if (!ic_local)
+                e_misc[2] = __hip_atomic_fetch_add(&p.cnt_ic[pg * p.grid_n + kt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_b - 1);
+        }
+        __syncthreads();
+        if (e_misc[1]) {
+            uint32_t late = 0;
+            for (int r = tid; r < MB * 16; r += 256) {
+                float sum = 0.f, chk = 0.f;
+                for (int c = 0; c < p.grid_n; ++c) {
+                    const int *src = &p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + c) * (2 * MB * 16) + r];
+                    sum += __builtin_bit_cast(float, ld_dev(src));
+                    chk += __builtin_bit_cast(float, ld_dev(src + MB * 16));
+                }
+                if (bad(sum, chk)) late |= (nt * MB + (r >> 4) < p.N) ? 1u : 4u;
+            }
+            if (late) __hip_atomic_fetch_or(&p.flags[((long long)pg * p.grid_b + nt) * p.grid_n], late, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (tid == 0) __hip_atomic_store(&p.cnt_fc[pg * p.grid_b + nt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (e_misc[2]) {
+            uint32_t late = 0;
+            for (int idx = tid; idx < WK * 64; idx += 256) {
+                const int kb = idx >> 6, ln = idx & 63;
+                const int fb = kt * WK + kb;
+                f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
+                for (int b = 0; b < p.grid_b; ++b) {
+                    const int *src = p.ws_ic + ((((long long)pg * p.grid_n + kt) * p.grid_b + b) * 2 * WK + kb) * 256 + ln * 4;
+                    sum += __builtin_bit_cast(f32x4, ld_dev4(src));
+                    chk += __builtin_bit_cast(f32x4, ld_dev4(src + WK * 256));
+                }
+                if (bad(sum[0], chk[0]) || bad(sum[1], chk[1]) || bad(sum[2], chk[2]) || bad(sum[3], chk[3]))
+                    late |= (fb < p.kblk) ? 2u : 4u;
+            }
+            if (late) __hip_atomic_fetch_or(&p.flags[((long long)pg * p.grid_b) * p.grid_n + kt], late, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (tid == 0) __hip_atomic_store(&p.cnt_ic[pg * p.grid_n + kt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    } else {
+    // ---------------- epilogue, int8 data ----------------
     const int pix = pg * 16 + lj;                // output pixel of this lane
     const bool pvalid = pix < PQ;
     int *e_ic = reinterpret_cast<int *>(lds);                 // [4 waves][WK][64 lanes][4]
@@ -501,6 +678,7 @@ __global__ __launch_bounds__(256) void conv_i8_kernel(const ConvParams p)
         if (late) __hip_atomic_fetch_or(&p.flags[((long long)pg * p.grid_b) * p.grid_n + kt], late, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (tid == 0) __hip_atomic_store(&p.cnt_ic[pg * p.grid_n + kt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    }  // int8 epilogue
 }
 
 }  // namespace abed

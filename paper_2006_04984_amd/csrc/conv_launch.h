@@ -13,12 +13,12 @@ static const int kWkList[] = {1, 4, 5, 8, 9};
 constexpr int kStages = 3;
 
 // Returns false if (wm, wk) is not a compiled configuration.
-bool launch_conv_i8(int wm, int wk, const ConvParams &p, int grid, hipStream_t st);
+bool launch_conv(bool f16, int wm, int wk, const ConvParams &p, int grid, hipStream_t st);
 
-bool launch_conv_i8_wk1(int wm, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_i8_wk4(int wm, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_i8_wk5(int wm, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_i8_wk8(int wm, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_i8_wk9(int wm, const ConvParams &p, int grid, hipStream_t st);
+bool launch_conv_wk1(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
+bool launch_conv_wk4(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
+bool launch_conv_wk5(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
+bool launch_conv_wk8(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
+bool launch_conv_wk9(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
 
 }  // namespace abed

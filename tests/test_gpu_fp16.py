@@ -1,0 +1,142 @@
+"""GPU parity for the fp16 path (Sec. 7): outputs against the double-precision oracle within
+1e-2 relative / 1e-3 absolute; flags against the oracle's threshold test wherever the oracle's
+margin is outside a guard band (the kernel sums in fp32 in its own order, so inside the band
+either answer is right)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2006_04984_amd as abed
+from synth import ConvShape, CONFIG4, fp16_tensors
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+SHAPES = [ConvShape(16, 9, 9, 32, 64, 3, 3, 1, 1, 1, 1, "n16_c32_k64_9x9"),
+          ConvShape(5, 7, 6, 16, 48, 3, 3, 2, 2, 1, 1, "n5_k48_stride2"),
+          ConvShape(40, 5, 5, 64, 144, 1, 1, 1, 1, 0, 0, "n40_1x1_k144_split"),
+          ConvShape(3, 10, 8, 8, 16, 3, 2, 1, 2, 1, 0, "n3_asym_c8")]
+
+
+class GpuConv16:
+    def __init__(self, s, variant, out_fp32=False):
+        self.s, self.variant, self.out_fp32 = s, variant, out_fp32
+        self.desc = abed.desc_from_shape(s)
+        self.lay = abed.get_layout(self.desc, 1, variant)
+        self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.float32 if out_fp32 else torch.float16, device=DEV)
+        self.y2 = torch.empty_like(self.y) if variant == 6 else None
+        self.flags = torch.full((max(1, self.lay.n_flag_words),), -1, dtype=torch.int32, device=DEV)
+        self.ws = torch.zeros((max(256, self.lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
+        abed.workspace_init(self.ws)
+        self.wchk = torch.empty((2, s.R, s.S, s.C), dtype=torch.float16, device=DEV)
+        self.xchk = torch.empty((2, s.H, s.W, s.C), dtype=torch.float16, device=DEV)
+
+    def prepare(self, w):
+        self.w = torch.from_numpy(w).to(DEV)
+        abed.filter_prepare_fp16(self.desc, self.w, self.wchk)
+
+    def run(self, x, rtol=1e-3, atol=1e-3, compute_xchk=True, inject=None):
+        self.x = x if torch.is_tensor(x) else torch.from_numpy(x).to(DEV)
+        abed.conv_fp16(self.desc, self.x, self.w, self.wchk, self.xchk, compute_xchk, self.y, self.variant, rtol, atol,
+                       flags=self.flags, out_fp32=self.out_fp32, workspace=self.ws, inject=inject, y2=self.y2)
+        torch.cuda.synchronize()
+        return self.y.cpu().numpy(), self.flags.cpu().numpy().view(np.uint32)[: self.lay.n_flag_words]
+
+
+def fold_margin(res, s, lay, thresh):
+    """Flag words expected if every check whose oracle margin exceeds `thresh` fires."""
+    PQ = s.P * s.Q
+    out = np.zeros((lay.grid_m, lay.grid_b, lay.grid_n), dtype=np.uint32)
+    fc = (~(res["fc_margin"] <= thresh)).reshape(s.N, PQ)
+    ic = (~(res["ic_margin"] <= thresh)).reshape(PQ, s.K)
+    for tm in range(lay.grid_m):
+        lo, hi = tm * 16, min(PQ, tm * 16 + 16)
+        for tb in range(lay.grid_b):
+            if fc[tb * lay.tile_batch:(tb + 1) * lay.tile_batch, lo:hi].any():
+                out[tm, tb, 0] |= 1
+        for tn in range(lay.grid_n):
+            if ic[lo:hi, tn * lay.tile_n:(tn + 1) * lay.tile_n].any():
+                out[tm, 0, tn] |= 2
+    return out
+
+
+def check_outputs(y, ref):
+    exact = ref["y_exact"]
+    err = np.abs(y.astype(np.float64) - exact)
+    assert np.all(err <= 1e-2 * np.abs(exact) + 1e-3), float(err.max())
+
+
+@pytest.mark.parametrize("out_fp32", [False, True])
+@pytest.mark.parametrize("variant", [0, 4, 6])
+@pytest.mark.parametrize("s", SHAPES, ids=lambda s: s.name)
+def test_fp16_clean(oracle, s, variant, out_fp32):
+    print("case", s.name, variant, out_fp32, flush=True)
+    x, w = fp16_tensors(s, 6161)
+    g = GpuConv16(s, variant, out_fp32)
+    g.prepare(w)
+    y, flags = g.run(x, rtol=1e-3, atol=1e-2)
+    wchk, xchk = g.wchk.cpu().numpy(), g.xchk.cpu().numpy()
+    ref = oracle.abed_fp16(x, w, s, 1e-3, 1e-2, wchk=wchk if variant == 4 else None, xchk=xchk if variant == 4 else None)
+    check_outputs(y, ref)
+    if variant == 4:
+        # the checksum tensors themselves: hi + lo reproduces the sums to fp32 accuracy
+        wsum = w.astype(np.float64).sum(0)
+        xsum = x.astype(np.float64).sum(0)
+        assert np.all(np.abs(wchk.astype(np.float64).sum(0) - wsum) <= 2.0 ** -20 * np.abs(wsum) + 2.0 ** -24)
+        assert np.all(np.abs(xchk.astype(np.float64).sum(0) - xsum) <= 2.0 ** -18 * np.abs(xsum) + 1e-6)
+        assert ref["fc_margin"].max() < -5e-3 and ref["ic_margin"].max() < -5e-3
+        assert not flags.any()
+    if variant == 6:
+        assert flags[0] == 0 and torch.equal(g.y, g.y2)
+
+
+@pytest.mark.parametrize("s", [SHAPES[0], SHAPES[2]], ids=lambda s: s.name)
+def test_fp16_flip_detection_and_threshold(oracle, s):
+    """Flips of one output bit: those the oracle puts clearly above the threshold must be flagged in
+    the right tile, those clearly below must not."""
+    x, w = fp16_tensors(s, 6262)
+    g = GpuConv16(s, 4)
+    g.prepare(w)
+    g.run(x)
+    wchk, xchk = g.wchk.cpu().numpy(), g.xchk.cpu().numpy()
+    rng = np.random.default_rng(11)
+    rtol, atol = 1e-3, 1e-2
+    decided = 0
+    for trial in range(24):
+        idx = int(rng.integers(0, s.N * s.P * s.Q * s.K))
+        bit = int(rng.integers(0, 16))
+        print("flip", s.name, idx, bit, flush=True)
+        y, flags = g.run(x, rtol, atol, compute_xchk=False, inject=(1, idx, bit))
+        ref = oracle.abed_fp16(x, w, s, rtol, atol, wchk=wchk, xchk=xchk, acc_flip=(idx, bit))
+        f = flags.reshape(g.lay.grid_m, g.lay.grid_b, g.lay.grid_n) & 3
+        must = fold_margin(ref, s, g.lay, 2e-3)
+        may = fold_margin(ref, s, g.lay, -2e-3)
+        assert np.all((f & must) == must), "a flip above the threshold was missed"
+        assert np.all((f & ~may) == 0), "a flag without a mismatch"
+        decided += int(np.array_equal(must, may))
+    assert decided >= 12
+
+
+def test_fp16_config4_shape_sampled(oracle):
+    """The fp16 layer of the benchmark configuration at full size: sampled outputs against the
+    oracle's single-element routine, and no flag on a clean run with a sensible absolute floor."""
+    s = CONFIG4[0]
+    x, w = fp16_tensors(s, 4000)
+    g = GpuConv16(s, 4)
+    g.prepare(w)
+    y, flags = g.run(x, rtol=1e-3, atol=2e-2)
+    assert not flags.any()
+    rng = np.random.default_rng(3)
+    pts = np.stack([rng.integers(0, d, 64) for d in (s.N, s.P, s.Q, s.K)], axis=1)
+    xs = np.ascontiguousarray(x[:, :, :, :], dtype=np.float64)
+    exact = np.empty(len(pts))
+    for e, (n, p, q, k) in enumerate(pts):
+        acc = 0.0
+        for r in range(3):
+            for c in range(3):
+                h, v = p - 1 + r, q - 1 + c
+                if 0 <= h < s.H and 0 <= v < s.W:
+                    acc += float(xs[n, h, v] @ w[k, r, c].astype(np.float64))
+        exact[e] = acc
+    got = y[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64)
+    assert np.all(np.abs(got - exact) <= 1e-2 * np.abs(exact) + 1e-3)
