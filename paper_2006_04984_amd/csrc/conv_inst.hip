@@ -13,8 +13,8 @@ namespace abed {
 template <int WM>
 static void go(bool f16, const ConvParams &p, int grid, hipStream_t st)
 {
-    if (f16) conv_kernel<true, WM, INST_WK, kStages><<<dim3(grid), dim3(256), 0, st>>>(p);
-    else conv_kernel<false, WM, INST_WK, kStages><<<dim3(grid), dim3(256), 0, st>>>(p);
+    if (f16) conv_kernel<true, WM, INST_WK, stages_for(WM, INST_WK)><<<dim3(grid), dim3(256), 0, st>>>(p);
+    else conv_kernel<false, WM, INST_WK, stages_for(WM, INST_WK)><<<dim3(grid), dim3(256), 0, st>>>(p);
 }
 
 bool CAT(launch_conv_wk, INST_WK)(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st)

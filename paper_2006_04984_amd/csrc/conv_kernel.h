@@ -24,8 +24,9 @@
 // because all entries of a tile share the same 16 pixels in the same lanes.
 // Wave w owns entries [w*WM, (w+1)*WM) of the tile and all WK filter blocks.
 //
-// Operands reach LDS by direct global->LDS loads (no staging registers), NST
-// stages deep; out-of-image taps and out-of-range rows read a zero page.
+// Operands reach LDS by direct global->LDS buffer loads (no staging registers), NST
+// stages deep; out-of-image taps and out-of-range rows are masked by the buffer
+// descriptor's range check.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -78,20 +79,10 @@ struct ConvParams {
     float rtol, atol;  // fp16 path: threshold of the checks
 };
 
-// 64 bytes of zeros: the source of every masked 16-byte chunk
-__device__ __attribute__((aligned(64))) const int8_t g_zero_page[64] = {0};
-
 __device__ __forceinline__ int lds_off(int row, int chunk)
 {
     // 64-byte rows; the 16-byte chunk position is swizzled with bits 2..3 of the row
     return row * 64 + (((chunk ^ (row >> 2)) & 3) << 4);
-}
-
-__device__ __forceinline__ void dma16(const int8_t *gptr, int8_t *lds_wave_base)
-{
-    // each lane's 16 bytes land at lds_wave_base + 16 * lane
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gptr,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
@@ -139,6 +130,7 @@ __device__ __forceinline__ int next_digit(int &s)
 template <bool F16, int WM, int WK, int NST>
 __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
 {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass needs the signature only (the body uses device-only types)
     using acc_t = typename std::conditional<F16, f32x4, i32x4>::type;
     constexpr int MB = 4 * WM;                 // batch entries per tile
     constexpr int NB = WK + MB;                // 1 KB blocks per stage: filter blocks, then entry blocks
@@ -165,67 +157,92 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
     const long long HWC = (long long)p.H * p.W * p.cb;      // bytes of one image
 
     // ---------------- loader set-up ----------------
-    // In a 1 KB block lane l fills row l>>2, chunk position l&3.
+    // Operands are fetched with buffer loads straight into LDS: a buffer descriptor per tensor (scalar
+    // registers), a per-lane byte offset, and a scalar byte offset per block.  An offset at or beyond
+    // the descriptor's size reads as zero, which is how padding taps, rows past K or N and the tail of
+    // the reduction axis are masked.  In a 1 KB block lane l fills row l>>2, chunk position l&3.
+    constexpr int OOB = 0x7ffffff0;             // never below a descriptor's size (sizes are < 2^31 - 16)
     const int ld_row = lane >> 2;
     const int ld_chunk = (lane & 3) ^ ((ld_row >> 2) & 3);   // which 16 bytes of the 64-byte step this lane fetches
-    const int8_t *zero = g_zero_page;
+    const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.N * (int)HWC, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_xc = __builtin_amdgcn_make_buffer_rsrc((void *)p.xchk, 0, p.xchk ? p.d_i * (int)HWC : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, p.K * p.crsb, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_wc = __builtin_amdgcn_make_buffer_rsrc((void *)p.wchk, 0, p.wchk ? p.d_f * p.crsb : 0, 0x00020000);
     // pixel of this lane's row (the same for every entry block)
     int h0 = INT_MIN / 2, w0 = 0;
-    long long pix_off = 0;
     {
         const int pix = pg * 16 + ld_row;
         if (pix < PQ) {
             const int pp = pix / p.Q, qq = pix - pp * p.Q;
             h0 = pp * p.sh - p.ph;
             w0 = qq * p.sw - p.pw;
-            pix_off = ((long long)h0 * p.W + w0) * p.cb;
         }
     }
-    // the L blocks this wave loads each step: block b = wave + 4 i (clamped: a duplicate load is harmless)
-    const int8_t *blk_base[L];   // per lane: filter row base, or entry base (wave-uniform), or null
-    bool blk_is_filter[L];
+    const int lane_base = (h0 * p.W + w0) * p.cb + ld_chunk * 16;   // byte offset of tap (0,0), channel chunk of this lane
+    // the L blocks this wave loads each step: block b = wave + 4 i (clamped: a duplicate load is harmless).
+    // Everything about a block that does not change from step to step is settled here: its
+    // descriptor (a descriptor of size 0 masks a whole block), whether it is a filter block, the
+    // scalar offset of an entry block's image, the per-lane row offset of a filter block.
+    const __amdgpu_buffer_rsrc_t rs_none = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, 0, 0x00020000);
+    __amdgpu_buffer_rsrc_t blk_rs[L];
+    bool blk_filter[L];   // wave-uniform
+    int blk_soff[L];      // wave-uniform scalar byte offset (entry blocks: the image)
+    int blk_voff[L];      // per-lane byte offset of the row at step 0 (filter blocks), or OOB
 #pragma unroll
     for (int i = 0; i < L; ++i) {
         int b = wave + 4 * i;
         if (b > NB - 1) b = NB - 1;
-        blk_is_filter[i] = b < WK;
-        blk_base[i] = nullptr;
+        blk_rs[i] = rs_none; blk_soff[i] = 0; blk_voff[i] = OOB;
+        blk_filter[i] = b < WK;
         if (b < WK) {
             const int fb = kt * WK + b;                       // global filter block
             const int f = fb * 16 + ld_row;
-            if (fb < p.kblk) { if (f < p.K) blk_base[i] = p.w + (long long)f * p.crsb; }
-            else if (fb == p.kblk && fb < p.n_fblk) { if (ld_row < p.d_f) blk_base[i] = p.wchk + (long long)ld_row * p.crsb; }
+            if (fb < p.kblk) { blk_rs[i] = rs_w; if (f < p.K) blk_voff[i] = f * p.crsb + ld_chunk * 16; }
+            else if (fb == p.kblk && fb < p.n_fblk) { blk_rs[i] = rs_wc; if (ld_row < p.d_f) blk_voff[i] = ld_row * p.crsb + ld_chunk * 16; }
         } else {
             const int e = nt * MB + (b - WK);
-            if (e < p.N) blk_base[i] = p.x + e * HWC;
-            else if (e < p.n_entries) blk_base[i] = p.xchk + (e - p.N) * HWC;
+            if (e < p.N) { blk_rs[i] = rs_x; blk_soff[i] = e * (int)HWC; }
+            else if (e < p.n_entries) { blk_rs[i] = rs_xc; blk_soff[i] = (e - p.N) * (int)HWC; }
         }
     }
 
-    // position of this lane's chunk on the crs axis
-    int crs_pos = ld_chunk * 16;                // byte position
+    // position on the reduction axis (bytes).  When a tap's bytes are a multiple of 64 every chunk of
+    // a step lies in the same tap and the tap is tracked in scalar registers; otherwise per lane.
+    const bool utap = (p.cb & 63) == 0;
+    int s_pos = 0, s_r = 0, s_s = 0, s_ch = 0;              // uniform: start of the step
+    int crs_pos = ld_chunk * 16;                             // per lane
     int tap_r = 0, tap_s = 0, ch = crs_pos;
-    while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
+    if (!utap)
+        while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
 
     auto issue = [&](int stage) {
-        const bool in_crs = crs_pos < p.crsb;
-        const bool inb = in_crs && (unsigned)(h0 + tap_r) < (unsigned)p.H && (unsigned)(w0 + tap_s) < (unsigned)p.W;
-        const long long tap_off = pix_off + ((long long)tap_r * p.W + tap_s) * p.cb + ch;
+        int voff_x;            // per-lane offset of this step's chunk inside an image, or OOB
+        bool in_crs;           // this lane's chunk lies inside the reduction axis
+        if (utap) {
+            in_crs = s_pos < p.crsb;
+            const bool inb = in_crs && (unsigned)(h0 + s_r) < (unsigned)p.H && (unsigned)(w0 + s_s) < (unsigned)p.W;
+            voff_x = inb ? lane_base + (s_r * p.W + s_s) * p.cb + s_ch : OOB;
+            s_pos += 64; s_ch += 64;
+            if (s_ch >= p.cb) { s_ch = 0; if (++s_s == p.S) { s_s = 0; ++s_r; } }
+        } else {
+            in_crs = crs_pos < p.crsb;
+            const bool inb = in_crs && (unsigned)(h0 + tap_r) < (unsigned)p.H && (unsigned)(w0 + tap_s) < (unsigned)p.W;
+            voff_x = inb ? ((h0 + tap_r) * p.W + (w0 + tap_s)) * p.cb + ch : OOB;
+            ch += 64;
+            while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
+        }
+        const int step_off = crs_pos - ld_chunk * 16;        // 64 * step
+        crs_pos += 64;
         int8_t *sbase = lds + stage * STAGE;
 #pragma unroll
         for (int i = 0; i < L; ++i) {
             int b = wave + 4 * i;
             if (b > NB - 1) b = NB - 1;
-            const int8_t *src = zero;
-            if (blk_base[i] != nullptr) {
-                if (blk_is_filter[i]) { if (in_crs) src = blk_base[i] + crs_pos; }
-                else if (inb) src = blk_base[i] + tap_off;
-            }
-            dma16(src, sbase + b * 1024);
+            __attribute__((address_space(3))) void *dst = (__attribute__((address_space(3))) void *)(sbase + b * 1024);
+            const int voff_w = (in_crs && blk_voff[i] != OOB) ? blk_voff[i] + step_off : OOB;
+            const int voff = blk_filter[i] ? voff_w : voff_x;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(blk_rs[i], dst, 16, voff, blk_soff[i], 0, 0);
         }
-        crs_pos += 64;
-        ch += 64;
-        while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
     };
 
     // ---------------- accumulators ----------------
@@ -242,6 +259,7 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s) issue(s);
     int stage = 0;
+    const int rd_lane = lds_off(lj, lg);         // this lane's 16 bytes inside any 1 KB block
     if (p.dbg & 4) return;
     for (int step = 0; step < ((p.dbg & 2) ? 0 : p.nsteps); ++step) {
         ABED_WAIT_VMCNT((NST - 2) * L);          // this wave's loads of `step` have landed
@@ -251,15 +269,15 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
             if (st >= NST) st -= NST;
             issue(st);                           // refill the stage that step-1 used
         }
-        const int8_t *ldsK = lds + stage * STAGE;
-        const int8_t *ldsM = ldsK + WK * 1024;
+        const int8_t *ldsK = lds + stage * STAGE + rd_lane;          // + 1024 * filter block
+        const int8_t *ldsM = ldsK + (WK + wave * WM) * 1024;         // + 1024 * entry of this wave
         i32x4 bfr[WM];
 #pragma unroll
         for (int i = 0; i < WM; ++i)
-            bfr[i] = *reinterpret_cast<const i32x4 *>(ldsM + lds_off((wave * WM + i) * 16 + lj, lg));
+            bfr[i] = *reinterpret_cast<const i32x4 *>(ldsM + i * 1024);
 #pragma unroll
         for (int kb = 0; kb < WK; ++kb) {
-            const i32x4 a = *reinterpret_cast<const i32x4 *>(ldsK + lds_off(kb * 16 + lj, lg));
+            const i32x4 a = *reinterpret_cast<const i32x4 *>(ldsK + kb * 1024);
 #pragma unroll
             for (int i = 0; i < WM; ++i)
                 if constexpr (F16)
@@ -679,6 +697,7 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
         if (tid == 0) __hip_atomic_store(&p.cnt_ic[pg * p.grid_n + kt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     }  // int8 epilogue
+#endif
 }
 
 }  // namespace abed
