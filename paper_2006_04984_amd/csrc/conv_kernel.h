@@ -81,8 +81,10 @@ struct ConvParams {
 
 __device__ __forceinline__ int lds_off(int row, int chunk)
 {
-    // 64-byte rows; the 16-byte chunk position is swizzled with bits 2..3 of the row
-    return row * 64 + (((chunk ^ (row >> 2)) & 3) << 4);
+    // 64-byte rows; the 16-byte chunk position is swizzled with bits 1..2 of the row, so that the 8
+    // lanes a 16-byte-per-lane LDS read serves per cycle (8 consecutive rows, same chunk) fall into
+    // 8 different 16-byte slots of the 128-byte bank window
+    return row * 64 + (((chunk ^ (row >> 1)) & 3) << 4);
 }
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding:
@@ -163,7 +165,7 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
     // the reduction axis are masked.  In a 1 KB block lane l fills row l>>2, chunk position l&3.
     constexpr int OOB = 0x7ffffff0;             // never below a descriptor's size (sizes are < 2^31 - 16)
     const int ld_row = lane >> 2;
-    const int ld_chunk = (lane & 3) ^ ((ld_row >> 2) & 3);   // which 16 bytes of the 64-byte step this lane fetches
+    const int ld_chunk = (lane & 3) ^ ((ld_row >> 1) & 3);   // which 16 bytes of the 64-byte step this lane fetches
     const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.N * (int)HWC, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_xc = __builtin_amdgcn_make_buffer_rsrc((void *)p.xchk, 0, p.xchk ? p.d_i * (int)HWC : 0, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, p.K * p.crsb, 0x00020000);
@@ -206,43 +208,58 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
         }
     }
 
-    // position on the reduction axis (bytes).  When a tap's bytes are a multiple of 64 every chunk of
-    // a step lies in the same tap and the tap is tracked in scalar registers; otherwise per lane.
-    const bool utap = (p.cb & 63) == 0;
-    int s_pos = 0, s_r = 0, s_s = 0, s_ch = 0;              // uniform: start of the step
-    int crs_pos = ld_chunk * 16;                             // per lane
-    int tap_r = 0, tap_s = 0, ch = crs_pos;
+    // Position on the reduction axis (bytes).  Fast path: when a tap's bytes are a multiple of 64
+    // (and the filter has at most 64 taps) every chunk of a step lies in one tap, so the tap, the
+    // byte offset of the step inside an image and the step's offset inside a filter row live in
+    // scalar registers, and each lane only keeps a bit mask of the taps that fall inside the image
+    // for its pixel.  Otherwise the tap is tracked per lane.
+    const bool utap = (p.cb & 63) == 0 && p.R * p.S <= 64;
+    unsigned mask_lo = 0, mask_hi = 0;                       // per lane: bit t set = tap t is inside the image
+    if (utap) {
+        int t = 0;
+        for (int r = 0; r < p.R; ++r)
+            for (int c = 0; c < p.S; ++c, ++t) {
+                const unsigned ok = ((unsigned)(h0 + r) < (unsigned)p.H && (unsigned)(w0 + c) < (unsigned)p.W) ? 1u : 0u;
+                if (t < 32) mask_lo |= ok << t; else mask_hi |= ok << (t - 32);
+            }
+    }
+    int s_step = 0;                                          // uniform: 64 * step
+    int s_off = 0, s_ch = 0, s_tap = 0, s_col = 0;           // uniform (fast path): offset in the image, channel byte, tap, tap column
+    const int row_jump = (p.W - p.S) * p.cb;                 // extra offset when the tap moves to the next filter row
+    int tap_r = 0, tap_s = 0, ch = ld_chunk * 16;            // per lane (slow path)
     if (!utap)
         while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
 
     auto issue = [&](int stage) {
         int voff_x;            // per-lane offset of this step's chunk inside an image, or OOB
-        bool in_crs;           // this lane's chunk lies inside the reduction axis
+        const bool live = s_step < p.crsb;                   // uniform: the step starts inside the reduction axis
+        bool in_crs = live;    // this lane's chunk lies inside the reduction axis
         if (utap) {
-            in_crs = s_pos < p.crsb;
-            const bool inb = in_crs && (unsigned)(h0 + s_r) < (unsigned)p.H && (unsigned)(w0 + s_s) < (unsigned)p.W;
-            voff_x = inb ? lane_base + (s_r * p.W + s_s) * p.cb + s_ch : OOB;
-            s_pos += 64; s_ch += 64;
-            if (s_ch >= p.cb) { s_ch = 0; if (++s_s == p.S) { s_s = 0; ++s_r; } }
+            const unsigned m = (s_tap & 32) ? mask_hi : mask_lo;
+            const bool inb = live && ((m >> (s_tap & 31)) & 1u);
+            voff_x = inb ? lane_base + s_off : OOB;
+            s_off += 64; s_ch += 64;
+            if (s_ch == p.cb) { s_ch = 0; ++s_tap; if (++s_col == p.S) { s_col = 0; s_off += row_jump; } }
         } else {
-            in_crs = crs_pos < p.crsb;
+            in_crs = s_step + ld_chunk * 16 < p.crsb;
             const bool inb = in_crs && (unsigned)(h0 + tap_r) < (unsigned)p.H && (unsigned)(w0 + tap_s) < (unsigned)p.W;
             voff_x = inb ? ((h0 + tap_r) * p.W + (w0 + tap_s)) * p.cb + ch : OOB;
             ch += 64;
             while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
         }
-        const int step_off = crs_pos - ld_chunk * 16;        // 64 * step
-        crs_pos += 64;
         int8_t *sbase = lds + stage * STAGE;
 #pragma unroll
         for (int i = 0; i < L; ++i) {
             int b = wave + 4 * i;
             if (b > NB - 1) b = NB - 1;
             __attribute__((address_space(3))) void *dst = (__attribute__((address_space(3))) void *)(sbase + b * 1024);
-            const int voff_w = (in_crs && blk_voff[i] != OOB) ? blk_voff[i] + step_off : OOB;
-            const int voff = blk_filter[i] ? voff_w : voff_x;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(blk_rs[i], dst, 16, voff, blk_soff[i], 0, 0);
+            // filter rows: constant per-lane row offset, the step in the scalar offset (the range check
+            // looks at the per-lane offset only, so a step past the end is masked explicitly)
+            const int voff = blk_filter[i] ? (in_crs ? blk_voff[i] : OOB) : voff_x;
+            const int soff = blk_filter[i] ? s_step : blk_soff[i];
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(blk_rs[i], dst, 16, voff, soff, 0, 0);
         }
+        s_step += 64;
     };
 
     // ---------------- accumulators ----------------
