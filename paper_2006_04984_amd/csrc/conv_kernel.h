@@ -107,14 +107,15 @@ __device__ __forceinline__ int requant(int acc, float sc, float bi, int relu)
 // before the arrival counter is bumped.
 __device__ __forceinline__ void st_dev(int *p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ int ld_dev(const int *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+// 16-byte versions: one write-through store / cache-bypassing load (device scope) per lane
 __device__ __forceinline__ void st_dev4(int *p, i32x4 v)
 {
-    st_dev(p, v[0]); st_dev(p + 1, v[1]); st_dev(p + 2, v[2]); st_dev(p + 3, v[3]);
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ i32x4 ld_dev4(const int *p)
 {
     i32x4 v;
-    v[0] = ld_dev(p); v[1] = ld_dev(p + 1); v[2] = ld_dev(p + 2); v[3] = ld_dev(p + 3);
+    asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
     return v;
 }
 
