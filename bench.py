@@ -23,6 +23,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA peak, TOP/s
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the checked convolution kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs scaled by a copy of known size (profiles/conv_int8_checked_config2.md); None where not measured.
+MEASURED_TRAFFIC_BYTES = {"3x3_c64_56": 36.3e6 + 39.0e6, "3x3_c512_7": 35.8e6 + 5.0e6}
 
 
 def main():
@@ -175,7 +178,8 @@ def main():
     achieved = dom_shape.ops / (dom["checked_conv_us"] * 1e-6) / 1e12
     roofline = dict(bound="mfma", kernel="conv_i8_kernel (augmented) on " + dom["layer"], achieved=achieved,
                     peak=PEAK_INT8_TOPS, unit="TFLOP/s", op="int8 multiply-add counted as 2 ops",
-                    frac=achieved / PEAK_INT8_TOPS, traffic=None,
+                    frac=achieved / PEAK_INT8_TOPS, traffic=MEASURED_TRAFFIC_BYTES.get(dom["layer"]),
+                    algorithmic_bytes=dom["min_bytes_i32"],
                     ops_per_launch=dom_shape.ops, avg_launch_us=dom["checked_conv_us"])
 
     out = dict(metric="checked conv TOPS (int8) and ABED overhead % vs unchecked and vs duplication",

@@ -262,7 +262,7 @@ abed_status_t abed_input_checksum_int8(const abed_conv_desc_t *desc, const int8_
     if (!x || !xchk) return ABED_EINVAL;
     const long long hwc = (long long)desc->H * desc->W * desc->C;
     const long long chunks = hwc / 16;
-    batch_checksum_i8_kernel<<<dim3((unsigned)((chunks + 63) / 64)), dim3(256), 0, (hipStream_t)stream>>>(x, xchk, desc->N, hwc, pl.d_i);
+    batch_checksum_i8_kernel<<<dim3((unsigned)((chunks + 31) / 32)), dim3(256), 0, (hipStream_t)stream>>>(x, xchk, desc->N, hwc, pl.d_i);
     LAUNCH_CHECK("batch_checksum_i8_kernel");
     return ABED_OK;
 }

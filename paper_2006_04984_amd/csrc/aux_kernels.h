@@ -29,33 +29,41 @@ __global__ void filter_checksum_i8_kernel(const int8_t *w, int8_t *wchk, int K, 
     for (int d = 0; d < d_f; ++d) wchk[(long long)d * crs + e] = (int8_t)take_digit(s);
 }
 
-// xsum[e] = sum_n x[n][e] for 16 consecutive elements per thread group of 4 lanes
-// (each lane sums a quarter of the images); digits to xchk[d][e].
+// xsum[e] = sum_n x[n][e] for 16 consecutive elements per group of 8 lanes (each lane sums an
+// eighth of the images, with all its loads in flight at once); digits to xchk[d][e].
 __global__ __launch_bounds__(256) void batch_checksum_i8_kernel(const int8_t *x, int8_t *xchk, int N, long long hwc, int d_i)
 {
-    const long long chunk = (long long)blockIdx.x * 64 + (threadIdx.x >> 2);
-    const int part = threadIdx.x & 3;
+    const long long chunk = (long long)blockIdx.x * 32 + (threadIdx.x >> 3);
+    const int part = threadIdx.x & 7;
     const long long e0 = chunk * 16;
     const bool live = e0 < hwc;
     int s[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = 0;
     if (live) {
-        for (int n = part; n < N; n += 4) {
-            const i32x4a v = *reinterpret_cast<const i32x4a *>(x + n * hwc + e0);
+        for (int n0 = part; n0 < N; n0 += 32) {
+            i32x4a v[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                s[4 * j + 0] += (v[j] << 24) >> 24;
-                s[4 * j + 1] += (v[j] << 16) >> 24;
-                s[4 * j + 2] += (v[j] << 8) >> 24;
-                s[4 * j + 3] += v[j] >> 24;
+            for (int u = 0; u < 4; ++u) {
+                const int n = n0 + 8 * u;
+                v[u] = n < N ? *reinterpret_cast<const i32x4a *>(x + n * hwc + e0) : i32x4a{0, 0, 0, 0};
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    s[4 * j + 0] += (v[u][j] << 24) >> 24;
+                    s[4 * j + 1] += (v[u][j] << 16) >> 24;
+                    s[4 * j + 2] += (v[u][j] << 8) >> 24;
+                    s[4 * j + 3] += v[u][j] >> 24;
+                }
         }
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         s[i] += __shfl_xor(s[i], 1, 64);
         s[i] += __shfl_xor(s[i], 2, 64);
+        s[i] += __shfl_xor(s[i], 4, 64);
     }
     if (live && part == 0) {
         for (int d = 0; d < d_i; ++d) {

@@ -1,0 +1,247 @@
+"""Evaluation runs on one GPU, beside bench.py (which covers the headline 3x3 configuration):
+
+  python -m paper_2006_04984_amd.evaluate layers   --config 3      per-layer table of a configuration
+  python -m paper_2006_04984_amd.evaluate fp16                      false-positive / detection rates (fp16 layer)
+  python -m paper_2006_04984_amd.evaluate detect                    int8 single-bit detection rates
+  python -m paper_2006_04984_amd.evaluate resnet50 --batch 128      the 53 convolution layers back to back
+
+All inputs are seeded and synthetic (synth/).  Each command prints one JSON object.
+Times are GPU times of HIP-graph replays measured with events on the launch stream.
+"""
+import argparse
+import json
+import sys
+
+import numpy as np
+import torch
+
+from . import binding as abed
+from .binding import Variant
+
+DEV = "cuda:0"
+PEAK_HBM_GBS = 8000.0
+
+
+def _graph_time(fn, stream, reps=20, replays=10):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(stream):
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for _ in range(reps):
+                fn()
+        g.replay()
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for _ in range(replays):
+            g.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / (reps * replays)
+
+
+class Int8Layer:
+    """Device buffers of one int8 convolution and a call closure per variant."""
+
+    def __init__(self, s, seed, variant, epilogue=False, x=None):
+        from synth import int8_tensors, requant_params
+        self.s, self.variant = s, Variant(variant)
+        self.desc = abed.desc_from_shape(s)
+        self.lay = abed.get_layout(self.desc, 0, self.variant)
+        xh, wh = int8_tensors(s, seed)
+        self.x = torch.from_numpy(xh).to(DEV) if x is None else x
+        self.w = torch.from_numpy(wh).to(DEV)
+        self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int8 if epilogue else torch.int32, device=DEV)
+        self.y2 = torch.empty_like(self.y) if self.variant == Variant.DUPLICATE else None
+        self.flags = torch.zeros((max(1, self.lay.n_flag_words),), dtype=torch.int32, device=DEV)
+        self.ws = torch.zeros((max(256, self.lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
+        self.wchk = torch.empty((self.lay.d_f, s.R, s.S, s.C), dtype=torch.int8, device=DEV)
+        self.xchk = torch.empty((self.lay.d_i, s.H, s.W, s.C), dtype=torch.int8, device=DEV)
+        self.xchk_next = torch.empty((self.lay.d_i, s.P, s.Q, s.K), dtype=torch.int8, device=DEV) if epilogue else None
+        self.epi = None
+        if epilogue:
+            sc, bi = requant_params(s, seed)
+            self.scale, self.bias = torch.from_numpy(sc).to(DEV), torch.from_numpy(bi).to(DEV)
+            self.epi = (self.scale, self.bias, True)
+        abed.workspace_init(self.ws)
+        abed.filter_prepare_int8(self.desc, self.w, self.wchk)
+
+    def run(self, compute_xchk=True, inject=None):
+        abed.conv_int8(self.desc, self.x, self.w, self.wchk, self.xchk, compute_xchk, self.y, self.variant,
+                       flags=self.flags, epilogue=self.epi, xchk_next=self.xchk_next, workspace=self.ws,
+                       inject=inject, y2=self.y2)
+
+
+def cmd_layers(args):
+    from synth import CONFIG2, CONFIG3, seed_for
+    layers = {2: CONFIG2, 3: CONFIG3}[args.config]
+    stream = torch.cuda.Stream()
+    rows = []
+    for i, s in enumerate(layers):
+        row = dict(layer=s.name, gop=s.ops / 1e9)
+        for epi in (False, True):
+            tag = "i8out" if epi else "i32out"
+            t = {}
+            for v in (Variant.NONE, Variant.FUSED_OCG, Variant.DUPLICATE):
+                L = Int8Layer(s, seed_for(args.config, i), v, epilogue=epi)
+                L.run()
+                t[v] = _graph_time(lambda: L.run(), stream)
+                if v == Variant.FUSED_OCG:
+                    assert int(L.flags.abs().max().item()) == 0
+            nbytes = s.min_bytes(1, 1, 1 if epi else 4)
+            row[tag] = dict(unchecked_us=t[Variant.NONE] * 1e6, checked_us=t[Variant.FUSED_OCG] * 1e6,
+                            duplicate_us=t[Variant.DUPLICATE] * 1e6,
+                            unchecked_tops=s.ops / t[Variant.NONE] / 1e12, checked_tops=s.ops / t[Variant.FUSED_OCG] / 1e12,
+                            overhead_pct=100.0 * (t[Variant.FUSED_OCG] / t[Variant.NONE] - 1.0),
+                            min_bytes=nbytes, unchecked_hbm_gbs=nbytes / t[Variant.NONE] / 1e9,
+                            checked_hbm_gbs=nbytes / t[Variant.FUSED_OCG] / 1e9,
+                            unchecked_frac_of_hbm_peak=nbytes / t[Variant.NONE] / 1e9 / PEAK_HBM_GBS)
+        rows.append(row)
+    print(json.dumps(dict(config=args.config, note="checked = FusedOCG incl. the ICG kernel; GB/s = algorithmic minimum bytes / time",
+                          layers=rows)))
+
+
+def cmd_detect(args):
+    """Single-bit flips in accumulators, filters, inputs of an int8 layer (Sec. 5.4 campaigns)."""
+    from synth import ConvShape
+    s = ConvShape(32, 14, 14, 64, 64, 3, 3, 1, 1, 1, 1, "3x3_c64_14_n32")
+    L = Int8Layer(s, 7001, Variant.FUSED_OCG)
+    L.run()
+    torch.cuda.synchronize()
+    clean = L.y.clone()
+    rng = np.random.default_rng(args.seed)
+    out = {}
+    # accumulators
+    det = 0
+    for _ in range(args.trials):
+        idx, bit = int(rng.integers(0, clean.numel())), int(rng.integers(0, 32))
+        L.run(compute_xchk=False, inject=(1, idx, bit))
+        det += int(L.flags.abs().max().item() != 0)
+    out["accumulator"] = dict(trials=args.trials, detected=det)
+    for name, t in (("filter", L.w), ("input", L.x)):
+        det = corrupting = 0
+        u = t.view(torch.uint8).view(-1)
+        for _ in range(args.trials):
+            idx, bit = int(rng.integers(0, u.numel())), int(rng.integers(0, 8))
+            u[idx] ^= (1 << bit)
+            L.run(compute_xchk=False)
+            changed = not torch.equal(L.y, clean)
+            flagged = int(L.flags.abs().max().item()) != 0
+            corrupting += int(changed)
+            det += int(changed and flagged)
+            u[idx] ^= (1 << bit)
+        out[name] = dict(trials=args.trials, corrupting=corrupting, detected_of_corrupting=det)
+    fp = 0
+    for r in range(args.clean):
+        L2 = Int8Layer(s, 8000 + r, Variant.FUSED_OCG)
+        L2.run()
+        fp += int(L2.flags.abs().max().item() != 0)
+    out["clean_runs"] = dict(runs=args.clean, false_positives=fp)
+    print(json.dumps(out))
+
+
+def cmd_fp16(args):
+    from synth import CONFIG4, fp16_tensors, seed_for
+    s = CONFIG4[0]
+    desc = abed.desc_from_shape(s)
+    lay = abed.get_layout(desc, 1, Variant.FUSED_OCG)
+    y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.float16, device=DEV)
+    flags = torch.zeros((lay.n_flag_words,), dtype=torch.int32, device=DEV)
+    ws = torch.zeros((max(256, lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
+    wchk = torch.empty((2, s.R, s.S, s.C), dtype=torch.float16, device=DEV)
+    xchk = torch.empty((2, s.H, s.W, s.C), dtype=torch.float16, device=DEV)
+    abed.workspace_init(ws)
+    res = dict(layer=s.name, runs=args.trials, thresholds=[])
+    settings = [(1e-3, 0.0), (1e-3, 1e-3), (1e-3, 1e-2), (1e-3, 3e-2)]
+    clean_fp = {st: 0 for st in settings}
+    tiles_fp = {st: 0 for st in settings}
+    for r in range(args.trials):
+        xh, wh = fp16_tensors(s, seed_for(4, 0, r))
+        x, w = torch.from_numpy(xh).to(DEV), torch.from_numpy(wh).to(DEV)
+        abed.filter_prepare_fp16(desc, w, wchk)
+        for i, (rt, at) in enumerate(settings):
+            abed.conv_fp16(desc, x, w, wchk, xchk, i == 0, y, Variant.FUSED_OCG, rt, at, flags=flags, workspace=ws)
+            n = int((flags != 0).sum().item())
+            clean_fp[(rt, at)] += int(n > 0)
+            tiles_fp[(rt, at)] += n
+    # detection: flips of one bit of one fp16 output value, on the last input
+    rng = np.random.default_rng(args.seed)
+    det = {st: [0] * 16 for st in settings}
+    cnt = [0] * 16
+    for _ in range(args.trials):
+        idx, bit = int(rng.integers(0, y.numel())), int(rng.integers(0, 16))
+        cnt[bit] += 1
+        for (rt, at) in settings:
+            abed.conv_fp16(desc, x, w, wchk, xchk, False, y, Variant.FUSED_OCG, rt, at, flags=flags, workspace=ws,
+                           inject=(1, idx, bit))
+            det[(rt, at)][bit] += int((flags != 0).any().item())
+    for st in settings:
+        res["thresholds"].append(dict(rtol=st[0], atol=st[1], clean_runs_with_a_flag=clean_fp[st],
+                                      flagged_tiles_per_clean_run=tiles_fp[st] / args.trials,
+                                      tiles_per_run=int(lay.n_flag_words),
+                                      flips_detected=sum(det[st]), flips=args.trials,
+                                      detected_by_bit=det[st], flips_by_bit=cnt))
+    print(json.dumps(res))
+
+
+def cmd_resnet50(args):
+    """The 53 convolution layers of a ResNet-50-shaped network, int8 with a fused requantize + ReLU
+    epilog, back to back on one stream: unchecked, checked (variant 5: inside a bottleneck the
+    second and third convolutions take their batch checksum from the previous kernel), duplicated."""
+    from synth import ConvShape, resnet50_layers
+    layers = resnet50_layers(args.batch)
+    stream = torch.cuda.Stream()
+    total_ops = sum(s.ops for s in layers)
+    result = dict(batch=args.batch, layers=len(layers), gop=total_ops / 1e9)
+    for mode, variant in (("unchecked", Variant.NONE), ("checked", Variant.FUSED_IOCG), ("duplicate", Variant.DUPLICATE)):
+        objs, chained = [], []
+        prev = None
+        for i, s in enumerate(layers):
+            if s.C % 16:      # the 3-channel stem: channels padded with zeros to 16 by the caller
+                s = ConvShape(s.N, s.H, s.W, 16, s.K, s.R, s.S, s.stride_h, s.stride_w, s.pad_h, s.pad_w, s.name)
+            chain = prev is not None and s.name.split(".")[-1] in ("c2", "c3") and prev.s.name.split(".")[0] == s.name.split(".")[0]
+            L = Int8Layer(s, 5000 + i, variant, epilogue=True, x=prev.y if chain else None)
+            objs.append(L)
+            chained.append(chain)
+            prev = L
+
+        def step():
+            for j, L in enumerate(objs):
+                L.run(compute_xchk=not (variant == Variant.FUSED_IOCG and chained[j]))
+        if variant == Variant.FUSED_IOCG:
+            # chained layers read the previous layer's emitted checksum directly
+            for j, L in enumerate(objs):
+                if chained[j]:
+                    L.xchk = objs[j - 1].xchk_next
+        step()
+        torch.cuda.synchronize()
+        if variant == Variant.FUSED_IOCG:
+            bad = [L.s.name for L in objs if int(L.flags.abs().max().item()) != 0]
+            assert not bad, "flags set on a clean run: %s" % bad
+        t = _graph_time(step, stream, reps=2, replays=5)
+        result[mode] = dict(ms=t * 1e3, tops=total_ops / t / 1e12)
+        del objs
+        torch.cuda.empty_cache()
+    result["overhead_pct"] = 100.0 * (result["checked"]["ms"] / result["unchecked"]["ms"] - 1.0)
+    result["duplicate_overhead_pct"] = 100.0 * (result["duplicate"]["ms"] / result["unchecked"]["ms"] - 1.0)
+    print(json.dumps(result))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    sub = ap.add_subparsers(dest="cmd", required=True)
+    a = sub.add_parser("layers"); a.add_argument("--config", type=int, default=3, choices=[2, 3])
+    a = sub.add_parser("detect"); a.add_argument("--trials", type=int, default=1000); a.add_argument("--clean", type=int, default=100); a.add_argument("--seed", type=int, default=1)
+    a = sub.add_parser("fp16"); a.add_argument("--trials", type=int, default=1000); a.add_argument("--seed", type=int, default=1)
+    a = sub.add_parser("resnet50"); a.add_argument("--batch", type=int, default=128)
+    args = ap.parse_args()
+    if not torch.cuda.is_available():
+        print("no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    abed.lib()
+    {"layers": cmd_layers, "detect": cmd_detect, "fp16": cmd_fp16, "resnet50": cmd_resnet50}[args.cmd](args)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,46 @@
+"""Small driver for rocprofv3 runs (kernel trace or counters):
+
+  rocprofv3 --kernel-trace --stats ... -- python3 -m paper_2006_04984_amd.profile_run --config 2 --layer 3 --variant 4
+  rocprofv3 --pmc FETCH_SIZE ...      -- python3 -m paper_2006_04984_amd.profile_run ... --copy-mb 256
+
+Launches the chosen int8 layer `--reps` times through abed_conv_int8 (eager launches, so that every
+dispatch is seen by the profiler) and, with --copy-mb, one device-to-device copy of that many MiB,
+whose known size calibrates the FETCH_SIZE / WRITE_SIZE counters.
+"""
+import argparse
+
+import torch
+
+from .binding import Variant
+from .evaluate import Int8Layer
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3])
+    ap.add_argument("--layer", type=int, default=3)
+    ap.add_argument("--variant", type=int, default=4)
+    ap.add_argument("--reps", type=int, default=20)
+    ap.add_argument("--int8-out", action="store_true")
+    ap.add_argument("--copy-mb", type=int, default=0)
+    args = ap.parse_args()
+    from synth import CONFIG2, CONFIG3, seed_for
+    s = {2: CONFIG2, 3: CONFIG3}[args.config][args.layer]
+    L = Int8Layer(s, seed_for(args.config, args.layer), Variant(args.variant), epilogue=args.int8_out)
+    for _ in range(args.reps):
+        L.run()
+    torch.cuda.synchronize()
+    if args.copy_mb:
+        a = torch.empty((args.copy_mb << 20,), dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        a.fill_(1)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+    print("profiled", s.name, "variant", args.variant, "grid", L.lay.grid_m, L.lay.grid_b, L.lay.grid_n,
+          "flags", int(L.flags.abs().max().item()))
+
+
+if __name__ == "__main__":
+    main()
