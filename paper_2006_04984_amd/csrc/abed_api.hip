@@ -50,6 +50,7 @@ struct Plan {
     int d_f, d_i;
     int n_entries, kblk, n_fblk;          // batch entries, real filter blocks, filter blocks incl. the digit block
     int wm, wk, mb;                       // entries per wave, filter blocks per tile, entries per tile
+    int kg;                               // groups of 4 waves along the reduction axis
     int grid_m, grid_b, grid_n;
     // workspace offsets in bytes (-1 = unused)
     long long off_cnt_fc, off_cnt_ic, off_convout, off_yf, off_yi, off_yfi, off_fc, off_ic, off_nx, ws_bytes;
@@ -67,28 +68,50 @@ int env_int(const char *name, int dflt)
 // library targets are small next to 256 compute units, so tiles are kept small (measured on
 // ResNet-50-shaped layers: 64 filters x 8..12 entries was best or within a few percent of it):
 // more workgroups in flight hide memory latency better than larger tiles save traffic.
+// Tile shape from the problem's extents.  The rules come from timing sweeps over the ResNet-style
+// layers: the kernel is bound by how fast a CU can fill LDS, so bigger tiles (more matrix
+// instructions per byte loaded) win as long as the grid still gives every CU work; below that,
+// smaller tiles and wave groups along the reduction axis keep the chip busy.
 void choose_tile(Plan &pl)
 {
     int wk;
     if (pl.n_fblk <= 1) wk = 1;
-    else if (pl.n_fblk == 5) wk = 5;      // 64 filters + the digit block in one tile: FC stays local
-    else wk = 4;
-    int wm;
-    if (pl.n_entries <= 4) wm = 1;
-    else if (pl.n_entries <= 8) wm = 2;
-    else if (pl.n_entries <= 12) wm = 3;
-    else if (pl.n_entries <= 20) wm = 5;  // the whole batch in one tile: IC stays local
     else {
-        const int waste2 = (pl.n_entries + 7) / 8 * 8 - pl.n_entries;
-        const int waste3 = (pl.n_entries + 11) / 12 * 12 - pl.n_entries;
-        wm = waste3 < waste2 ? 3 : 2;
+        const int pad4 = (pl.n_fblk + 3) / 4 * 4, pad5 = (pl.n_fblk + 4) / 5 * 5;
+        wk = (pad5 + 2 <= pad4 || pl.n_fblk == 5) ? 5 : 4;   // 5: e.g. 64 filters + the digit block in one tile, FC stays local
     }
+    const int grid_m = (pl.PQ + 15) / 16, grid_n = (pl.n_fblk + wk - 1) / wk;
+    auto tiles = [&](int wm) { return (long long)grid_m * ((pl.n_entries + 4 * wm - 1) / (4 * wm)) * grid_n; };
+    auto waste = [&](int wm) { const int mb = 4 * wm; return (pl.n_entries + mb - 1) / mb * mb - pl.n_entries; };
+    static const int cand[] = {5, 3, 2};
+    int wm = 0;
+    // the largest tile that leaves at least 1.5 workgroups per CU and pads the batch by at most a
+    // fifth (a smaller one that pads nothing is preferred); failing that, the largest that still gives
+    // most CUs a workgroup; failing that, the smallest
+    for (int c : cand)
+        if (!wm && tiles(c) >= 384 && 5 * waste(c) <= pl.n_entries) wm = c;
+    if (wm)
+        for (int c : cand)
+            if (c < wm && waste(c) == 0 && waste(wm) != 0) { wm = c; break; }
+    if (!wm)
+        for (int c : cand)
+            if (!wm && tiles(c) >= 160 && 5 * waste(c) <= pl.n_entries) wm = c;
+    if (!wm) wm = 1;
+    if (pl.n_entries <= 4) wm = 1;
     wm = env_int("ABED_TILE_WM", wm);
     wk = env_int("ABED_TILE_WK", wk);
     pl.wm = wm; pl.wk = wk; pl.mb = 4 * wm;
-    pl.grid_m = (pl.PQ + 15) / 16;
+    pl.grid_m = grid_m;
     pl.grid_b = (pl.n_entries + pl.mb - 1) / pl.mb;
     pl.grid_n = (pl.n_fblk + wk - 1) / wk;
+    // wave groups along the reduction axis when the grid alone cannot put two waves on every SIMD
+    const long long t = (long long)pl.grid_m * pl.grid_b * pl.grid_n;
+    const int nsteps = (pl.crs * pl.esize + 63) / 64;
+    int kg = 1;
+    if (t < 384 && nsteps >= 16) kg = (t <= 256 && nsteps >= 64) ? 4 : 2;
+    kg = env_int("ABED_TILE_KG", kg);
+    while (kg > 1 && !tile_ok(wm, wk, kg)) kg /= 2;
+    pl.kg = kg;
 }
 
 abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool int8_out, Plan &pl)
@@ -185,7 +208,7 @@ abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_
     cp.x = x; cp.w = w; cp.y = y; cp.mode = MODE_PLAIN;
     if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
     set_injection(cp, d, pl, inject);
-    if (!launch_conv(false, pl.wm, pl.wk, cp, pl.grid_m * pl.grid_b * pl.grid_n, st)) return ABED_EUNSUPPORTED;
+    if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, pl.grid_m * pl.grid_b * pl.grid_n, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("conv_kernel (unchecked)");
     return ABED_OK;
 }
@@ -367,7 +390,7 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
             cp.out_int8 = 0;
             cp.mode = MODE_WRITE;
             cp.ws_yf = yf; cp.ws_yi = yi; cp.ws_yfi = yfi;
-            if (!launch_conv(false, pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
+            if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
             LAUNCH_CHECK("conv_i8_kernel (augmented, write)");
         }
         if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)convout, inject->index, 1u << inject->bit);
@@ -396,7 +419,7 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     cp.cnt_fc = (uint32_t *)wsp(pl.off_cnt_fc);
     cp.cnt_ic = (uint32_t *)wsp(pl.off_cnt_ic);
     cp.ws_fc = wsp(pl.off_fc); cp.ws_ic = wsp(pl.off_ic); cp.ws_nx = wsp(pl.off_nx);
-    if (!launch_conv(false, pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
+    if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("conv_i8_kernel (augmented)");
     if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)y, inject->index, 1u << inject->bit);
     if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
@@ -445,10 +468,10 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
     if (variant == ABED_NONE || variant == ABED_DUPLICATE) {
         cp.mode = MODE_PLAIN;
         if (variant == ABED_DUPLICATE) fill_u32_kernel<<<1, 64, 0, st>>>(flags, 1, 0u);
-        if (!launch_conv(true, pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
+        if (!launch_conv(true, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
         if (variant == ABED_DUPLICATE) {
             cp.y = y2; cp.inj_on = 0;
-            launch_conv(true, pl.wm, pl.wk, cp, grid, st);
+            launch_conv(true, pl.wm, pl.wk, pl.kg, cp, grid, st);
             const long long bytes = (long long)desc->N * pl.PQ * desc->K * (out_fp32 ? 4 : 2);
             compare_kernel<<<dim3((unsigned)((bytes / 16 + 256) / 256)), dim3(256), 0, st>>>(y, y2, bytes, flags);
         }
@@ -459,7 +482,7 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
     cp.cnt_fc = (uint32_t *)wsp(pl.off_cnt_fc);
     cp.cnt_ic = (uint32_t *)wsp(pl.off_cnt_ic);
     cp.ws_fc = wsp(pl.off_fc); cp.ws_ic = wsp(pl.off_ic);
-    if (!launch_conv(true, pl.wm, pl.wk, cp, grid, st)) return ABED_EUNSUPPORTED;
+    if (!launch_conv(true, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("conv_kernel (fp16, augmented)");
     return ABED_OK;
 }

@@ -2,15 +2,10 @@
 
 namespace abed {
 
-bool launch_conv(bool f16, int wm, int wk, const ConvParams &p, int grid, hipStream_t st)
+bool launch_conv(bool f16, int wm, int wk, int kg, const ConvParams &p, int grid, hipStream_t st)
 {
-    switch (wk) {
-    case 1: return launch_conv_wk1(f16, wm, p, grid, st);
-    case 4: return launch_conv_wk4(f16, wm, p, grid, st);
-    case 5: return launch_conv_wk5(f16, wm, p, grid, st);
-    case 8: return launch_conv_wk8(f16, wm, p, grid, st);
-    case 9: return launch_conv_wk9(f16, wm, p, grid, st);
-    }
+#define ABED_CASE(WK, KG) if (wk == WK && kg == KG) return launch_conv_wk##WK##_kg##KG(f16, wm, p, grid, st);
+    ABED_FOR_ALL_WK_KG(ABED_CASE)
     return false;
 }
 

@@ -1,30 +1,37 @@
-// One translation unit per filter-block count WK (set with -DINST_WK=<n>).
+// One translation unit per (filter-block count WK, reduction-axis group count KG), set with
+// -DINST_WK=<n> -DINST_KG=<n>, so the build runs in parallel.
 #include "conv_launch.h"
 
-#ifndef INST_WK
-#error "compile with -DINST_WK=<filter blocks per tile>"
+#if !defined(INST_WK) || !defined(INST_KG)
+#error "compile with -DINST_WK=<filter blocks per tile> -DINST_KG=<wave groups>"
 #endif
 
-#define CAT_(a, b) a##b
-#define CAT(a, b) CAT_(a, b)
+#define CAT4_(a, b, c, d) a##b##c##d
+#define CAT4(a, b, c, d) CAT4_(a, b, c, d)
 
 namespace abed {
 
 template <int WM>
-static void go(bool f16, const ConvParams &p, int grid, hipStream_t st)
+static bool go(bool f16, const ConvParams &p, int grid, hipStream_t st)
 {
-    if (f16) conv_kernel<true, WM, INST_WK, stages_for(WM, INST_WK)><<<dim3(grid), dim3(256), 0, st>>>(p);
-    else conv_kernel<false, WM, INST_WK, stages_for(WM, INST_WK)><<<dim3(grid), dim3(256), 0, st>>>(p);
+    if constexpr (tile_ok(WM, INST_WK, INST_KG)) {
+        constexpr int NST = stages_for(WM, INST_WK, INST_KG);
+        if (f16) conv_kernel<true, WM, INST_WK, NST, INST_KG><<<dim3(grid), dim3(256 * INST_KG), 0, st>>>(p);
+        else conv_kernel<false, WM, INST_WK, NST, INST_KG><<<dim3(grid), dim3(256 * INST_KG), 0, st>>>(p);
+        return true;
+    } else {
+        return false;
+    }
 }
 
-bool CAT(launch_conv_wk, INST_WK)(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st)
+bool CAT4(launch_conv_wk, INST_WK, _kg, INST_KG)(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st)
 {
     switch (wm) {
-    case 1: go<1>(f16, p, grid, st); return true;
-    case 2: go<2>(f16, p, grid, st); return true;
-    case 3: go<3>(f16, p, grid, st); return true;
-    case 5: go<5>(f16, p, grid, st); return true;
-    case 9: go<9>(f16, p, grid, st); return true;
+    case 1: return go<1>(f16, p, grid, st);
+    case 2: return go<2>(f16, p, grid, st);
+    case 3: return go<3>(f16, p, grid, st);
+    case 5: return go<5>(f16, p, grid, st);
+    case 9: return go<9>(f16, p, grid, st);
     }
     return false;
 }

@@ -24,6 +24,13 @@
 // because all entries of a tile share the same 16 pixels in the same lanes.
 // Wave w owns entries [w*WM, (w+1)*WM) of the tile and all WK filter blocks.
 //
+// A workgroup has KG groups of 4 waves.  With KG > 1 the groups split the reduction axis: a
+// pipeline stage holds KG consecutive 64-byte steps, group g loads and multiplies step g of
+// the stage, and after the loop the groups' accumulators are added through LDS into group 0,
+// which runs the epilogue alone.  This puts 2 or 4 waves on every SIMD (the matrix pipe
+// stays busy while another wave waits for LDS or for the barrier) on layers whose grid
+// is too small to fill the chip with several workgroups per CU.
+//
 // Operands reach LDS by direct global->LDS buffer loads (no staging registers), NST
 // stages deep; out-of-image taps and out-of-range rows are masked by the buffer
 // descriptor's range check.
@@ -112,12 +119,14 @@ __device__ __forceinline__ void st_dev4(int *p, i32x4 v)
 {
     asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(p), "v"(v) : "memory");
 }
-__device__ __forceinline__ i32x4 ld_dev4(const int *p)
+#if defined(__HIP_DEVICE_COMPILE__)
+// 16 bytes per lane read past the non-coherent caches (device scope), as a buffer load so that the
+// compiler keeps several of them in flight
+__device__ __forceinline__ i32x4 ld_dev4(const __amdgpu_buffer_rsrc_t rs, int byte_off)
 {
-    i32x4 v;
-    asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
-    return v;
+    return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, byte_off, 0, 16 /* sc1 */));
 }
+#endif
 
 // balanced base-256 digit (same rule as the ICG kernel)
 __device__ __forceinline__ int next_digit(int &s)
@@ -130,24 +139,29 @@ __device__ __forceinline__ int next_digit(int &s)
 // F16 = false: int8 data, int32 accumulators, exact checks mod 2^32.
 // F16 = true: fp16 data, fp32 accumulators, threshold checks (Sec. 7); the two checksum tensors
 // per side are the hi/lo pair, recombined by addition.
-template <bool F16, int WM, int WK, int NST>
-__global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
+template <bool F16, int WM, int WK, int NST, int KG>
+__global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass needs the signature only (the body uses device-only types)
     using acc_t = typename std::conditional<F16, f32x4, i32x4>::type;
     constexpr int MB = 4 * WM;                 // batch entries per tile
     constexpr int NB = WK + MB;                // 1 KB blocks per stage: filter blocks, then entry blocks
     constexpr int L = (NB + 3) / 4;            // direct-to-LDS loads per wave and step
-    constexpr int STAGE = NB * 1024;
+    constexpr int SUB = NB * 1024;              // one 64-byte step of the tile
+    constexpr int STAGE = KG * SUB;
     constexpr int EPI_BYTES = (F16 ? 8 : 4) * WK * 1024 + 64;
-    constexpr int LDS_BYTES = (NST * STAGE > EPI_BYTES) ? NST * STAGE : EPI_BYTES;
+    constexpr int RED_BYTES = (KG - 1) * 4 * WM * WK * 1024;   // accumulators of groups 1..KG-1
+    constexpr int LDS_MIN = EPI_BYTES > RED_BYTES ? EPI_BYTES : RED_BYTES;
+    constexpr int LDS_BYTES = (NST * STAGE > LDS_MIN) ? NST * STAGE : LDS_MIN;
     static_assert((NST - 1) * L <= 63, "vmcnt is a 6-bit counter");
     __shared__ __attribute__((aligned(1024))) int8_t lds[LDS_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63;
     // wave index as a scalar: every wave-level condition must be a scalar branch, matrix
     // instructions ignore the per-lane execution mask
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kg = KG > 1 ? wave_all >> 2 : 0;  // group along the reduction axis
+    const int wave = wave_all & 3;              // position inside the group: which entries
     const int lg = lane >> 4, lj = lane & 15;
     const bool aug = p.mode != MODE_PLAIN;
 
@@ -231,24 +245,36 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
     if (!utap)
         while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
 
-    auto issue = [&](int stage) {
+    // move the position one 64-byte step along the reduction axis (ut: the fast path, as a
+    // compile-time tag so that the main loop is compiled once per path without branches on it)
+    auto advance = [&](auto ut) {
+        if constexpr (decltype(ut)::value) {
+            s_off += 64; s_ch += 64;
+            if (s_ch == p.cb) { s_ch = 0; ++s_tap; if (++s_col == p.S) { s_col = 0; s_off += row_jump; } }
+        } else {
+            ch += 64;
+            while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
+        }
+        s_step += 64;
+    };
+    for (int g = 0; g < kg; ++g) {                           // group g starts at step g
+        if (utap) advance(std::true_type{}); else advance(std::false_type{});
+    }
+
+    auto issue = [&](int stage, auto ut) {
         int voff_x;            // per-lane offset of this step's chunk inside an image, or OOB
         const bool live = s_step < p.crsb;                   // uniform: the step starts inside the reduction axis
         bool in_crs = live;    // this lane's chunk lies inside the reduction axis
-        if (utap) {
+        if constexpr (decltype(ut)::value) {
             const unsigned m = (s_tap & 32) ? mask_hi : mask_lo;
             const bool inb = live && ((m >> (s_tap & 31)) & 1u);
             voff_x = inb ? lane_base + s_off : OOB;
-            s_off += 64; s_ch += 64;
-            if (s_ch == p.cb) { s_ch = 0; ++s_tap; if (++s_col == p.S) { s_col = 0; s_off += row_jump; } }
         } else {
             in_crs = s_step + ld_chunk * 16 < p.crsb;
             const bool inb = in_crs && (unsigned)(h0 + tap_r) < (unsigned)p.H && (unsigned)(w0 + tap_s) < (unsigned)p.W;
             voff_x = inb ? ((h0 + tap_r) * p.W + (w0 + tap_s)) * p.cb + ch : OOB;
-            ch += 64;
-            while (ch >= p.cb) { ch -= p.cb; if (++tap_s == p.S) { tap_s = 0; ++tap_r; } }
         }
-        int8_t *sbase = lds + stage * STAGE;
+        int8_t *sbase = lds + stage * STAGE + kg * SUB;
 #pragma unroll
         for (int i = 0; i < L; ++i) {
             int b = wave + 4 * i;
@@ -260,7 +286,8 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
             const int soff = blk_filter[i] ? s_step : blk_soff[i];
             __builtin_amdgcn_raw_ptr_buffer_load_lds(blk_rs[i], dst, 16, voff, soff, 0, 0);
         }
-        s_step += 64;
+#pragma unroll
+        for (int g = 0; g < KG; ++g) advance(ut);            // this group's next step
     };
 
     // ---------------- accumulators ----------------
@@ -272,22 +299,23 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
         for (int k = 0; k < WK; ++k) acc[i][k] = zero4;
 
     // ---------------- main loop ----------------
-    // Stage s holds step s (mod NST).  Loads run NST-1 steps ahead; steps past the end load zeros
-    // into stages nobody reads, which keeps the per-wave load count per step constant.
-#pragma unroll
-    for (int s = 0; s < NST - 1; ++s) issue(s);
-    int stage = 0;
+    // Stage s holds steps s*KG .. s*KG+KG-1 (s mod NST).  Loads run NST-1 stages ahead; steps past
+    // the end load zeros, which keeps the per-wave load count per stage constant.
     const int rd_lane = lds_off(lj, lg);         // this lane's 16 bytes inside any 1 KB block
-    if (p.dbg & 4) return;
-    for (int step = 0; step < ((p.dbg & 2) ? 0 : p.nsteps); ++step) {
+    const int nstages = (p.nsteps + KG - 1) / KG;
+    auto main_loop = [&](auto ut) {
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s) issue(s, ut);
+    int stage = 0;
+    for (int step = 0; step < ((p.dbg & 2) ? 0 : nstages); ++step) {
         ABED_WAIT_VMCNT((NST - 2) * L);          // this wave's loads of `step` have landed
         __builtin_amdgcn_s_barrier();            // everyone's have, and everyone is done with step-1
         {
-            int st = stage + NST - 1;
+            int st = stage + NST - 1;            // the stage that step-1 used gets refilled
             if (st >= NST) st -= NST;
-            issue(st);                           // refill the stage that step-1 used
+            issue(st, ut);
         }
-        const int8_t *ldsK = lds + stage * STAGE + rd_lane;          // + 1024 * filter block
+        const int8_t *ldsK = lds + stage * STAGE + kg * SUB + rd_lane;   // + 1024 * filter block
         const int8_t *ldsM = ldsK + (WK + wave * WM) * 1024;         // + 1024 * entry of this wave
         i32x4 bfr[WM];
 #pragma unroll
@@ -305,8 +333,32 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
         }
         if (++stage == NST) stage = 0;
     }
+    };
+    if (utap) main_loop(std::true_type{}); else main_loop(std::false_type{});
     ABED_WAIT_VMCNT(0);                          // drain the run-ahead loads before LDS is reused
     __builtin_amdgcn_s_barrier();
+
+    // ---------------- sum over the groups of the reduction axis ----------------
+    if constexpr (KG > 1) {
+        acc_t *red = reinterpret_cast<acc_t *>(lds);             // [KG-1][4 waves][WM*WK][64 lanes]
+        if (kg > 0) {
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int k = 0; k < WK; ++k)
+                    red[(((kg - 1) * 4 + wave) * (WM * WK) + i * WK + k) * 64 + lane] = acc[i][k];
+        }
+        __syncthreads();
+        if (kg > 0) return;                      // barriers from here on count the surviving waves only
+#pragma unroll
+        for (int g = 1; g < KG; ++g)
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int k = 0; k < WK; ++k)
+                    acc[i][k] += red[(((g - 1) * 4 + wave) * (WM * WK) + i * WK + k) * 64 + lane];
+        __syncthreads();                         // the epilogue reuses this memory
+    }
 
     if constexpr (F16) {
         // ---------------- epilogue, fp16 data (Sec. 7) ----------------
@@ -361,7 +413,62 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
             }
         }
         if (p.dbg & 1) return;
-        // (3) stores (checksum rows and columns are trimmed)
+        const bool exchange = checking && !(fc_local && ic_local);
+        const long long word = ((long long)pg * p.grid_b + nt) * p.grid_n + kt;
+        if (aug) {
+            // (3) IC: sum over the real images of every (pixel, filter) against hi + lo of the checksum-image fmaps
+#pragma unroll
+            for (int kb = 0; kb < WK; ++kb) {
+                f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int i = 0; i < WM; ++i) {
+                    const int e = nt * MB + wave * WM + i;
+                    if (e < p.N) sum += acc[i][kb];
+                    else if (e < p.n_entries) chk += acc[i][kb];
+                }
+                *reinterpret_cast<f32x4 *>(e_ic + ((wave * WK + kb) * 64 + lane) * 4) = sum;
+                *reinterpret_cast<f32x4 *>(e_ic + 4 * WK * 256 + ((wave * WK + kb) * 64 + lane) * 4) = chk;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int c4 = 0; c4 < (WK + 3) / 4; ++c4) {
+                const int kb = 4 * c4 + wave;
+                if (kb >= WK) continue;
+                f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    sum += *reinterpret_cast<const f32x4 *>(e_ic + ((w * WK + kb) * 64 + lane) * 4);
+                    chk += *reinterpret_cast<const f32x4 *>(e_ic + 4 * WK * 256 + ((w * WK + kb) * 64 + lane) * 4);
+                }
+                const int fb = kt * WK + kb;
+                if (checking && ic_local) {
+                    if (bad(sum[0], chk[0]) || bad(sum[1], chk[1]) || bad(sum[2], chk[2]) || bad(sum[3], chk[3]))
+                        my_flag |= (fb < p.kblk) ? 2u : 4u;
+                } else {
+                    int *dst = p.ws_ic + ((((long long)pg * p.grid_n + kt) * p.grid_b + nt) * 2 * WK + kb) * 256 + lane * 4;
+                    st_dev4(dst, __builtin_bit_cast(i32x4, sum));
+                    st_dev4(dst + WK * 256, __builtin_bit_cast(i32x4, chk));
+                }
+            }
+            if (checking) {
+                // (4) flags of this tile; when sums span several tiles, count this tile's arrival (the
+                // answer is picked up after the output stores have been issued)
+                if (my_flag) atomicOr(reinterpret_cast<unsigned *>(&e_misc[0]), my_flag);
+                __syncthreads();
+                if (tid == 0) __hip_atomic_store(&p.flags[word], (uint32_t)e_misc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (exchange) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                    __syncthreads();
+                    if (tid == 0) {
+                        if (!fc_local)
+                            e_misc[1] = __hip_atomic_fetch_add(&p.cnt_fc[pg * p.grid_b + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_n - 1);
+                        if (!ic_local)
+                            e_misc[2] = __hip_atomic_fetch_add(&p.cnt_ic[pg * p.grid_n + kt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_b - 1);
+                    }
+                }
+            }
+        }
+        // (5) stores (checksum rows and columns are trimmed)
 #pragma unroll
         for (int kb = 0; kb < WK; ++kb) {
             const int fb = kt * WK + kb;
@@ -389,56 +496,8 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
                 }
             }
         }
-        if (!aug || (p.dbg & 8)) return;
-        // (4) IC: sum over the real images of every (pixel, filter) against hi + lo of the checksum-image fmaps
-#pragma unroll
-        for (int kb = 0; kb < WK; ++kb) {
-            f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int i = 0; i < WM; ++i) {
-                const int e = nt * MB + wave * WM + i;
-                if (e < p.N) sum += acc[i][kb];
-                else if (e < p.n_entries) chk += acc[i][kb];
-            }
-            *reinterpret_cast<f32x4 *>(e_ic + ((wave * WK + kb) * 64 + lane) * 4) = sum;
-            *reinterpret_cast<f32x4 *>(e_ic + 4 * WK * 256 + ((wave * WK + kb) * 64 + lane) * 4) = chk;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int c4 = 0; c4 < (WK + 3) / 4; ++c4) {
-            const int kb = 4 * c4 + wave;
-            if (kb >= WK) continue;
-            f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                sum += *reinterpret_cast<const f32x4 *>(e_ic + ((w * WK + kb) * 64 + lane) * 4);
-                chk += *reinterpret_cast<const f32x4 *>(e_ic + 4 * WK * 256 + ((w * WK + kb) * 64 + lane) * 4);
-            }
-            const int fb = kt * WK + kb;
-            if (checking && ic_local) {
-                if (bad(sum[0], chk[0]) || bad(sum[1], chk[1]) || bad(sum[2], chk[2]) || bad(sum[3], chk[3]))
-                    my_flag |= (fb < p.kblk) ? 2u : 4u;
-            } else {
-                int *dst = p.ws_ic + ((((long long)pg * p.grid_n + kt) * p.grid_b + nt) * 2 * WK + kb) * 256 + lane * 4;
-                st_dev4(dst, __builtin_bit_cast(i32x4, sum));
-                st_dev4(dst + WK * 256, __builtin_bit_cast(i32x4, chk));
-            }
-        }
-        if (!checking) return;
-        // (5) flags; sums that span several tiles are finished by the workgroup that arrives last
-        if (my_flag) atomicOr(reinterpret_cast<unsigned *>(&e_misc[0]), my_flag);
-        __syncthreads();
-        const long long word = ((long long)pg * p.grid_b + nt) * p.grid_n + kt;
-        if (tid == 0) __hip_atomic_store(&p.flags[word], (uint32_t)e_misc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (fc_local && ic_local) return;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __syncthreads();
-        if (tid == 0) {
-            if (!fc_local)
-                e_misc[1] = __hip_atomic_fetch_add(&p.cnt_fc[pg * p.grid_b + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_n - 1);
-            if (!ic_local)
-                e_misc[2] = __hip_atomic_fetch_add(&p.cnt_ic[pg * p.grid_n + kt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_b - 1);
-        }
+        if (!exchange) return;
+        // (6) sums that span several tiles are finished by the workgroup that arrives last
         __syncthreads();
         if (e_misc[1]) {
             uint32_t late = 0;
@@ -456,14 +515,18 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
         }
         if (e_misc[2]) {
             uint32_t late = 0;
+            // the partials of this (pixel group, filter tile): [grid_b][2][WK][256] words
+            const __amdgpu_buffer_rsrc_t rs_ic = __builtin_amdgcn_make_buffer_rsrc(
+                (void *)(p.ws_ic + (((long long)pg * p.grid_n + kt) * p.grid_b) * 2 * WK * 256), 0, p.grid_b * 2 * WK * 1024, 0x00020000);
             for (int idx = tid; idx < WK * 64; idx += 256) {
                 const int kb = idx >> 6, ln = idx & 63;
                 const int fb = kt * WK + kb;
                 f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
                 for (int b = 0; b < p.grid_b; ++b) {
-                    const int *src = p.ws_ic + ((((long long)pg * p.grid_n + kt) * p.grid_b + b) * 2 * WK + kb) * 256 + ln * 4;
-                    sum += __builtin_bit_cast(f32x4, ld_dev4(src));
-                    chk += __builtin_bit_cast(f32x4, ld_dev4(src + WK * 256));
+                    const int off = (((b * 2 * WK) + kb) * 256 + ln * 4) * 4;
+                    sum += __builtin_bit_cast(f32x4, ld_dev4(rs_ic, off));
+                    chk += __builtin_bit_cast(f32x4, ld_dev4(rs_ic, off + WK * 1024));
                 }
                 if (bad(sum[0], chk[0]) || bad(sum[1], chk[1]) || bad(sum[2], chk[2]) || bad(sum[3], chk[3]))
                     late |= (fb < p.kblk) ? 2u : 4u;
@@ -481,6 +544,9 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
     uint32_t my_flag = 0;
     const bool fc_local = p.grid_n == 1, ic_local = p.grid_b == 1;
     const bool checking = p.mode == MODE_CHECK || p.mode == MODE_CHECK_NEXT;
+    const bool reduce = aug && p.mode != MODE_WRITE;          // residuals are formed in this kernel
+    const bool want_next = p.mode == MODE_CHECK_NEXT && p.out_int8 && p.xchk_next != nullptr;
+    const long long tile = ((long long)pg * p.grid_b + nt) * p.grid_n + kt;
 
     // (1) accumulator fault injection (tests)
     if (p.inj_on && pg == p.inj_pg && nt == p.inj_nt && kt == p.inj_kt) {
@@ -495,7 +561,7 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
     }
 
     // (2) FC residual of every row of the tile (Sec. 3.1; digit shifts of Sec. 4.1)
-    if (aug && p.mode != MODE_WRITE) {
+    if (reduce) {
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             const int e = nt * MB + wave * WM + i;
@@ -515,83 +581,22 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
             if (checking && fc_local) {
                 if (r != 0) my_flag |= (e < p.N) ? 1u : 4u;
             } else if (lg == 0) {
-                st_dev(&p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + kt) * (MB * 16) + (wave * WM + i) * 16 + lj], (int)r);
+                st_dev(&p.ws_fc[tile * (MB * 16) + (wave * WM + i) * 16 + lj], (int)r);
             }
         }
     }
-
     if (p.dbg & 1) return;
-    // (3) stores; checksum rows and columns are trimmed from y (end of Sec. 4.3)
+
     int nx[WK][4];   // batch sums of the int8 outputs (variant 5)
-    const bool want_next = p.mode == MODE_CHECK_NEXT && p.out_int8 && p.xchk_next != nullptr;
 #pragma unroll
     for (int kb = 0; kb < WK; ++kb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) nx[kb][v] = 0;
-#pragma unroll
-    for (int kb = 0; kb < WK; ++kb) {
-        const int fb = kt * WK + kb;
-        const int k = fb * 16 + lg * 4;                       // first of this lane's 4 filters
-        if (fb < p.kblk) {
-            float sc[4], bi[4];
-            if (p.out_int8) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    sc[v] = (k + v < p.K) ? p.scale[k + v] : 0.f;
-                    bi[v] = (k + v < p.K) ? p.bias[k + v] : 0.f;
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < WM; ++i) {
-                const int e = nt * MB + wave * WM + i;
-                if (!pvalid) continue;
-                if (e < p.N) {
-                    const long long o = ((long long)e * PQ + pix) * p.K + k;
-                    if (p.out_int8) {
-                        unsigned pk = 0;
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const int q8 = requant(acc[i][kb][v], sc[v], bi[v], p.relu);
-                            pk |= ((unsigned)q8 & 0xffu) << (8 * v);
-                            if (k + v < p.K) nx[kb][v] += q8;
-                        }
-                        int8_t *dst = reinterpret_cast<int8_t *>(p.y) + o;
-                        if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<unsigned *>(dst) = pk;
-                        else
-                            for (int v = 0; v < 4; ++v)
-                                if (k + v < p.K) dst[v] = (int8_t)((pk >> (8 * v)) & 0xff);
-                    } else {
-                        int32_t *dst = reinterpret_cast<int32_t *>(p.y) + o;
-                        if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<i32x4 *>(dst) = acc[i][kb];
-                        else
-                            for (int v = 0; v < 4; ++v)
-                                if (k + v < p.K) dst[v] = acc[i][kb][v];
-                    }
-                } else if (p.mode == MODE_WRITE && e < p.n_entries) {
-                    int32_t *dst = p.ws_yi + ((long long)(e - p.N) * PQ + pix) * p.K + k;
-                    for (int v = 0; v < 4; ++v)
-                        if (k + v < p.K) dst[v] = acc[i][kb][v];
-                }
-            }
-        } else if (fb == p.kblk && p.mode == MODE_WRITE && lg == 0 && pvalid) {
-#pragma unroll
-            for (int i = 0; i < WM; ++i) {
-                const int e = nt * MB + wave * WM + i;
-                if (e < p.N) {
-                    for (int v = 0; v < p.d_f; ++v) p.ws_yf[((long long)e * PQ + pix) * p.d_f + v] = acc[i][kb][v];
-                } else if (e < p.n_entries) {
-                    for (int v = 0; v < p.d_f; ++v) p.ws_yfi[((long long)(e - p.N) * PQ + pix) * p.d_f + v] = acc[i][kb][v];
-                }
-            }
-        }
-    }
-    if (!aug || p.mode == MODE_WRITE || (p.dbg & 8)) return;
 
-    // (4) IC residual of every (pixel, filter) of the tile (Sec. 3.2 option 1): sum over this
-    // wave's entries in registers, then over the 4 waves through LDS.  A second pass does the
-    // same for the int8 outputs (the next layer's batch checksum, Sec. 4.3).
-    for (int pass = 0; pass < (want_next ? 2 : 1); ++pass) {
-        if (pass == 1) __syncthreads();
+    // IC residual of every (pixel, filter) of the tile (Sec. 3.2 option 1), pass 0: sum over this
+    // wave's entries in registers, then over the 4 waves through LDS.  Pass 1 does the same for the
+    // int8 outputs (the next layer's batch checksum, Sec. 4.3).
+    auto ic_pass = [&](int pass) {
 #pragma unroll
         for (int kb = 0; kb < WK; ++kb) {
             i32x4 c = zero4;
@@ -651,36 +656,114 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
                 }
             }
         }
+    };
+
+    // Flags of this tile; when residuals span several tiles, count this tile's arrival.  The
+    // partial stores are write-through, so waiting for them to complete (the release fence) is
+    // enough before the arrival is counted.  The answer (was this the last tile?) is picked up
+    // after the output stores have been issued, which hides the round trip of the counter.
+    const bool exchange = checking && !(fc_local && ic_local);
+    auto arrive = [&]() {
+        if (my_flag) atomicOr(reinterpret_cast<unsigned *>(&e_misc[0]), my_flag);
+        __syncthreads();
+        if (tid == 0) __hip_atomic_store(&p.flags[tile], (uint32_t)e_misc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (!exchange) return;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        if (tid == 0) {
+            if (!fc_local)
+                e_misc[1] = __hip_atomic_fetch_add(&p.cnt_fc[pg * p.grid_b + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_n - 1);
+            if (!ic_local)
+                e_misc[2] = __hip_atomic_fetch_add(&p.cnt_ic[pg * p.grid_n + kt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_b - 1);
+        }
+    };
+
+    // (3) residuals first (they are small), then the output stores; variant 5 needs the
+    // requantised outputs for its second pass, so there the order is the other way round
+    if (reduce && !want_next) {
+        ic_pass(0);
+        if (checking) arrive();
     }
 
-    if (!checking) return;   // MODE_PARTIAL: the finish kernel compares
-
-    // (5) flags.  Word (pg, nt, kt) gets this tile's own findings; residuals that span several
-    // tiles are summed by the workgroup that arrives last and reported on kt = 0 (FC) / nt = 0 (IC).
-    if (my_flag) atomicOr(reinterpret_cast<unsigned *>(&e_misc[0]), my_flag);
-    __syncthreads();
-    const long long word = ((long long)pg * p.grid_b + nt) * p.grid_n + kt;
-    if (tid == 0) __hip_atomic_store(&p.flags[word], (uint32_t)e_misc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if ((fc_local && ic_local) || (p.dbg & 16)) return;
-    // all partial stores of this workgroup have completed (they are write-through) ...
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
-    // ... before its arrival is counted
-    if (tid == 0) {
-        if (!fc_local)
-            e_misc[1] = __hip_atomic_fetch_add(&p.cnt_fc[pg * p.grid_b + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_n - 1);
-        if (!ic_local)
-            e_misc[2] = __hip_atomic_fetch_add(&p.cnt_ic[pg * p.grid_n + kt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_b - 1);
+    // (4) stores; checksum rows and columns are trimmed from y (end of Sec. 4.3)
+#pragma unroll
+    for (int kb = 0; kb < WK; ++kb) {
+        const int fb = kt * WK + kb;
+        const int k = fb * 16 + lg * 4;                       // first of this lane's 4 filters
+        if (fb < p.kblk) {
+            float sc[4], bi[4];
+            if (p.out_int8) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    sc[v] = (k + v < p.K) ? p.scale[k + v] : 0.f;
+                    bi[v] = (k + v < p.K) ? p.bias[k + v] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < WM; ++i) {
+                const int e = nt * MB + wave * WM + i;
+                if (!pvalid) continue;
+                if (e < p.N) {
+                    const long long o = ((long long)e * PQ + pix) * p.K + k;
+                    if (p.out_int8) {
+                        unsigned pk = 0;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int q8 = requant(acc[i][kb][v], sc[v], bi[v], p.relu);
+                            pk |= ((unsigned)q8 & 0xffu) << (8 * v);
+                            if (k + v < p.K) nx[kb][v] += q8;
+                        }
+                        int8_t *dst = reinterpret_cast<int8_t *>(p.y) + o;
+                        if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<unsigned *>(dst) = pk;
+                        else
+                            for (int v = 0; v < 4; ++v)
+                                if (k + v < p.K) dst[v] = (int8_t)((pk >> (8 * v)) & 0xff);
+                    } else {
+                        int32_t *dst = reinterpret_cast<int32_t *>(p.y) + o;
+                        if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<i32x4 *>(dst) = acc[i][kb];
+                        else
+                            for (int v = 0; v < 4; ++v)
+                                if (k + v < p.K) dst[v] = acc[i][kb][v];
+                    }
+                } else if (p.mode == MODE_WRITE && e < p.n_entries) {
+                    int32_t *dst = p.ws_yi + ((long long)(e - p.N) * PQ + pix) * p.K + k;
+                    for (int v = 0; v < 4; ++v)
+                        if (k + v < p.K) dst[v] = acc[i][kb][v];
+                }
+            }
+        } else if (fb == p.kblk && p.mode == MODE_WRITE && lg == 0 && pvalid) {
+#pragma unroll
+            for (int i = 0; i < WM; ++i) {
+                const int e = nt * MB + wave * WM + i;
+                if (e < p.N) {
+                    for (int v = 0; v < p.d_f; ++v) p.ws_yf[((long long)e * PQ + pix) * p.d_f + v] = acc[i][kb][v];
+                } else if (e < p.n_entries) {
+                    for (int v = 0; v < p.d_f; ++v) p.ws_yfi[((long long)(e - p.N) * PQ + pix) * p.d_f + v] = acc[i][kb][v];
+                }
+            }
+        }
     }
+    if (!reduce) return;
+    if (want_next) {
+        ic_pass(0);
+        __syncthreads();
+        ic_pass(1);
+        arrive();
+    }
+    if (!exchange) return;   // MODE_PARTIAL: the finish kernel compares; local sums: done
+
+    // (5) residuals that span several tiles are summed by the workgroup that arrives last and
+    // reported on kt = 0 (FC) / nt = 0 (IC)
     __syncthreads();
     const bool last_fc = e_misc[1] != 0, last_ic = e_misc[2] != 0;
     if (!last_fc && !last_ic) return;
     if (last_fc) {
         uint32_t late = 0;
+        const int *src = &p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n) * (MB * 16)];
         for (int r = tid; r < MB * 16; r += 256) {
             unsigned s = 0;
-            for (int c = 0; c < p.grid_n; ++c)
-                s += (unsigned)ld_dev(&p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + c) * (MB * 16) + r]);
+#pragma unroll 4
+            for (int c = 0; c < p.grid_n; ++c) s += (unsigned)ld_dev(src + c * (MB * 16) + r);
             if (s != 0) late |= (nt * MB + (r >> 4) < p.N) ? 1u : 4u;
         }
         if (late) __hip_atomic_fetch_or(&p.flags[((long long)pg * p.grid_b + nt) * p.grid_n], late, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -688,14 +771,19 @@ __global__ __launch_bounds__(256) void conv_kernel(const ConvParams p)
     }
     if (last_ic) {
         uint32_t late = 0;
+        // the partials of this (pixel group, filter tile): [grid_b][WK][256] words
+        const long long base = (((long long)pg * p.grid_n + kt) * p.grid_b) * WK * 256;
+        const __amdgpu_buffer_rsrc_t rs_ic = __builtin_amdgcn_make_buffer_rsrc((void *)(p.ws_ic + base), 0, p.grid_b * WK * 1024, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rs_nx = __builtin_amdgcn_make_buffer_rsrc((void *)(want_next ? p.ws_nx + base : p.ws_ic + base), 0, p.grid_b * WK * 1024, 0x00020000);
         for (int idx = tid; idx < WK * 64; idx += 256) {      // one (filter block, lane) vector each
             const int kb = idx >> 6, ln = idx & 63;
             const int fb = kt * WK + kb;
             i32x4 s = zero4, sn = zero4;
+#pragma unroll 4
             for (int b = 0; b < p.grid_b; ++b) {
-                const long long part = ((((long long)pg * p.grid_n + kt) * p.grid_b + b) * WK + kb) * 256 + ln * 4;
-                s += ld_dev4(p.ws_ic + part);
-                if (want_next) sn += ld_dev4(p.ws_nx + part);
+                const int off = ((b * WK + kb) * 256 + ln * 4) * 4;
+                s += ld_dev4(rs_ic, off);
+                if (want_next) sn += ld_dev4(rs_nx, off);
             }
             if ((s[0] | s[1] | s[2] | s[3]) != 0) late |= (fb < p.kblk) ? 2u : 4u;
             if (want_next && fb < p.kblk) {

@@ -7,9 +7,11 @@
 
 namespace abed {
 
-// compiled tile shapes: WM (batch entries per wave), WK (filter blocks per tile)
+// compiled tile shapes: WM (batch entries per wave), WK (filter blocks per tile), KG (groups of
+// 4 waves along the reduction axis)
 static const int kWmList[] = {1, 2, 3, 5, 9};
 static const int kWkList[] = {1, 4, 5, 8, 9};
+static const int kKgList[] = {1, 2, 4};
 #ifndef ABED_STAGES
 #define ABED_STAGES 3
 #endif
@@ -18,21 +20,30 @@ static const int kWkList[] = {1, 4, 5, 8, 9};
 #endif
 // LDS stages of the load pipeline for a tile shape: as many as asked for, within a per-workgroup LDS
 // budget and within the 6-bit vector-memory counter the hand-counted waits rely on.
-constexpr int stages_for(int wm, int wk)
+constexpr int stages_for(int wm, int wk, int kg)
 {
     const int nb = wk + 4 * wm, l = (nb + 3) / 4;
     int n = ABED_STAGES;
-    while (n > 2 && (n * nb * 1024 > ABED_LDS_BUDGET || (n - 1) * l > 63)) --n;
+    while (n > 2 && (n * kg * nb * 1024 > ABED_LDS_BUDGET || (n - 1) * l > 63)) --n;
     return n;
 }
+// Whether (wm, wk, kg) is compiled: the accumulators, the operand fragments and the loader state must
+// fit the registers a wave gets when 4*kg waves share a CU's SIMDs (512 / kg), and two pipeline stages
+// and the group-sum buffer must fit LDS.
+constexpr bool tile_ok(int wm, int wk, int kg)
+{
+    const int regs = 4 * wm * wk + 4 * wm + 4 + 72;
+    const int nb = wk + 4 * wm;
+    if (kg == 4 && wm * wk > 8) return false;   // 128 registers per wave
+    return regs <= 512 / kg && 2 * kg * nb * 1024 <= 160 * 1024 - 1024 && (kg - 1) * 4 * wm * wk * 1024 <= 160 * 1024 - 1024;
+}
 
-// Returns false if (wm, wk) is not a compiled configuration.
-bool launch_conv(bool f16, int wm, int wk, const ConvParams &p, int grid, hipStream_t st);
+// Returns false if (wm, wk, kg) is not a compiled configuration.
+bool launch_conv(bool f16, int wm, int wk, int kg, const ConvParams &p, int grid, hipStream_t st);
 
-bool launch_conv_wk1(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_wk4(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_wk5(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_wk8(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
-bool launch_conv_wk9(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
+#define ABED_DECL_LAUNCH(WK, KG) bool launch_conv_wk##WK##_kg##KG(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
+#define ABED_FOR_ALL_WK_KG(X) \
+    X(1, 1) X(4, 1) X(5, 1) X(8, 1) X(9, 1) X(1, 2) X(4, 2) X(5, 2) X(8, 2) X(9, 2) X(1, 4) X(4, 4) X(5, 4) X(8, 4) X(9, 4)
+ABED_FOR_ALL_WK_KG(ABED_DECL_LAUNCH)
 
 }  // namespace abed
