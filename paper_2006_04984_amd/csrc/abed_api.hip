@@ -398,14 +398,12 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
         vp.y = convout; vp.yf = yf; vp.yi = yi; vp.yfi = yfi; vp.flags = flags;
         vp.N = desc->N; vp.PQ = pl.PQ; vp.K = desc->K; vp.d_f = pl.d_f; vp.d_i = pl.d_i;
         vp.tile_batch = pl.mb; vp.tile_n = 16 * pl.wk; vp.grid_b = pl.grid_b; vp.grid_n = pl.grid_n;
-        const size_t shm = ((size_t)16 * desc->K + 16 + (size_t)pl.grid_b * pl.grid_n) * 4;
-        if (shm > 160 * 1024) return ABED_EUNSUPPORTED;
-        static bool attr_set = false;
-        if (!attr_set) {
-            HIP_TRY(hipFuncSetAttribute((const void *)verify_i8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-            attr_set = true;
-        }
-        verify_i8_kernel<<<dim3(pl.grid_m), dim3(256), shm, st>>>(vp);
+        const size_t shm = ((size_t)desc->N + desc->K + 2) * 4;
+        if (shm > 64 * 1024) return ABED_EUNSUPPORTED;
+        const long long words = (long long)pl.grid_m * pl.grid_b * pl.grid_n;
+        fill_u32_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st>>>(flags, words, 0u);
+        LAUNCH_CHECK("fill_u32_kernel");
+        verify_i8_kernel<<<dim3(pl.PQ), dim3(256), shm, st>>>(vp);
         LAUNCH_CHECK("verify_i8_kernel");
         if (int8_out) {
             epilog_i8_kernel<<<dim3((unsigned)((npqk / 4 + 256) / 256)), dim3(256), 0, st>>>(convout, (int8_t *)y, epi->scale, epi->bias, epi->relu, npqk, desc->K);
@@ -426,7 +424,7 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
         FinishParams fp;
         fp.fc = cp.ws_fc; fp.ic = cp.ws_ic; fp.flags = flags;
         fp.N = desc->N; fp.kblk = pl.kblk; fp.tile_batch = pl.mb; fp.wk = pl.wk; fp.grid_b = pl.grid_b; fp.grid_n = pl.grid_n;
-        finish_i8_kernel<<<dim3(pl.grid_m), dim3(256), (size_t)pl.grid_b * pl.grid_n * 4, st>>>(fp);
+        finish_i8_kernel<<<dim3(pl.grid_m * (pl.grid_b + pl.grid_n)), dim3(256), 0, st>>>(fp);
         LAUNCH_CHECK("finish_i8_kernel");
     }
     return ABED_OK;

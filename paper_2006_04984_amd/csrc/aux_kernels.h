@@ -140,66 +140,62 @@ struct VerifyParams {
 
 // Variants that verify from memory (Sec. 4.3, unfused option): read ConvOut back,
 // reduce over filters and over the batch, compare with the checksum fmaps.
-// One workgroup per group of 16 pixels (all images, all filters).
-// Bit 0 goes to word (batch tile of the image, 0), bit 1 to word (0, filter tile of the
-// channel), bit 2 to word (0, 0) of the pixel group.
+// One workgroup per output pixel: its N x K block of ConvOut is read once, 16 bytes per lane;
+// column sums (over the batch) stay in registers, row sums (over the filters) go through LDS.
+// The flag words must be zero on entry.  Bit 0 goes to word (batch tile of the image, 0), bit 1
+// to word (0, filter tile of the channel), bit 2 to word (0, 0) of the pixel group.
 __global__ __launch_bounds__(256) void verify_i8_kernel(const VerifyParams p)
 {
     extern __shared__ int vs[];
-    int *cs = vs;                       // [16][K]   sum over images
-    int *syf = cs + 16 * p.K;           // [16]      sum over images of the FC fmap
-    int *fl = syf + 16;                 // [grid_b][grid_n]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int pg = blockIdx.x;
-    const int nwords = p.grid_b * p.grid_n;
-    for (int i = tid; i < 16 * p.K + 16 + nwords; i += 256) vs[i] = 0;
+    int *rowsum = vs;                   // [N]   sum over filters of image n
+    int *colsum = vs + p.N;             // [K]   sum over images of filter k
+    int *misc = colsum + p.K;           // [0] sum_n of the FC fmap, [1] sum_k of the IC fmap
+    const int tid = threadIdx.x;
+    const int pix = blockIdx.x, tm = pix >> 4;
+    for (int i = tid; i < p.N + p.K + 2; i += 256) vs[i] = 0;
     __syncthreads();
-    const int rows = 16 * p.N;
-    for (int r = wave; r < rows; r += 4) {
-        const int n = r >> 4, t = r & 15;
-        const int pix = pg * 16 + t;
-        if (pix >= p.PQ) continue;
-        const int32_t *row = p.y + ((long long)n * p.PQ + pix) * p.K;
-        unsigned s = 0;
-        for (int k = lane; k < p.K; k += 64) {
-            const int v = row[k];
-            s += (unsigned)v;
-            atomicAdd(&cs[t * p.K + k], v);
-        }
-        for (int m = 32; m >= 1; m >>= 1) s += (unsigned)__shfl_xor((int)s, m, 64);
-        if (lane == 0) {
-            unsigned c = 0;
-            for (int d = 0; d < p.d_f; ++d) c += (unsigned)p.yf[((long long)n * p.PQ + pix) * p.d_f + d] << (8 * d);
-            if (s != c) atomicOr(reinterpret_cast<unsigned *>(&fl[(n / p.tile_batch) * p.grid_n]), 1u);
-            atomicAdd(&syf[t], (int)c);
+    const int cw = (p.K & 3) ? 1 : 4;              // filters per lane and load
+    const int nchunk = p.K / cw;
+    const int lanes_per_row = nchunk < 256 ? nchunk : 256;
+    const int rows_par = 256 / lanes_per_row;      // images handled side by side
+    const int slot = tid / lanes_per_row, c0 = tid - slot * lanes_per_row;
+    if (slot < rows_par) {
+        for (int c = c0; c < nchunk; c += lanes_per_row) {
+            int col[4] = {0, 0, 0, 0};
+            for (int n = slot; n < p.N; n += rows_par) {
+                const int32_t *src = p.y + ((long long)n * p.PQ + pix) * p.K + c * cw;
+                int v[4] = {0, 0, 0, 0};
+                if (cw == 4) { const int4 t = *reinterpret_cast<const int4 *>(src); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
+                else v[0] = src[0];
+                for (int q = 0; q < 4; ++q) col[q] += v[q];
+                atomicAdd(&rowsum[n], (int)((unsigned)v[0] + (unsigned)v[1] + (unsigned)v[2] + (unsigned)v[3]));
+            }
+            for (int q = 0; q < cw; ++q) atomicAdd(&colsum[c * cw + q], col[q]);
         }
     }
     __syncthreads();
-    for (int i = tid; i < 16 * p.K; i += 256) {
-        const int t = i / p.K, k = i - t * p.K;
-        const int pix = pg * 16 + t;
-        if (pix >= p.PQ) continue;
+    // FC: every image's row sum against the recombined checksum-filter fmap
+    for (int n = tid; n < p.N; n += 256) {
+        unsigned c = 0;
+        for (int d = 0; d < p.d_f; ++d) c += (unsigned)p.yf[((long long)n * p.PQ + pix) * p.d_f + d] << (8 * d);
+        if ((unsigned)rowsum[n] != c) atomicOr(&p.flags[((long long)tm * p.grid_b + n / p.tile_batch) * p.grid_n], 1u);
+        atomicAdd(&misc[0], (int)c);
+    }
+    // IC: every filter's column sum against the recombined checksum-image fmap
+    for (int k = tid; k < p.K; k += 256) {
         unsigned c = 0;
         for (int j = 0; j < p.d_i; ++j) c += (unsigned)p.yi[((long long)j * p.PQ + pix) * p.K + k] << (8 * j);
-        if ((unsigned)cs[i] != c) atomicOr(reinterpret_cast<unsigned *>(&fl[k / p.tile_n]), 2u);
-    }
-    // corner: sum_n yf and sum_k yi against conv(xsum, wsum)
-    for (int t = wave; t < 16; t += 4) {
-        const int pix = pg * 16 + t;
-        if (pix >= p.PQ) continue;
-        unsigned sk = 0;
-        for (int k = lane; k < p.K; k += 64)
-            for (int j = 0; j < p.d_i; ++j) sk += (unsigned)p.yi[((long long)j * p.PQ + pix) * p.K + k] << (8 * j);
-        for (int m = 32; m >= 1; m >>= 1) sk += (unsigned)__shfl_xor((int)sk, m, 64);
-        if (lane == 0) {
-            unsigned c = 0;
-            for (int j = 0; j < p.d_i; ++j)
-                for (int d = 0; d < p.d_f; ++d) c += (unsigned)p.yfi[((long long)j * p.PQ + pix) * p.d_f + d] << (8 * (j + d));
-            if (sk != c || (unsigned)syf[t] != c) atomicOr(reinterpret_cast<unsigned *>(&fl[0]), 4u);
-        }
+        if ((unsigned)colsum[k] != c) atomicOr(&p.flags[(long long)tm * p.grid_b * p.grid_n + k / p.tile_n], 2u);
+        atomicAdd(&misc[1], (int)c);
     }
     __syncthreads();
-    for (int i = tid; i < nwords; i += 256) p.flags[(long long)pg * nwords + i] = (uint32_t)fl[i];
+    // corner: sum_n yf and sum_k yi against conv(xsum, wsum)
+    if (tid == 0) {
+        unsigned c = 0;
+        for (int j = 0; j < p.d_i; ++j)
+            for (int d = 0; d < p.d_f; ++d) c += (unsigned)p.yfi[((long long)j * p.PQ + pix) * p.d_f + d] << (8 * (j + d));
+        if ((unsigned)misc[0] != c || (unsigned)misc[1] != c) atomicOr(&p.flags[(long long)tm * p.grid_b * p.grid_n], 4u);
+    }
 }
 
 struct FinishParams {
@@ -210,28 +206,40 @@ struct FinishParams {
 };
 
 // Partial-reduction variant: add the per-tile residuals across tiles and test for zero.
-// One workgroup per pixel group.
+// Workgroup (pixel group, j): j < grid_b sums the FC residuals of batch tile j over the filter
+// tiles, j >= grid_b the IC residuals of filter tile j - grid_b over the batch tiles.  The
+// convolution kernel has zeroed every flag word; findings are OR-ed in.
 __global__ __launch_bounds__(256) void finish_i8_kernel(const FinishParams p)
 {
-    extern __shared__ int fs[];   // [grid_b][grid_n]
-    const int tid = threadIdx.x, pg = blockIdx.x;
-    const int nwords = p.grid_b * p.grid_n, mb16 = p.tile_batch * 16, wk256 = p.wk * 256;
-    for (int i = tid; i < nwords; i += 256) fs[i] = 0;
-    __syncthreads();
-    for (int i = tid; i < p.grid_b * mb16; i += 256) {
-        const int nt = i / mb16, r = i - nt * mb16;
-        unsigned s = 0;
-        for (int kt = 0; kt < p.grid_n; ++kt) s += (unsigned)p.fc[(((long long)pg * p.grid_b + nt) * p.grid_n + kt) * mb16 + r];
-        if (s != 0) atomicOr(reinterpret_cast<unsigned *>(&fs[nt * p.grid_n]), (nt * p.tile_batch + (r >> 4) < p.N) ? 1u : 4u);
+    const int tid = threadIdx.x;
+    const int per_pg = p.grid_b + p.grid_n;
+    const int pg = blockIdx.x / per_pg, j = blockIdx.x - pg * per_pg;
+    const int mb16 = p.tile_batch * 16, wk256 = p.wk * 256;
+    unsigned found = 0;
+    if (j < p.grid_b) {
+        const int nt = j;
+        const int32_t *src = p.fc + ((long long)pg * p.grid_b + nt) * p.grid_n * mb16;
+        for (int r = tid; r < mb16; r += 256) {
+            unsigned s = 0;
+#pragma unroll 4
+            for (int kt = 0; kt < p.grid_n; ++kt) s += (unsigned)src[kt * mb16 + r];
+            if (s != 0) found |= (nt * p.tile_batch + (r >> 4) < p.N) ? 1u : 4u;
+        }
+        if (found) atomicOr(&p.flags[((long long)pg * p.grid_b + nt) * p.grid_n], found);
+    } else {
+        const int kt = j - p.grid_b;
+        const int4 *src = reinterpret_cast<const int4 *>(p.ic + ((long long)pg * p.grid_n + kt) * p.grid_b * wk256);
+        for (int r = tid; r < wk256 / 4; r += 256) {
+            int4 s = {0, 0, 0, 0};
+#pragma unroll 4
+            for (int nt = 0; nt < p.grid_b; ++nt) {
+                const int4 t = src[nt * (wk256 / 4) + r];
+                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+            }
+            if ((s.x | s.y | s.z | s.w) != 0) found |= (kt * p.wk + (r >> 6) < p.kblk) ? 2u : 4u;
+        }
+        if (found) atomicOr(&p.flags[(long long)pg * p.grid_b * p.grid_n + kt], found);
     }
-    for (int i = tid; i < p.grid_n * wk256; i += 256) {
-        const int kt = i / wk256, r = i - kt * wk256;
-        unsigned s = 0;
-        for (int nt = 0; nt < p.grid_b; ++nt) s += (unsigned)p.ic[(((long long)pg * p.grid_n + kt) * p.grid_b + nt) * wk256 + r];
-        if (s != 0) atomicOr(reinterpret_cast<unsigned *>(&fs[kt]), (kt * p.wk + (r >> 8) < p.kblk) ? 2u : 4u);
-    }
-    __syncthreads();
-    for (int i = tid; i < nwords; i += 256) p.flags[(long long)pg * nwords + i] = (uint32_t)fs[i];
 }
 
 // Separate epilog (Sec. 4.3): ConvOut int32 -> int8, 4 elements per thread.
