@@ -179,6 +179,7 @@ void fill_params(ConvParams &cp, const abed_conv_desc_t *d, const Plan &pl)
     cp.n_entries = pl.n_entries; cp.n_fblk = pl.n_fblk; cp.kblk = pl.kblk;
     cp.d_f = pl.d_f; cp.d_i = pl.d_i;
     cp.grid_m = pl.grid_m; cp.grid_b = pl.grid_b; cp.grid_n = pl.grid_n;
+    cp.kt_slowest = env_int("ABED_KT_SLOWEST", (long long)d->K * pl.crs > (long long)d->N * d->H * d->W * d->C ? 1 : 0);
     cp.dbg = env_int("ABED_DBG", 0);
 }
 
@@ -208,7 +209,7 @@ abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_
     cp.x = x; cp.w = w; cp.y = y; cp.mode = MODE_PLAIN;
     if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
     set_injection(cp, d, pl, inject);
-    if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, pl.grid_m * pl.grid_b * pl.grid_n, st)) return ABED_EUNSUPPORTED;
+    if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, (pl.grid_m * pl.grid_b * pl.grid_n + 7) / 8 * 8, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("conv_kernel (unchecked)");
     return ABED_OK;
 }
@@ -371,7 +372,7 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     cp.flags = flags; cp.xchk_next = xchk_next;
     if (int8_out) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
     set_injection(cp, desc, pl, inject);
-    const int grid = pl.grid_m * pl.grid_b * pl.grid_n;
+    const int grid = (pl.grid_m * pl.grid_b * pl.grid_n + 7) / 8 * 8;   // whole rounds over the 8 XCDs
 
     if (variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE) {
         int32_t *convout = int8_out ? wsp(pl.off_convout) : (int32_t *)y;
@@ -462,7 +463,7 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
     cp.x = (const int8_t *)x; cp.w = (const int8_t *)w; cp.wchk = (const int8_t *)wchk; cp.xchk = (const int8_t *)xchk;
     cp.y = y; cp.flags = flags; cp.out_fp32 = out_fp32 ? 1 : 0; cp.rtol = rtol; cp.atol = atol;
     set_injection(cp, desc, pl, inject);
-    const int grid = pl.grid_m * pl.grid_b * pl.grid_n;
+    const int grid = (pl.grid_m * pl.grid_b * pl.grid_n + 7) / 8 * 8;   // whole rounds over the 8 XCDs
     if (variant == ABED_NONE || variant == ABED_DUPLICATE) {
         cp.mode = MODE_PLAIN;
         if (variant == ABED_DUPLICATE) fill_u32_kernel<<<1, 64, 0, st>>>(flags, 1, 0u);

@@ -76,6 +76,7 @@ struct ConvParams {
     int kblk;         // ceil(K/16): index of the digit block
     int d_f, d_i;
     int grid_m, grid_b, grid_n;
+    int kt_slowest;   // order of the tile list: 1 = filter tile slowest, 0 = pixel group slowest
     int mode;
     int out_int8, relu;
     // accumulator fault injection (tests): tile coordinates of the element
@@ -165,11 +166,25 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     const int lg = lane >> 4, lj = lane & 15;
     const bool aug = p.mode != MODE_PLAIN;
 
-    // block index -> (pixel group, batch tile, filter tile); filter tile fastest
-    int bid = blockIdx.x;
-    const int kt = bid % p.grid_n; bid /= p.grid_n;
-    const int nt = bid % p.grid_b;
-    const int pg = bid / p.grid_b;
+    // Block index -> tile.  Workgroups go to the 8 XCDs round-robin by block index, and every XCD has
+    // its own L2, so blocks b, b + 8, b + 16, ... get consecutive tiles: one XCD then works on one
+    // contiguous eighth of the tile list.  The list is ordered so that this eighth shares the larger
+    // operand: filter tile slowest when the filters outweigh the activations, pixel group slowest
+    // otherwise.  (Only locality depends on how the hardware places blocks, never the result.)
+    const int ntiles = p.grid_m * p.grid_b * p.grid_n;
+    const int per_xcd = (ntiles + 7) >> 3;
+    int bid = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    if (bid >= ntiles) return;                   // the grid is rounded up to a multiple of 8
+    int kt, nt, pg;
+    if (p.kt_slowest) {
+        pg = bid % p.grid_m; bid /= p.grid_m;
+        nt = bid % p.grid_b;
+        kt = bid / p.grid_b;
+    } else {
+        kt = bid % p.grid_n; bid /= p.grid_n;
+        nt = bid % p.grid_b;
+        pg = bid / p.grid_b;
+    }
     const int PQ = p.P * p.Q;
     const long long HWC = (long long)p.H * p.W * p.cb;      // bytes of one image
 
