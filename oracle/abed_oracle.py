@@ -25,6 +25,9 @@ What is computed, each step following the paper:
   on values reduced mod 2^32, and the exact int64 values are kept beside them;
 * the epilog of Sec. 4.3 (scale in fp32, add bias, activation, clamp to int8)
   and the next layer's batch checksum taken from the epilog's output;
+* FIC, the filter and input fmap checksum scheme, Sec. 3.3: the input is reduced
+  to a checksum of the size of one filter, its dot product with the filter
+  checksum (int64) must equal the sum of all outputs (int64);
 * fp16 (Sec. 7): double-precision reference, checksums stored as a hi/lo pair
   of fp16 tensors, comparison against a threshold.
 
@@ -257,6 +260,57 @@ def abed_int8(x, w, shape, wchk=None, xchk=None, acc_flip=None, stored_flip=None
         res["out8"] = out8
         res["xsum_next"] = batch_checksum(out8)       # [P,Q,K], the next layer's IC input
         res["xchk_next"] = split_digits(res["xsum_next"], num_digits_for_count(N))
+    return res
+
+
+# ----------------------------------------------------------------------------
+# FIC, the filter and input fmap checksum scheme (Sec. 3.3)
+# ----------------------------------------------------------------------------
+def patch_checksum(x, shape):
+    """Input fmap checksum of the FIC scheme (Sec. 3.2 option 2, used by Sec. 3.3): a
+    tensor of the size of one filter, X[r,s,c] = sum over the batch and over all
+    output positions (p,q) of the input element that filter element (r,s,c) meets
+    there, zero where the window hangs over the padding.  Exact, int64[R,S,C];
+    each entry is a sum of N*P*Q int8 values (8 + log2(PQN) bits, Sec. 4.1)."""
+    sh = shape
+    xp = np.zeros((sh.N, sh.H + 2 * sh.pad_h, sh.W + 2 * sh.pad_w, sh.C), dtype=np.int64)
+    xp[:, sh.pad_h:sh.pad_h + sh.H, sh.pad_w:sh.pad_w + sh.W] = np.asarray(x, dtype=np.int8)
+    X = np.zeros((sh.R, sh.S, sh.C), dtype=np.int64)
+    for r in range(sh.R):
+        for s_ in range(sh.S):
+            for p in range(sh.P):
+                for q in range(sh.Q):
+                    X[r, s_] += xp[:, p * sh.stride_h + r, q * sh.stride_w + s_].sum(axis=0)
+    return X
+
+
+def abed_fic_int8(x, w, shape, wsum=None, xpatch=None, acc_flip=None, epilog=None):
+    """FIC check of an int8 convolution (Sec. 3.3; widths of Sec. 4.1; tasks of Sec. 4.3).
+
+    The filter checksum wsum[r,s,c] = sum_k w[k] (int32 suffices) and the input
+    checksum X[r,s,c] (patch_checksum; int32 suffices) meet in a dot product over
+    C*R*S elements, an int64; the convolution output is reduced to one int64;
+    the two must be equal.  wsum / xpatch may be passed in to model checksums
+    made before w or x was corrupted.  acc_flip = (flat index into y, bit): one
+    accumulator bit flipped before the reduction and the store.
+
+    Returns dict: y int32[N,P,Q,K] as stored, ocs (output checksum) and dot as
+    Python ints, bad = ocs != dot, wsum, xpatch, out8 when an epilog is given."""
+    x = np.asarray(x, dtype=np.int8)
+    w = np.asarray(w, dtype=np.int8)
+    if wsum is None:
+        wsum = filter_checksum(w)
+    if xpatch is None:
+        xpatch = patch_checksum(x, shape)
+    y = wrap32(conv_int(x, w, shape)).copy()
+    if acc_flip is not None:
+        flip_bit(y, *acc_flip)
+    ocs = int(y.astype(np.int64).sum())
+    dot = int((np.asarray(xpatch, dtype=np.int64) * np.asarray(wsum, dtype=np.int64)).sum())
+    res = dict(y=y, ocs=ocs, dot=dot, bad=ocs != dot, wsum=np.asarray(wsum), xpatch=np.asarray(xpatch))
+    if epilog is not None:
+        scale, bias, relu = epilog
+        res["out8"] = epilog_int8(y, scale, bias, relu)
     return res
 
 
