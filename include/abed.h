@@ -186,6 +186,55 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
                              uint32_t *flags, void *workspace, size_t workspace_bytes,
                              const abed_inject_t *inject, void *y2, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * FIC, the filter and input fmap checksum scheme (Sec. 3.3): one scalar check per convolution.
+ *   wsum[r,s,c]  = sum_k w[k,r,s,c]                                   (filter checksum, offline, int32)
+ *   X[r,s,c]     = sum over n and over all output positions (p,q) of the input element that
+ *                  filter element (r,s,c) meets there                 (input fmap checksum, int32)
+ *   dot          = sum_{r,s,c} X[r,s,c] * wsum[r,s,c]                 (int64)
+ *   ocs          = sum of all ConvOut accumulators                    (output fmap checksum, int64)
+ * and ocs must equal dot (bit widths: Sec. 4.1; tasks and their fusion: Sec. 4.3).  The convolution
+ * runs with its original parameters: nothing is appended to it.  int8 only.
+ *
+ * The input checksum is kept in its row-wise form xrows[h,s,c] = sum over n and over the input
+ * columns that filter column s meets of x[n,h,w,c] (int32 [H][S][C]); X[r,s,c] is the sum of
+ * xrows over the input rows that filter row r meets and is formed together with the dot product.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    int64_t workspace_bytes;
+    int64_t wsum_bytes;    /* R*S*C int32 */
+    int64_t xrows_bytes;   /* H*S*C int32 */
+} abed_fic_layout_t;
+
+/* Host only.  variant: ABED_UNFUSED (one kernel per task) or ABED_FUSED_OCG (output fmap checksum
+ * generation fused into the convolution + epilog kernel); ABED_EUNSUPPORTED otherwise. */
+abed_status_t abed_fic_get_layout(const abed_conv_desc_t *desc, int32_t variant, abed_fic_layout_t *out);
+
+/* Offline (task 1 of Sec. 4.3): the filter checksum. */
+abed_status_t abed_fic_filter_prepare_int8(const abed_conv_desc_t *desc, const int8_t *w, int32_t *wsum,
+                                           void *stream);
+
+/* Online input fmap checksum generation (task 2), row-wise form; one pass over x. */
+abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, const int8_t *x, int32_t *xrows,
+                                           void *stream);
+
+/* Convolution checked by FIC (tasks 2 to 7 of Sec. 4.3).
+ *   wsum          from abed_fic_filter_prepare_int8.
+ *   xrows         xrows_bytes, caller-provided; if compute_xrows != 0 the call first runs the input
+ *                 checksum kernel into it, else it uses the contents as given (a test's).
+ *   y, epilogue   as for abed_conv_int8.
+ *   result        two int64 on the device: [0] = ocs, [1] = dot.
+ *   flag          one word on the device: 1 if ocs != dot, else 0 (written on every call).
+ *   inject        site 1 (accumulator) for both variants; site 2 (stored ConvOut) for ABED_UNFUSED.
+ * Errors as for abed_conv_int8; ABED_ERANGE if an input checksum entry could exceed int32
+ * (128 * N*P*Q >= 2^31). */
+abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+                                 const int32_t *wsum, int32_t *xrows, int32_t compute_xrows,
+                                 void *y, const abed_epilogue_t *epilogue, int32_t variant,
+                                 int64_t *result, uint32_t *flag,
+                                 void *workspace, size_t workspace_bytes,
+                                 const abed_inject_t *inject, void *stream);
+
 const char *abed_status_string(abed_status_t status);
 /* Text of the last HIP error seen by this thread's most recent failing call. */
 const char *abed_last_hip_error(void);

@@ -45,7 +45,12 @@ class Layout(ctypes.Structure):
                 ("n_flag_words", "workspace_bytes", "wchk_bytes", "xchk_bytes", "xchk_next_bytes")]
 
 
-EXPORTS = ["abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_fp16",
+class FicLayout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("workspace_bytes", "wsum_bytes", "xrows_bytes")]
+
+
+EXPORTS = ["abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
+           "abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_fp16",
            "abed_input_checksum_int8", "abed_input_checksum_fp16", "abed_workspace_init",
            "abed_conv_int8", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error"]
 
@@ -79,6 +84,11 @@ def lib():
         L.abed_input_checksum_fp16.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
         L.abed_conv_fp16.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, i32, i32, f32, f32,
                                      vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp, vp]
+        L.abed_fic_get_layout.argtypes = [ctypes.POINTER(ConvDesc), i32, ctypes.POINTER(FicLayout)]
+        L.abed_fic_filter_prepare_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+        L.abed_fic_input_checksum_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+        L.abed_fic_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
+                                         vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp]
         _LIB = L
     return _LIB
 
@@ -160,3 +170,32 @@ def conv_fp16(desc, x, w, wchk, xchk, compute_xchk, y, variant, rtol=1e-3, atol=
     _check(lib().abed_conv_fp16(ctypes.byref(desc), _p(x), _p(w), _p(wchk), _p(xchk), int(bool(compute_xchk)),
                                 _p(y), int(bool(out_fp32)), int(variant), float(rtol), float(atol), _p(flags),
                                 _p(workspace), nbytes, inj, _p(y2), _stream(stream)))
+
+
+def fic_get_layout(desc, variant):
+    out = FicLayout()
+    _check(lib().abed_fic_get_layout(ctypes.byref(desc), int(variant), ctypes.byref(out)))
+    return out
+
+
+def fic_filter_prepare_int8(desc, w, wsum, stream=None):
+    _check(lib().abed_fic_filter_prepare_int8(ctypes.byref(desc), _p(w), _p(wsum), _stream(stream)))
+
+
+def fic_input_checksum_int8(desc, x, xrows, stream=None):
+    _check(lib().abed_fic_input_checksum_int8(ctypes.byref(desc), _p(x), _p(xrows), _stream(stream)))
+
+
+def fic_conv_int8(desc, x, w, wsum, xrows, compute_xrows, y, variant, result, flag, epilogue=None,
+                  workspace=None, inject=None, stream=None):
+    """abed_fic_conv_int8.  result: int64[2] tensor, flag: int32[1] tensor (device)."""
+    epi = None
+    if epilogue is not None:
+        epi = ctypes.byref(_Epilogue(epilogue[0].data_ptr(), epilogue[1].data_ptr(), int(bool(epilogue[2]))))
+    inj = None
+    if inject is not None:
+        inj = ctypes.byref(_Inject(int(inject[0]), int(inject[1]), int(inject[2])))
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().abed_fic_conv_int8(ctypes.byref(desc), _p(x), _p(w), _p(wsum), _p(xrows), int(bool(compute_xrows)),
+                                    _p(y), epi, int(variant), _p(result), _p(flag), _p(workspace), nbytes,
+                                    inj, _stream(stream)))

@@ -8,6 +8,7 @@
 
 #include "../../include/abed.h"
 #include "aux_kernels.h"
+#include "fic_kernels.h"
 #include "conv_launch.h"
 
 using namespace abed;
@@ -229,6 +230,139 @@ const char *abed_status_string(abed_status_t s)
     case ABED_ERANGE: return "checksum needs more than four digits";
     }
     return "unknown status";
+}
+
+// ---------------------------------------------------------------------------
+// FIC scheme (Sec. 3.3)
+// ---------------------------------------------------------------------------
+namespace {
+
+abed_status_t fic_plan(const abed_conv_desc_t *desc, int variant, Plan &pl, bool int8_out)
+{
+    if (variant != ABED_UNFUSED && variant != ABED_FUSED_OCG) return desc ? ABED_EUNSUPPORTED : ABED_EINVAL;
+    abed_status_t s = make_plan(desc, ABED_INT8, ABED_NONE, int8_out, pl);
+    if (s != ABED_OK) return s;
+    if (128LL * desc->N * pl.PQ >= (1LL << 31)) return ABED_ERANGE;     // input checksum entries are int32 (Sec. 4.1)
+    if (desc->S > 7) return ABED_EUNSUPPORTED;
+    return ABED_OK;
+}
+
+abed_status_t fic_input_rows(const abed_conv_desc_t *d, const Plan &pl, const int8_t *x, int32_t *xrows,
+                             unsigned long long *zero_me, hipStream_t st)
+{
+    FicRowsParams rp;
+    rp.x = x; rp.xrows = xrows; rp.zero_me = zero_me;
+    rp.N = d->N; rp.H = d->H; rp.W = d->W; rp.C = d->C; rp.S = d->S; rp.Q = pl.Q; rp.sw = d->stride_w; rp.pw = d->pad_w;
+    const dim3 grid((unsigned)(d->H * ((d->C + 63) / 64)));
+    if (d->S <= 1) fic_input_rows_i8_kernel<1><<<grid, dim3(256), 0, st>>>(rp);
+    else if (d->S <= 3) fic_input_rows_i8_kernel<3><<<grid, dim3(256), 0, st>>>(rp);
+    else fic_input_rows_i8_kernel<7><<<grid, dim3(256), 0, st>>>(rp);
+    LAUNCH_CHECK("fic_input_rows_i8_kernel");
+    return ABED_OK;
+}
+
+}  // namespace
+
+abed_status_t abed_fic_get_layout(const abed_conv_desc_t *desc, int32_t variant, abed_fic_layout_t *out)
+{
+    if (!out) return ABED_EINVAL;
+    Plan pl;
+    abed_status_t s = fic_plan(desc, variant, pl, false);
+    if (s != ABED_OK) return s;
+    out->wsum_bytes = 4LL * pl.crs;
+    out->xrows_bytes = 4LL * desc->H * desc->S * desc->C;
+    // the unfused option with an int8 output keeps the int32 ConvOut here
+    out->workspace_bytes = variant == ABED_UNFUSED ? align256(4LL * desc->N * pl.PQ * desc->K) : 256;
+    return ABED_OK;
+}
+
+abed_status_t abed_fic_filter_prepare_int8(const abed_conv_desc_t *desc, const int8_t *w, int32_t *wsum, void *stream)
+{
+    Plan pl;
+    abed_status_t s = make_plan(desc, ABED_INT8, ABED_NONE, false, pl);
+    if (s != ABED_OK) return s;
+    if (!w || !wsum) return ABED_EINVAL;
+    fic_filter_checksum_i8_kernel<<<dim3((pl.crs + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(w, wsum, desc->K, pl.crs);
+    LAUNCH_CHECK("fic_filter_checksum_i8_kernel");
+    return ABED_OK;
+}
+
+abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, const int8_t *x, int32_t *xrows, void *stream)
+{
+    Plan pl;
+    abed_status_t s = fic_plan(desc, ABED_FUSED_OCG, pl, false);
+    if (s != ABED_OK) return s;
+    if (!x || !xrows) return ABED_EINVAL;
+    return fic_input_rows(desc, pl, x, xrows, nullptr, (hipStream_t)stream);
+}
+
+abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+                                 const int32_t *wsum, int32_t *xrows, int32_t compute_xrows,
+                                 void *y, const abed_epilogue_t *epi, int32_t variant,
+                                 int64_t *result, uint32_t *flag,
+                                 void *workspace, size_t workspace_bytes,
+                                 const abed_inject_t *inject, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const bool int8_out = epi != nullptr;
+    Plan pl;
+    abed_status_t s = fic_plan(desc, variant, pl, int8_out);
+    if (s != ABED_OK) return s;
+    if (!x || !w || !wsum || !xrows || !y || !result || !flag) return ABED_EINVAL;
+    if (epi && (!epi->scale || !epi->bias)) return ABED_EINVAL;
+    const long long npqk = (long long)desc->N * pl.PQ * desc->K;
+    if (inject && inject->site != 0) {
+        if (inject->site != 1 && inject->site != 2) return ABED_EINVAL;
+        if (inject->index < 0 || inject->index >= npqk || inject->bit < 0 || inject->bit > 31) return ABED_EINVAL;
+        if (inject->site == 2 && variant != ABED_UNFUSED) return ABED_EUNSUPPORTED;
+    }
+    const bool unfused_i8 = variant == ABED_UNFUSED && int8_out;
+    if (unfused_i8 && (!workspace || (long long)workspace_bytes < align256(4 * npqk))) return ABED_EWORKSPACE;
+    unsigned long long *ocs = (unsigned long long *)result;
+
+    // task 2: input fmap checksum generation (also clears the output checksum accumulator)
+    if (compute_xrows) {
+        if ((s = fic_input_rows(desc, pl, x, xrows, ocs, st)) != ABED_OK) return s;
+    } else {
+        fill_u64_kernel<<<1, 1, 0, st>>>(ocs, 0ull);
+        LAUNCH_CHECK("fill_u64_kernel");
+    }
+
+    // tasks 4 to 6: convolution, output fmap checksum generation, epilog
+    ConvParams cp;
+    fill_params(cp, desc, pl);
+    cp.x = x; cp.w = w; cp.mode = MODE_PLAIN;
+    set_injection(cp, desc, pl, inject);
+    const int grid = (pl.grid_m * pl.grid_b * pl.grid_n + 7) / 8 * 8;
+    if (variant == ABED_FUSED_OCG) {
+        cp.y = y; cp.fic_ocs = ocs;
+        if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
+        if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
+        LAUNCH_CHECK("conv_kernel (FIC, fused output checksum)");
+    } else {
+        int32_t *convout = unfused_i8 ? (int32_t *)workspace : (int32_t *)y;
+        cp.y = convout;
+        if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
+        LAUNCH_CHECK("conv_kernel (unchecked)");
+        if (inject && inject->site == 2) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)convout, inject->index, 1u << inject->bit);
+        long long blocks = (npqk / 4 + 255) / 256;
+        if (blocks > 2048) blocks = 2048;
+        if (blocks < 1) blocks = 1;
+        fic_output_sum_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(convout, npqk, ocs);
+        LAUNCH_CHECK("fic_output_sum_kernel");
+        if (int8_out) {
+            epilog_i8_kernel<<<dim3((unsigned)((npqk / 4 + 256) / 256)), dim3(256), 0, st>>>(convout, (int8_t *)y, epi->scale, epi->bias, epi->relu, npqk, desc->K);
+            LAUNCH_CHECK("epilog_i8_kernel");
+        }
+    }
+
+    // tasks 3 and 7: dot product of the two checksums, comparison
+    FicVerifyParams vp;
+    vp.xrows = xrows; vp.wsum = wsum; vp.result = (long long *)result; vp.flag = flag;
+    vp.H = desc->H; vp.C = desc->C; vp.R = desc->R; vp.S = desc->S; vp.P = pl.P; vp.sh = desc->stride_h; vp.ph = desc->pad_h;
+    fic_verify_kernel<<<1, 1024, 0, st>>>(vp);
+    LAUNCH_CHECK("fic_verify_kernel");
+    return ABED_OK;
 }
 
 const char *abed_last_hip_error(void) { return g_hip_error; }

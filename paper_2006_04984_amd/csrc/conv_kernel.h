@@ -85,6 +85,7 @@ struct ConvParams {
     int dbg;
     int out_fp32;      // fp16 path: 1 = fp32 output
     float rtol, atol;  // fp16 path: threshold of the checks
+    unsigned long long *fic_ocs;   // FIC scheme (Sec. 3.3): the sum of all accumulators is added here, or null
 };
 
 __device__ __forceinline__ int lds_off(int row, int chunk)
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     constexpr int L = (NB + 3) / 4;            // direct-to-LDS loads per wave and step
     constexpr int SUB = NB * 1024;              // one 64-byte step of the tile
     constexpr int STAGE = KG * SUB;
-    constexpr int EPI_BYTES = (F16 ? 8 : 4) * WK * 1024 + 64;
+    constexpr int EPI_BYTES = (F16 ? 8 : 4) * WK * 1024 + 128;
     constexpr int RED_BYTES = (KG - 1) * 4 * WM * WK * 1024;   // accumulators of groups 1..KG-1
     constexpr int LDS_MIN = EPI_BYTES > RED_BYTES ? EPI_BYTES : RED_BYTES;
     constexpr int LDS_BYTES = (NST * STAGE > LDS_MIN) ? NST * STAGE : LDS_MIN;
@@ -573,6 +574,22 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 for (int v = 0; v < 4; ++v)
                     if (wave * WM + i == p.inj_mb && kb == p.inj_kb && v == p.inj_v && lane == p.inj_lane)
                         acc[i][kb][v] ^= (int)p.inj_mask;
+    }
+
+    // (1b) FIC scheme (Sec. 3.3): output fmap checksum = the sum of all accumulators, in 64 bits
+    // (Sec. 4.1).  Rows, entries and filters beyond the problem were loaded as zeros and add nothing.
+    if (p.fic_ocs) {
+        long long t = 0;
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+            for (int kb = 0; kb < WK; ++kb)
+                t += (long long)acc[i][kb][0] + acc[i][kb][1] + acc[i][kb][2] + acc[i][kb][3];
+        for (int m = 32; m >= 1; m >>= 1) t += __shfl_xor(t, m, 64);
+        long long *e64 = reinterpret_cast<long long *>(e_misc + 16);
+        if (lane == 0) e64[wave] = t;
+        __syncthreads();
+        if (tid == 0) atomicAdd(p.fic_ocs, (unsigned long long)(e64[0] + e64[1] + e64[2] + e64[3]));
     }
 
     // (2) FC residual of every row of the tile (Sec. 3.1; digit shifts of Sec. 4.1)

@@ -1,0 +1,159 @@
+"""GPU parity of the FIC scheme (Sec. 3.3) through the C ABI against the oracle: the filter
+checksum, the row-wise input checksum (folded here to the filter-sized checksum the oracle
+defines), the two 64-bit scalars, the flag and the outputs, bit-exact; single faults in the
+accumulators, the stored ConvOut, the filters and the inputs."""
+import numpy as np
+import pytest
+import torch
+
+from synth import ConvShape, CONFIG1, CONFIG2, int8_tensors, requant_params
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+SHAPES = [
+    CONFIG1[0],
+    ConvShape(32, 9, 9, 64, 64, 3, 3, 1, 1, 1, 1, "n32_c64_k64_9x9"),
+    ConvShape(5, 7, 6, 16, 48, 3, 3, 2, 2, 1, 1, "n5_k48_stride2"),
+    ConvShape(16, 6, 5, 64, 128, 1, 1, 1, 1, 0, 0, "n16_1x1_k128"),
+    ConvShape(3, 10, 8, 16, 16, 3, 2, 1, 2, 1, 0, "n3_asym"),
+    ConvShape(48, 4, 4, 80, 96, 3, 3, 1, 1, 1, 1, "n48_c80_k96"),
+    ConvShape(2, 12, 12, 16, 64, 7, 7, 2, 2, 3, 3, "7x7_s2"),
+    ConvShape(12, 5, 5, 320, 80, 3, 3, 1, 1, 1, 1, "n12_c320_k80"),
+]
+
+
+class GpuFic:
+    def __init__(self, s, variant, int8_out=False):
+        import paper_2006_04984_amd as abed
+        self.abed, self.s, self.variant = abed, s, variant
+        self.desc = abed.desc_from_shape(s)
+        self.lay = abed.fic_get_layout(self.desc, variant)
+        self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int8 if int8_out else torch.int32, device=DEV)
+        self.wsum = torch.empty((s.R, s.S, s.C), dtype=torch.int32, device=DEV)
+        self.xrows = torch.empty((s.H, s.S, s.C), dtype=torch.int32, device=DEV)
+        self.result = torch.full((2,), -12345, dtype=torch.int64, device=DEV)
+        self.flag = torch.full((1,), 77, dtype=torch.int32, device=DEV)
+        self.ws = torch.empty((max(256, self.lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
+
+    def prepare(self, w):
+        self.w = torch.from_numpy(w).to(DEV)
+        self.abed.fic_filter_prepare_int8(self.desc, self.w, self.wsum)
+
+    def run(self, x, compute=True, epilogue=None, inject=None):
+        self.x = torch.from_numpy(x).to(DEV)
+        epi = None
+        if epilogue is not None:
+            self.scale, self.bias = torch.from_numpy(epilogue[0]).to(DEV), torch.from_numpy(epilogue[1]).to(DEV)
+            epi = (self.scale, self.bias, epilogue[2])
+        self.abed.fic_conv_int8(self.desc, self.x, self.w, self.wsum, self.xrows, compute, self.y, self.variant,
+                                self.result, self.flag, epilogue=epi, workspace=self.ws, inject=inject)
+        torch.cuda.synchronize()
+        r = self.result.cpu().numpy()
+        return self.y.cpu().numpy(), int(r[0]), int(r[1]), int(self.flag.item())
+
+
+def fold_rows(xrows, s):
+    """Row-wise input checksum -> the filter-sized one: X[r] = sum of xrows over the input rows filter row r meets."""
+    X = np.zeros((s.R, s.S, s.C), dtype=np.int64)
+    for r in range(s.R):
+        for p in range(s.P):
+            h = p * s.stride_h - s.pad_h + r
+            if 0 <= h < s.H:
+                X[r] += xrows[h]
+    return X
+
+
+@pytest.mark.parametrize("variant", [1, 4])
+@pytest.mark.parametrize("s", SHAPES, ids=lambda s: s.name)
+def test_clean_run_and_accumulator_flip(oracle, s, variant):
+    print("case", s.name, "variant", variant, flush=True)
+    lo, hi = (-8, 7) if s.name.startswith("cfg1") else (-128, 127)
+    x, w = int8_tensors(s, 6161, lo, hi)
+    ref = oracle.abed_fic_int8(x, w, s)
+    g = GpuFic(s, variant)
+    g.prepare(w)
+    y, ocs, dot, flag = g.run(x)
+    assert np.array_equal(y, ref["y"])
+    assert np.array_equal(g.wsum.cpu().numpy(), ref["wsum"])
+    assert np.array_equal(fold_rows(g.xrows.cpu().numpy().astype(np.int64), s), ref["xpatch"])
+    assert (ocs, dot, flag) == (ref["ocs"], ref["dot"], 0)
+    rng = np.random.default_rng(11)
+    for _ in range(3):
+        idx, bit = int(rng.integers(0, y.size)), int(rng.integers(0, 32))
+        print("  flip", idx, bit, flush=True)
+        ref2 = oracle.abed_fic_int8(x, w, s, acc_flip=(idx, bit))
+        y2, ocs2, dot2, flag2 = g.run(x, inject=(1, idx, bit))
+        assert np.array_equal(y2, ref2["y"])
+        assert (ocs2, dot2, flag2) == (ref2["ocs"], ref2["dot"], 1)
+    # a second clean call on the same buffers clears the flag again
+    assert g.run(x)[1:] == (ref["ocs"], ref["dot"], 0)
+
+
+@pytest.mark.parametrize("variant", [1, 4])
+@pytest.mark.parametrize("s", [SHAPES[1], SHAPES[2], SHAPES[7]], ids=lambda s: s.name)
+def test_epilog_output(oracle, s, variant):
+    print("case", s.name, "variant", variant, flush=True)
+    x, w = int8_tensors(s, 6262)
+    scale, bias = requant_params(s, 6262)
+    ref = oracle.abed_fic_int8(x, w, s, epilog=(scale, bias, True))
+    g = GpuFic(s, variant, int8_out=True)
+    g.prepare(w)
+    y, ocs, dot, flag = g.run(x, epilogue=(scale, bias, True))
+    assert np.array_equal(y, ref["out8"]) and (ocs, dot, flag) == (ref["ocs"], ref["dot"], 0)
+
+
+def test_stored_flip_filter_flip_input_flip(oracle):
+    s = SHAPES[1]
+    x, w = int8_tensors(s, 6363)
+    clean = oracle.abed_fic_int8(x, w, s)
+    # stored ConvOut corrupted between the kernels: only the unfused option reads it back
+    g = GpuFic(s, 1)
+    g.prepare(w)
+    idx, bit = 1234, 9
+    y, ocs, dot, flag = g.run(x, inject=(2, idx, bit))
+    exp = clean["y"].copy(); oracle.flip_bit(exp, idx, bit)
+    assert np.array_equal(y, exp) and flag == 1 and abs(ocs - clean["ocs"]) == 2 ** bit and dot == clean["dot"]
+    # a filter corrupted after its checksum was made
+    g = GpuFic(s, 4)
+    g.prepare(w)
+    w2 = w.copy(); w2[3, 1, 2, 5] ^= 0x20
+    g.w = torch.from_numpy(w2).to(DEV)
+    ref = oracle.abed_fic_int8(x, w2, s, wsum=clean["wsum"])
+    y, ocs, dot, flag = g.run(x)
+    assert np.array_equal(y, ref["y"]) and (ocs, dot, flag) == (ref["ocs"], ref["dot"], 1) and ref["bad"]
+    # an input corrupted after its checksum was made
+    g = GpuFic(s, 4)
+    g.prepare(w)
+    g.abed.fic_input_checksum_int8(g.desc, torch.from_numpy(x).to(DEV), g.xrows)
+    x2 = x.copy(); x2[7, 4, 4, 17] ^= 0x08
+    ref = oracle.abed_fic_int8(x2, w, s, xpatch=clean["xpatch"])
+    y, ocs, dot, flag = g.run(x2, compute=False)
+    assert np.array_equal(y, ref["y"]) and (ocs, dot, flag) == (ref["ocs"], ref["dot"], 1) and ref["bad"]
+
+
+def test_full_size_layer_scalars(oracle):
+    """A config-2 layer at full size in the launch configuration the benchmark times: the two 64-bit
+    scalars against the oracle, outputs on sampled points."""
+    s = CONFIG2[1]
+    x, w = int8_tensors(s, 2001)
+    g = GpuFic(s, 4)
+    g.prepare(w)
+    y, ocs, dot, flag = g.run(x)
+    X = oracle.patch_checksum(x, s)
+    ref_dot = int((X * oracle.filter_checksum(w)).sum())
+    assert dot == ref_dot and ocs == ref_dot and flag == 0
+    rng = np.random.default_rng(5)
+    pts = np.stack([rng.integers(0, s.N, 500), rng.integers(0, s.P, 500), rng.integers(0, s.Q, 500), rng.integers(0, s.K, 500)], axis=1)
+    exp = oracle.conv_int_points(x, w, s, pts)
+    assert np.array_equal(y[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], exp.astype(np.int32))
+
+
+def test_unsupported_variants_are_refused():
+    import paper_2006_04984_amd as abed
+    d = abed.desc_from_shape(SHAPES[1])
+    for v in (0, 2, 3, 5, 6):
+        with pytest.raises(abed.AbedError) as e:
+            abed.fic_get_layout(d, v)
+        assert e.value.status == 2
