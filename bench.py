@@ -76,6 +76,27 @@ def main():
         abed.filter_prepare_int8(L.desc, L.w, L.wchk)      # offline step, not timed (Sec. 3.4: filter checksums are made offline)
         return L
 
+    def setup_fic(s, idx, variant):
+        """Buffers for the FIC scheme (Sec. 3.3) on the same layer and data."""
+        L = Layer()
+        L.s, L.variant = s, Variant(variant)
+        L.desc = abed.desc_from_shape(s)
+        lay = abed.fic_get_layout(L.desc, L.variant)
+        x, w = int8_tensors(s, seed_for(2, idx))
+        L.x = torch.from_numpy(x).to(dev)
+        L.w = torch.from_numpy(w).to(dev)
+        L.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int32, device=dev)
+        L.wsum = torch.empty((s.R, s.S, s.C), dtype=torch.int32, device=dev)
+        L.xrows = torch.empty((lay.xrows_parts, s.H, s.S, s.C), dtype=torch.int32, device=dev)
+        L.result = torch.zeros((2,), dtype=torch.int64, device=dev)
+        L.flag = torch.zeros((1,), dtype=torch.int32, device=dev)
+        L.ws = torch.zeros((max(256, lay.workspace_bytes),), dtype=torch.uint8, device=dev)
+        abed.fic_filter_prepare_int8(L.desc, L.w, L.wsum)   # offline step, not timed
+        return L
+
+    def run_fic(L):
+        abed.fic_conv_int8(L.desc, L.x, L.w, L.wsum, L.xrows, True, L.y, L.variant, L.result, L.flag, workspace=L.ws)
+
     def run_layer(L, compute_xchk=True):
         abed.conv_int8(L.desc, L.x, L.w, L.wchk, L.xchk, compute_xchk, L.y, L.variant, flags=L.flags,
                        workspace=L.ws, y2=L.y2)
@@ -155,6 +176,14 @@ def main():
     for v in wanted[1:]:
         t_var[v] = time_steps(step_of(v), max(20, args.steps // 2 // 10 * 10), max(10, args.warmup // 2))
     t_unchecked = t_var[Variant.NONE]
+    # the paper's own FIC scheme (one scalar check per layer), fused and unfused options
+    fic_sets = {v: [setup_fic(s, i, v) for i, s in enumerate(layers)] for v in (Variant.FUSED_OCG, Variant.UNFUSED)}
+    t_fic = {}
+    for v, Ls in fic_sets.items():
+        t_fic[v] = time_steps(lambda: [run_fic(L) for L in Ls], max(20, args.steps // 2 // 10 * 10), max(10, args.warmup // 2))
+        for L in Ls:
+            r = L.result.cpu().numpy()
+            assert int(L.flag.item()) == 0 and r[0] == r[1], "FIC mismatch on a fault-free run"
     t_checked_eager = time_eager(step_of(Variant.FUSED_OCG), max(20, args.steps // 4), 5)
     t_dup = t_var[Variant.DUPLICATE]
 
@@ -196,6 +225,12 @@ def main():
                duplicate_overhead_pct=100.0 * (t_dup / t_unchecked - 1.0),
                speedup_vs_duplicate=t_dup / t_checked,
                variant_overhead_pct={v.name: 100.0 * (t / t_unchecked - 1.0) for v, t in t_var.items() if v != Variant.NONE},
+               fic=dict(note="FIC scheme of Sec. 3.3 (input patch checksum . filter checksum == sum of ConvOut, int64): "
+                             "input checksum kernel + convolution with fused output checksum + dot/compare kernel",
+                        fused_tops=total_ops / t_fic[Variant.FUSED_OCG] / 1e12,
+                        fused_overhead_pct=100.0 * (t_fic[Variant.FUSED_OCG] / t_unchecked - 1.0),
+                        unfused_tops=total_ops / t_fic[Variant.UNFUSED] / 1e12,
+                        unfused_overhead_pct=100.0 * (t_fic[Variant.UNFUSED] / t_unchecked - 1.0)),
                per_layer=per_layer, roofline=roofline)
 
     if not args.no_cpu_baseline:

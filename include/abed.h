@@ -196,14 +196,17 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
  * and ocs must equal dot (bit widths: Sec. 4.1; tasks and their fusion: Sec. 4.3).  The convolution
  * runs with its original parameters: nothing is appended to it.  int8 only.
  *
- * The input checksum is kept in its row-wise form xrows[h,s,c] = sum over n and over the input
- * columns that filter column s meets of x[n,h,w,c] (int32 [H][S][C]); X[r,s,c] is the sum of
- * xrows over the input rows that filter row r meets and is formed together with the dot product.
+ * The input checksum is kept in its row-wise form xrows[j,h,s,c] = sum over the images n of part j of
+ * the batch and over the input columns that filter column s meets of x[n,h,w,c] (int32
+ * [xrows_parts][H][S][C]; the kernel splits the batch into parts to have enough workgroups).
+ * X[r,s,c] is the sum of xrows over the parts and over the input rows that filter row r meets;
+ * that sum is formed together with the dot product.
  * ------------------------------------------------------------------------------------------ */
 typedef struct {
     int64_t workspace_bytes;
     int64_t wsum_bytes;    /* R*S*C int32 */
-    int64_t xrows_bytes;   /* H*S*C int32 */
+    int64_t xrows_bytes;   /* xrows_parts*H*S*C int32 */
+    int32_t xrows_parts;   /* parts of the batch summed separately */
 } abed_fic_layout_t;
 
 /* Host only.  variant: ABED_UNFUSED (one kernel per task) or ABED_FUSED_OCG (output fmap checksum
@@ -225,6 +228,7 @@ abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, const i
  *   y, epilogue   as for abed_conv_int8.
  *   result        two int64 on the device: [0] = ocs, [1] = dot.
  *   flag          one word on the device: 1 if ocs != dot, else 0 (written on every call).
+ *   workspace     workspace_bytes of scratch (partial output checksums; ConvOut of the unfused option).
  *   inject        site 1 (accumulator) for both variants; site 2 (stored ConvOut) for ABED_UNFUSED.
  * Errors as for abed_conv_int8; ABED_ERANGE if an input checksum entry could exceed int32
  * (128 * N*P*Q >= 2^31). */

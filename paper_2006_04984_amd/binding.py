@@ -46,7 +46,7 @@ class Layout(ctypes.Structure):
 
 
 class FicLayout(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int64) for n in ("workspace_bytes", "wsum_bytes", "xrows_bytes")]
+    _fields_ = [(n, ctypes.c_int64) for n in ("workspace_bytes", "wsum_bytes", "xrows_bytes")] + [("xrows_parts", ctypes.c_int32)]
 
 
 EXPORTS = ["abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",

@@ -247,19 +247,36 @@ abed_status_t fic_plan(const abed_conv_desc_t *desc, int variant, Plan &pl, bool
     return ABED_OK;
 }
 
-abed_status_t fic_input_rows(const abed_conv_desc_t *d, const Plan &pl, const int8_t *x, int32_t *xrows,
-                             unsigned long long *zero_me, hipStream_t st)
+// parts of the batch the input checksum kernel works on side by side: enough workgroups for the chip
+int fic_parts(const abed_conv_desc_t *d)
+{
+    const int per_part = d->H * ((d->C + 63) / 64);
+    int parts = (512 + per_part - 1) / per_part;
+    if (parts > 8) parts = 8;
+    if (parts > d->N) parts = d->N;
+    return parts < 1 ? 1 : parts;
+}
+
+int fic_rows_blocks(const abed_conv_desc_t *d) { return fic_parts(d) * d->H * ((d->C + 63) / 64); }
+
+// Input checksum kernel.  wsum/dotpart null: only xrows is made.  from_rows: xrows is given and only
+// the partial dot products are formed from it.
+abed_status_t fic_input_rows(const abed_conv_desc_t *d, const Plan &pl, const int8_t *x, const int32_t *wsum,
+                             int32_t *xrows, long long *dotpart, bool from_rows, hipStream_t st)
 {
     FicRowsParams rp;
-    rp.x = x; rp.xrows = xrows; rp.zero_me = zero_me;
-    rp.N = d->N; rp.H = d->H; rp.W = d->W; rp.C = d->C; rp.S = d->S; rp.Q = pl.Q; rp.sw = d->stride_w; rp.pw = d->pad_w;
-    const dim3 grid((unsigned)(d->H * ((d->C + 63) / 64)));
+    rp.x = x; rp.wsum = wsum; rp.xrows = xrows; rp.dotpart = dotpart; rp.parts = fic_parts(d); rp.from_rows = from_rows ? 1 : 0;
+    rp.N = d->N; rp.H = d->H; rp.W = d->W; rp.C = d->C; rp.R = wsum ? d->R : 0; rp.S = d->S; rp.P = pl.P; rp.Q = pl.Q;
+    rp.sh = d->stride_h; rp.sw = d->stride_w; rp.ph = d->pad_h; rp.pw = d->pad_w;
+    const dim3 grid((unsigned)fic_rows_blocks(d));
     if (d->S <= 1) fic_input_rows_i8_kernel<1><<<grid, dim3(256), 0, st>>>(rp);
     else if (d->S <= 3) fic_input_rows_i8_kernel<3><<<grid, dim3(256), 0, st>>>(rp);
     else fic_input_rows_i8_kernel<7><<<grid, dim3(256), 0, st>>>(rp);
     LAUNCH_CHECK("fic_input_rows_i8_kernel");
     return ABED_OK;
 }
+
+const int kFicSumBlocks = 1024;   // workgroups (= partial sums) of the separate output checksum pass
 
 }  // namespace
 
@@ -270,9 +287,13 @@ abed_status_t abed_fic_get_layout(const abed_conv_desc_t *desc, int32_t variant,
     abed_status_t s = fic_plan(desc, variant, pl, false);
     if (s != ABED_OK) return s;
     out->wsum_bytes = 4LL * pl.crs;
-    out->xrows_bytes = 4LL * desc->H * desc->S * desc->C;
-    // the unfused option with an int8 output keeps the int32 ConvOut here
-    out->workspace_bytes = variant == ABED_UNFUSED ? align256(4LL * desc->N * pl.PQ * desc->K) : 256;
+    out->xrows_parts = fic_parts(desc);
+    out->xrows_bytes = 4LL * out->xrows_parts * desc->H * desc->S * desc->C;
+    // partial output checksums (one per tile / per workgroup of the separate pass); the unfused
+    // option keeps the int32 ConvOut behind them when the output is int8
+    const long long partials = align256(8LL * (variant == ABED_UNFUSED ? kFicSumBlocks : (long long)pl.grid_m * pl.grid_b * pl.grid_n));
+    const long long dotparts = align256(8LL * fic_rows_blocks(desc));
+    out->workspace_bytes = partials + dotparts + (variant == ABED_UNFUSED ? align256(4LL * desc->N * pl.PQ * desc->K) : 0);
     return ABED_OK;
 }
 
@@ -293,7 +314,7 @@ abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, const i
     abed_status_t s = fic_plan(desc, ABED_FUSED_OCG, pl, false);
     if (s != ABED_OK) return s;
     if (!x || !xrows) return ABED_EINVAL;
-    return fic_input_rows(desc, pl, x, xrows, nullptr, (hipStream_t)stream);
+    return fic_input_rows(desc, pl, x, nullptr, xrows, nullptr, false, (hipStream_t)stream);
 }
 
 abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
@@ -316,39 +337,38 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
         if (inject->index < 0 || inject->index >= npqk || inject->bit < 0 || inject->bit > 31) return ABED_EINVAL;
         if (inject->site == 2 && variant != ABED_UNFUSED) return ABED_EUNSUPPORTED;
     }
-    const bool unfused_i8 = variant == ABED_UNFUSED && int8_out;
-    if (unfused_i8 && (!workspace || (long long)workspace_bytes < align256(4 * npqk))) return ABED_EWORKSPACE;
-    unsigned long long *ocs = (unsigned long long *)result;
+    abed_fic_layout_t lay;
+    if ((s = abed_fic_get_layout(desc, variant, &lay)) != ABED_OK) return s;
+    if (!workspace || (long long)workspace_bytes < lay.workspace_bytes) return ABED_EWORKSPACE;
+    const int ntiles = pl.grid_m * pl.grid_b * pl.grid_n;
+    long long *partial = (long long *)workspace;
+    const long long npart_bytes = align256(8LL * (variant == ABED_UNFUSED ? kFicSumBlocks : ntiles));
+    long long *dotpart = (long long *)((char *)workspace + npart_bytes);
+    const long long convout_off = npart_bytes + align256(8LL * fic_rows_blocks(desc));
 
-    // task 2: input fmap checksum generation (also clears the output checksum accumulator)
-    if (compute_xrows) {
-        if ((s = fic_input_rows(desc, pl, x, xrows, ocs, st)) != ABED_OK) return s;
-    } else {
-        fill_u64_kernel<<<1, 1, 0, st>>>(ocs, 0ull);
-        LAUNCH_CHECK("fill_u64_kernel");
-    }
+    // tasks 2 and 3: input fmap checksum generation and its partial dot products with the filter checksum
+    if ((s = fic_input_rows(desc, pl, x, wsum, xrows, dotpart, !compute_xrows, st)) != ABED_OK) return s;
 
     // tasks 4 to 6: convolution, output fmap checksum generation, epilog
     ConvParams cp;
     fill_params(cp, desc, pl);
     cp.x = x; cp.w = w; cp.mode = MODE_PLAIN;
     set_injection(cp, desc, pl, inject);
-    const int grid = (pl.grid_m * pl.grid_b * pl.grid_n + 7) / 8 * 8;
+    const int grid = (ntiles + 7) / 8 * 8;
+    int npartial;
     if (variant == ABED_FUSED_OCG) {
-        cp.y = y; cp.fic_ocs = ocs;
+        cp.y = y; cp.fic_ocs = partial; npartial = ntiles;
         if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
         if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
         LAUNCH_CHECK("conv_kernel (FIC, fused output checksum)");
     } else {
-        int32_t *convout = unfused_i8 ? (int32_t *)workspace : (int32_t *)y;
+        int32_t *convout = int8_out ? (int32_t *)((char *)workspace + convout_off) : (int32_t *)y;
         cp.y = convout;
         if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
         LAUNCH_CHECK("conv_kernel (unchecked)");
         if (inject && inject->site == 2) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)convout, inject->index, 1u << inject->bit);
-        long long blocks = (npqk / 4 + 255) / 256;
-        if (blocks > 2048) blocks = 2048;
-        if (blocks < 1) blocks = 1;
-        fic_output_sum_kernel<<<dim3((unsigned)blocks), dim3(256), 0, st>>>(convout, npqk, ocs);
+        npartial = kFicSumBlocks;
+        fic_output_sum_kernel<<<dim3(kFicSumBlocks), dim3(256), 0, st>>>(convout, npqk, partial);
         LAUNCH_CHECK("fic_output_sum_kernel");
         if (int8_out) {
             epilog_i8_kernel<<<dim3((unsigned)((npqk / 4 + 256) / 256)), dim3(256), 0, st>>>(convout, (int8_t *)y, epi->scale, epi->bias, epi->relu, npqk, desc->K);
@@ -358,8 +378,8 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
 
     // tasks 3 and 7: dot product of the two checksums, comparison
     FicVerifyParams vp;
-    vp.xrows = xrows; vp.wsum = wsum; vp.result = (long long *)result; vp.flag = flag;
-    vp.H = desc->H; vp.C = desc->C; vp.R = desc->R; vp.S = desc->S; vp.P = pl.P; vp.sh = desc->stride_h; vp.ph = desc->pad_h;
+    vp.dotpart = dotpart; vp.partial = partial; vp.result = (long long *)result; vp.flag = flag;
+    vp.ndot = fic_rows_blocks(desc); vp.npartial = npartial;
     fic_verify_kernel<<<1, 1024, 0, st>>>(vp);
     LAUNCH_CHECK("fic_verify_kernel");
     return ABED_OK;

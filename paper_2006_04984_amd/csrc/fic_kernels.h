@@ -13,8 +13,8 @@
 // input columns that filter column s meets do not depend on each other.  So it is made in two
 // steps: xrows[h,s,c] = sum over n and over the input columns w that filter column s meets of
 // x[n,h,w,c] (one pass over x, the ICG kernel), then X[r,s,c] = sum over the input rows h that
-// filter row r meets of xrows[h,s,c], which is so small that it rides in the kernel that also
-// takes the dot product and compares.
+// filter row r meets of xrows[h,s,c].  The second step is folded into the dot product, whose
+// partial sums the ICG kernel forms while it still holds its piece of xrows.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -32,65 +32,123 @@ __global__ void fic_filter_checksum_i8_kernel(const int8_t *w, int32_t *wsum, in
 
 struct FicRowsParams {
     const int8_t *x;
-    int32_t *xrows;               // [H][S][C]
-    unsigned long long *zero_me;  // a word to clear (the output checksum accumulator), or null
-    int N, H, W, C, S, Q, sw, pw;
+    const int32_t *wsum;          // [R][S][C]
+    int32_t *xrows;               // [parts][H][S][C]
+    long long *dotpart;           // one partial dot product per workgroup [parts * H * ceil(C/64)], or null (then R = 0)
+    int N, H, W, C, R, S, P, Q, sh, sw, ph, pw, parts;
+    int from_rows;                // 1: xrows is given, only the partial dot products are formed
 };
 
-// One workgroup per (input row h, group of 64 channels).  Lane t: 16-byte channel chunk t & 3 of the
-// group, slot t >> 2 of 64 slots that stride over the (image, column) pairs of the row.
+// sum of wsum[r][rest] over the filter rows r that meet input row h:  h = q*sh - ph + r for an output row q
+__device__ __forceinline__ long long fic_wsum_meeting_row(const int32_t *wsum, int rest, int sc, int h, int R, int P, int sh, int ph)
+{
+    long long wv = 0;
+    for (int r = 0; r < R; ++r) {
+        const int t = h + ph - r;
+        if (t >= 0 && t % sh == 0 && t / sh < P) wv += wsum[r * sc + rest];
+    }
+    return wv;
+}
+
+// One workgroup per (part of the batch, input row h, group of 64 channels).  Phase 1: lane t takes the
+// 16-byte channel chunk t & 3 of the group and slot t >> 2 of 64 slots; a slot is one input column w
+// (and, when the row is short, one of several interleaved subsets of the part's images); the lane sums
+// its column over its images and leaves the 16 sums in LDS.  Phase 2: thread (s, c) adds the slots whose
+// column w meets filter column s.  The workgroup then stores its piece of xrows and its share of the
+// dot product with the filter checksum:
+//   sum_{r,s,c} X * wsum = sum_{h,s,c} xrows[h,s,c] * (sum of wsum[r,s,c] over the filter rows r that meet h).
 template <int SMAX>
 __global__ __launch_bounds__(256) void fic_input_rows_i8_kernel(const FicRowsParams p)
 {
-    __shared__ int red[4][SMAX][64];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ __attribute__((aligned(16))) int cols[64][64];   // [slot][channel of the group]
+    __shared__ unsigned char meets[SMAX][64];                   // does the slot's column meet filter column s
+    __shared__ long long dsum[4];
+    const int tid = threadIdx.x;
     const int cgroups = (p.C + 63) / 64;
-    const int h = blockIdx.x / cgroups, cg = blockIdx.x - h * cgroups;
-    if (blockIdx.x == 0 && tid == 0 && p.zero_me) *p.zero_me = 0ull;
-    const int chunk = tid & 3, slot = tid >> 2;
-    const int c0 = cg * 64 + chunk * 16;
-    int acc[SMAX][16];
+    int b = blockIdx.x;
+    const int cg = b % cgroups; b /= cgroups;
+    const int h = b % p.H;
+    const int part = b / p.H;
+    const int sc = p.S * p.C;
+    int32_t *rows = p.xrows + ((long long)part * p.H + h) * sc;
+    int acc[(SMAX * 64 + 255) / 256];                           // phase-2 sums of elements tid, tid + 256, ...
+    long long wv[(SMAX * 64 + 255) / 256];                      // their factors of the dot product (fetched early)
 #pragma unroll
-    for (int s = 0; s < SMAX; ++s)
+    for (int j = 0; j < (SMAX * 64 + 255) / 256; ++j) {
+        acc[j] = 0;
+        const int e = tid + 256 * j;
+        const int s = e >> 6, c = cg * 64 + (e & 63);
+        wv[j] = (e < SMAX * 64 && s < p.S && c < p.C) ? fic_wsum_meeting_row(p.wsum, s * p.C + c, sc, h, p.R, p.P, p.sh, p.ph) : 0;
+    }
+    if (!p.from_rows) {
+        const int chunk = tid & 3, slot = tid >> 2;
+        const int c0 = cg * 64 + chunk * 16;
+        const int n_lo = p.N * part / p.parts, n_hi = p.N * (part + 1) / p.parts;
+        const int nsub = p.W >= 64 ? 1 : 64 / p.W;              // image subsets side by side when the row is short
+        const int sub = slot / p.W, w_first = slot - sub * p.W;
+        const long long img = (long long)p.H * p.W * p.C;
+        for (int w0 = 0; w0 < p.W; w0 += 64) {                  // 64 columns at a time
+            const int w = w0 + w_first;
+            int tot[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[s][i] = 0;
-    if (c0 < p.C) {
-        const int pairs = p.N * p.W;
-        for (int idx = slot; idx < pairs; idx += 64) {
-            const int n = idx / p.W, w = idx - n * p.W;
-            const int4 v = *reinterpret_cast<const int4 *>(p.x + (((long long)n * p.H + h) * p.W + w) * p.C + c0);
-            const int words[4] = {v.x, v.y, v.z, v.w};
+            for (int i = 0; i < 16; ++i) tot[i] = 0;
+            const bool live = c0 < p.C && sub < nsub && w < p.W;
+            if (live) {
+                const int8_t *src = p.x + ((long long)h * p.W + w) * p.C + c0;
+#pragma unroll 4
+                for (int n = n_lo + sub; n < n_hi; n += nsub) {
+                    const int4 v = *reinterpret_cast<const int4 *>(src + n * img);
+                    const int words[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int s = 0; s < SMAX; ++s) {
-                // does filter column s meet input column w at some output column q?  w = q*sw - pw + s
-                const int t = w + p.pw - s;
-                const bool hit = s < p.S && t >= 0 && t % p.sw == 0 && t / p.sw < p.Q;
-                if (hit) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[s][i] += (int)(int8_t)(words[i >> 2] >> (8 * (i & 3)));
+                    for (int i = 0; i < 16; ++i) tot[i] += (int)(int8_t)(words[i >> 2] >> (8 * (i & 3)));
                 }
             }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<int4 *>(&cols[slot][chunk * 16 + q * 4]) = make_int4(tot[4 * q], tot[4 * q + 1], tot[4 * q + 2], tot[4 * q + 3]);
+            for (int e = tid; e < SMAX * 64; e += 256) {
+                // does filter column s meet input column w at some output column q?  w = q*sw - pw + s
+                const int s = e >> 6, sl = e & 63;
+                const int sb = sl / p.W, wc = w0 + sl - sb * p.W;
+                const int t = wc + p.pw - s;
+                meets[s][sl] = (s < p.S && sb < nsub && wc < p.W && t >= 0 && t % p.sw == 0 && t / p.sw < p.Q) ? 1 : 0;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < (SMAX * 64 + 255) / 256; ++j) {
+                const int e = tid + 256 * j;
+                if (e < SMAX * 64) {
+                    const int s = e >> 6, c = e & 63;
+                    int a = 0;
+#pragma unroll 8
+                    for (int sl = 0; sl < 64; ++sl) a += meets[s][sl] ? cols[sl][c] : 0;
+                    acc[j] += a;
+                }
+            }
+            __syncthreads();
         }
     }
-    // sum over the 16 slots of a wave (lanes with the same chunk: lane bits 2..5), then over the 4 waves
+    long long dot = 0;
 #pragma unroll
-    for (int s = 0; s < SMAX; ++s)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            int v = acc[s][i];
-            v += __shfl_xor(v, 4, 64); v += __shfl_xor(v, 8, 64); v += __shfl_xor(v, 16, 64); v += __shfl_xor(v, 32, 64);
-            if (lane < 4) red[wave][s][lane * 16 + i] = v;
+    for (int j = 0; j < (SMAX * 64 + 255) / 256; ++j) {
+        const int e = tid + 256 * j;
+        const int s = e >> 6, c = cg * 64 + (e & 63);
+        if (e < SMAX * 64 && s < p.S && c < p.C) {
+            int xr;
+            if (p.from_rows) xr = rows[s * p.C + c];
+            else { xr = acc[j]; rows[s * p.C + c] = xr; }
+            dot += (long long)xr * wv[j];
         }
+    }
+    for (int m = 32; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
+    if ((tid & 63) == 0) dsum[tid >> 6] = dot;
     __syncthreads();
-    for (int i = tid; i < p.S * 64; i += 256) {
-        const int s = i >> 6, c = i & 63;
-        if (cg * 64 + c < p.C)
-            p.xrows[((long long)h * p.S + s) * p.C + cg * 64 + c] = red[0][s][c] + red[1][s][c] + red[2][s][c] + red[3][s][c];
-    }
+    if (tid == 0 && p.dotpart) p.dotpart[blockIdx.x] = dsum[0] + dsum[1] + dsum[2] + dsum[3];
 }
 
-// Output fmap checksum of the unfused option: one more pass over the stored int32 ConvOut.
-__global__ __launch_bounds__(256) void fic_output_sum_kernel(const int32_t *y, long long total, unsigned long long *ocs)
+// Output fmap checksum of the unfused option: one more pass over the stored int32 ConvOut; one
+// partial sum per workgroup.
+__global__ __launch_bounds__(256) void fic_output_sum_kernel(const int32_t *y, long long total, long long *partial)
 {
     __shared__ long long part[4];
     long long s = 0;
@@ -106,44 +164,35 @@ __global__ __launch_bounds__(256) void fic_output_sum_kernel(const int32_t *y, l
     for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
     __syncthreads();
-    if (threadIdx.x == 0) atomicAdd(ocs, (unsigned long long)(part[0] + part[1] + part[2] + part[3]));
+    if (threadIdx.x == 0) partial[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
 }
 
 struct FicVerifyParams {
-    const int32_t *xrows;   // [H][S][C]
-    const int32_t *wsum;    // [R][S][C]
-    long long *result;      // [0] output checksum (read), [1] dot product (written)
-    uint32_t *flag;         // 1 = the two differ
-    int H, C, R, S, P, sh, ph;
+    const long long *dotpart;   // partial dot products, one per workgroup of the input checksum kernel
+    const long long *partial;   // output checksum partials, one per producer workgroup
+    long long *result;          // [0] output checksum, [1] dot product
+    uint32_t *flag;             // 1 = the two differ
+    int ndot, npartial;
 };
 
-// X[r,s,c] = sum over the input rows that filter row r meets, dot product with wsum, comparison.
-// One workgroup; the tensors have C*R*S entries (at most 64K).
+// Tasks 3 and 7 of Sec. 4.3, last step: add up the partial dot products and the partial output
+// checksums and compare the two 64-bit values.  One workgroup.
 __global__ __launch_bounds__(1024) void fic_verify_kernel(const FicVerifyParams p)
 {
-    __shared__ long long part[16];
-    const int sc = p.S * p.C;
-    long long dot = 0;
-    for (int e = threadIdx.x; e < p.R * sc; e += 1024) {
-        const int r = e / sc, rest = e - r * sc;          // rest = s*C + c
-        int X = 0;
-        for (int q = 0; q < p.P; ++q) {
-            const int h = q * p.sh - p.ph + r;
-            if (h >= 0 && h < p.H) X += p.xrows[(long long)h * sc + rest];
-        }
-        dot += (long long)X * p.wsum[e];
-    }
-    for (int m = 32; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = dot;
+    __shared__ long long part[2][16];
+    long long dot = 0, ocs = 0;
+    for (int i = threadIdx.x; i < p.ndot; i += 1024) dot += p.dotpart[i];
+    for (int i = threadIdx.x; i < p.npartial; i += 1024) ocs += p.partial[i];
+    for (int m = 32; m >= 1; m >>= 1) { dot += __shfl_xor(dot, m, 64); ocs += __shfl_xor(ocs, m, 64); }
+    if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = dot; part[1][threadIdx.x >> 6] = ocs; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        long long d = 0;
-        for (int i = 0; i < 16; ++i) d += part[i];
+        long long d = 0, o = 0;
+        for (int i = 0; i < 16; ++i) { d += part[0][i]; o += part[1][i]; }
+        p.result[0] = o;
         p.result[1] = d;
-        *p.flag = (p.result[0] != d) ? 1u : 0u;
+        *p.flag = (o != d) ? 1u : 0u;
     }
 }
-
-__global__ void fill_u64_kernel(unsigned long long *p, unsigned long long v) { *p = v; }
 
 }  // namespace abed

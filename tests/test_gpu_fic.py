@@ -32,7 +32,7 @@ class GpuFic:
         self.lay = abed.fic_get_layout(self.desc, variant)
         self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int8 if int8_out else torch.int32, device=DEV)
         self.wsum = torch.empty((s.R, s.S, s.C), dtype=torch.int32, device=DEV)
-        self.xrows = torch.empty((s.H, s.S, s.C), dtype=torch.int32, device=DEV)
+        self.xrows = torch.empty((self.lay.xrows_parts, s.H, s.S, s.C), dtype=torch.int32, device=DEV)
         self.result = torch.full((2,), -12345, dtype=torch.int64, device=DEV)
         self.flag = torch.full((1,), 77, dtype=torch.int32, device=DEV)
         self.ws = torch.empty((max(256, self.lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
@@ -77,7 +77,7 @@ def test_clean_run_and_accumulator_flip(oracle, s, variant):
     y, ocs, dot, flag = g.run(x)
     assert np.array_equal(y, ref["y"])
     assert np.array_equal(g.wsum.cpu().numpy(), ref["wsum"])
-    assert np.array_equal(fold_rows(g.xrows.cpu().numpy().astype(np.int64), s), ref["xpatch"])
+    assert np.array_equal(fold_rows(g.xrows.cpu().numpy().astype(np.int64).sum(axis=0), s), ref["xpatch"])
     assert (ocs, dot, flag) == (ref["ocs"], ref["dot"], 0)
     rng = np.random.default_rng(11)
     for _ in range(3):
