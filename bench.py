@@ -91,6 +91,7 @@ def main():
         L.result = torch.zeros((2,), dtype=torch.int64, device=dev)
         L.flag = torch.zeros((1,), dtype=torch.int32, device=dev)
         L.ws = torch.zeros((max(256, lay.workspace_bytes),), dtype=torch.uint8, device=dev)
+        abed.workspace_init(L.ws)
         abed.fic_filter_prepare_int8(L.desc, L.w, L.wsum)   # offline step, not timed
         return L
 
@@ -226,7 +227,7 @@ def main():
                speedup_vs_duplicate=t_dup / t_checked,
                variant_overhead_pct={v.name: 100.0 * (t / t_unchecked - 1.0) for v, t in t_var.items() if v != Variant.NONE},
                fic=dict(note="FIC scheme of Sec. 3.3 (input patch checksum . filter checksum == sum of ConvOut, int64): "
-                             "input checksum kernel + convolution with fused output checksum + dot/compare kernel",
+                             "fused option = the input checksum workgroups ride in the convolution's launch, then a one-workgroup kernel adds up the partial sums and compares",
                         fused_tops=total_ops / t_fic[Variant.FUSED_OCG] / 1e12,
                         fused_overhead_pct=100.0 * (t_fic[Variant.FUSED_OCG] / t_unchecked - 1.0),
                         unfused_tops=total_ops / t_fic[Variant.UNFUSED] / 1e12,

@@ -217,9 +217,10 @@ abed_status_t abed_fic_get_layout(const abed_conv_desc_t *desc, int32_t variant,
 abed_status_t abed_fic_filter_prepare_int8(const abed_conv_desc_t *desc, const int8_t *w, int32_t *wsum,
                                            void *stream);
 
-/* Online input fmap checksum generation (task 2), row-wise form; one pass over x. */
-abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, const int8_t *x, int32_t *xrows,
-                                           void *stream);
+/* Online input fmap checksum generation (task 2), row-wise form; one pass over x.  xrows has the
+ * layout abed_fic_get_layout reports for the same variant. */
+abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, int32_t variant, const int8_t *x,
+                                           int32_t *xrows, void *stream);
 
 /* Convolution checked by FIC (tasks 2 to 7 of Sec. 4.3).
  *   wsum          from abed_fic_filter_prepare_int8.
@@ -228,7 +229,10 @@ abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, const i
  *   y, epilogue   as for abed_conv_int8.
  *   result        two int64 on the device: [0] = ocs, [1] = dot.
  *   flag          one word on the device: 1 if ocs != dot, else 0 (written on every call).
- *   workspace     workspace_bytes of scratch (partial output checksums; ConvOut of the unfused option).
+ *   workspace     workspace_bytes of scratch, 256-byte aligned (partial sums, ConvOut of the unfused option).
+ * ABED_FUSED_OCG is two launches: the input checksum workgroups ride in front of the convolution's
+ * tiles in one launch (they do not depend on each other), then a one-workgroup kernel adds up the
+ * partial sums and compares.
  *   inject        site 1 (accumulator) for both variants; site 2 (stored ConvOut) for ABED_UNFUSED.
  * Errors as for abed_conv_int8; ABED_ERANGE if an input checksum entry could exceed int32
  * (128 * N*P*Q >= 2^31). */

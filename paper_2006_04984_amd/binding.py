@@ -86,7 +86,7 @@ def lib():
                                      vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp, vp]
         L.abed_fic_get_layout.argtypes = [ctypes.POINTER(ConvDesc), i32, ctypes.POINTER(FicLayout)]
         L.abed_fic_filter_prepare_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
-        L.abed_fic_input_checksum_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+        L.abed_fic_input_checksum_int8.argtypes = [ctypes.POINTER(ConvDesc), i32, vp, vp, vp]
         L.abed_fic_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
                                          vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp]
         _LIB = L
@@ -182,8 +182,8 @@ def fic_filter_prepare_int8(desc, w, wsum, stream=None):
     _check(lib().abed_fic_filter_prepare_int8(ctypes.byref(desc), _p(w), _p(wsum), _stream(stream)))
 
 
-def fic_input_checksum_int8(desc, x, xrows, stream=None):
-    _check(lib().abed_fic_input_checksum_int8(ctypes.byref(desc), _p(x), _p(xrows), _stream(stream)))
+def fic_input_checksum_int8(desc, variant, x, xrows, stream=None):
+    _check(lib().abed_fic_input_checksum_int8(ctypes.byref(desc), int(variant), _p(x), _p(xrows), _stream(stream)))
 
 
 def fic_conv_int8(desc, x, w, wsum, xrows, compute_xrows, y, variant, result, flag, epilogue=None,

@@ -247,28 +247,36 @@ abed_status_t fic_plan(const abed_conv_desc_t *desc, int variant, Plan &pl, bool
     return ABED_OK;
 }
 
-// parts of the batch the input checksum kernel works on side by side: enough workgroups for the chip
-int fic_parts(const abed_conv_desc_t *d)
+// Parts of the batch the input checksum workgroups take side by side.  With a launch of their own
+// (unfused option): enough workgroups for the chip.  Riding in the convolution's launch (fused option):
+// as few as keep one workgroup short, about 16 loads per lane.
+int fic_parts(const abed_conv_desc_t *d, int variant)
 {
-    const int per_part = d->H * ((d->C + 63) / 64);
-    int parts = (512 + per_part - 1) / per_part;
-    if (parts > 8) parts = 8;
+    int parts;
+    if (variant == ABED_UNFUSED) {
+        const int per_part = d->H * ((d->C + 63) / 64);
+        parts = (512 + per_part - 1) / per_part;
+        if (parts > 8) parts = 8;
+    } else {
+        const int nsub = d->W >= 64 ? 1 : 64 / d->W;      // image subsets a workgroup takes side by side
+        parts = (d->N + 16 * nsub - 1) / (16 * nsub);
+    }
     if (parts > d->N) parts = d->N;
     return parts < 1 ? 1 : parts;
 }
 
-int fic_rows_blocks(const abed_conv_desc_t *d) { return fic_parts(d) * d->H * ((d->C + 63) / 64); }
+int fic_rows_blocks(const abed_conv_desc_t *d, int variant) { return fic_parts(d, variant) * d->H * ((d->C + 63) / 64); }
 
 // Input checksum kernel.  wsum/dotpart null: only xrows is made.  from_rows: xrows is given and only
 // the partial dot products are formed from it.
-abed_status_t fic_input_rows(const abed_conv_desc_t *d, const Plan &pl, const int8_t *x, const int32_t *wsum,
+abed_status_t fic_input_rows(const abed_conv_desc_t *d, const Plan &pl, int variant, const int8_t *x, const int32_t *wsum,
                              int32_t *xrows, long long *dotpart, bool from_rows, hipStream_t st)
 {
     FicRowsParams rp;
-    rp.x = x; rp.wsum = wsum; rp.xrows = xrows; rp.dotpart = dotpart; rp.parts = fic_parts(d); rp.from_rows = from_rows ? 1 : 0;
+    rp.x = x; rp.wsum = wsum; rp.xrows = xrows; rp.dotpart = dotpart; rp.parts = fic_parts(d, variant); rp.from_rows = from_rows ? 1 : 0;
     rp.N = d->N; rp.H = d->H; rp.W = d->W; rp.C = d->C; rp.R = wsum ? d->R : 0; rp.S = d->S; rp.P = pl.P; rp.Q = pl.Q;
     rp.sh = d->stride_h; rp.sw = d->stride_w; rp.ph = d->pad_h; rp.pw = d->pad_w;
-    const dim3 grid((unsigned)fic_rows_blocks(d));
+    const dim3 grid((unsigned)fic_rows_blocks(d, variant));
     if (d->S <= 1) fic_input_rows_i8_kernel<1><<<grid, dim3(256), 0, st>>>(rp);
     else if (d->S <= 3) fic_input_rows_i8_kernel<3><<<grid, dim3(256), 0, st>>>(rp);
     else fic_input_rows_i8_kernel<7><<<grid, dim3(256), 0, st>>>(rp);
@@ -287,13 +295,13 @@ abed_status_t abed_fic_get_layout(const abed_conv_desc_t *desc, int32_t variant,
     abed_status_t s = fic_plan(desc, variant, pl, false);
     if (s != ABED_OK) return s;
     out->wsum_bytes = 4LL * pl.crs;
-    out->xrows_parts = fic_parts(desc);
+    out->xrows_parts = fic_parts(desc, variant);
     out->xrows_bytes = 4LL * out->xrows_parts * desc->H * desc->S * desc->C;
     // partial output checksums (one per tile / per workgroup of the separate pass); the unfused
     // option keeps the int32 ConvOut behind them when the output is int8
     const long long partials = align256(8LL * (variant == ABED_UNFUSED ? kFicSumBlocks : (long long)pl.grid_m * pl.grid_b * pl.grid_n));
-    const long long dotparts = align256(8LL * fic_rows_blocks(desc));
-    out->workspace_bytes = partials + dotparts + (variant == ABED_UNFUSED ? align256(4LL * desc->N * pl.PQ * desc->K) : 0);
+    const long long dotparts = align256(8LL * fic_rows_blocks(desc, variant));
+    out->workspace_bytes = 256 + partials + dotparts + (variant == ABED_UNFUSED ? align256(4LL * desc->N * pl.PQ * desc->K) : 0);
     return ABED_OK;
 }
 
@@ -308,13 +316,13 @@ abed_status_t abed_fic_filter_prepare_int8(const abed_conv_desc_t *desc, const i
     return ABED_OK;
 }
 
-abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, const int8_t *x, int32_t *xrows, void *stream)
+abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, int32_t variant, const int8_t *x, int32_t *xrows, void *stream)
 {
     Plan pl;
-    abed_status_t s = fic_plan(desc, ABED_FUSED_OCG, pl, false);
+    abed_status_t s = fic_plan(desc, variant, pl, false);
     if (s != ABED_OK) return s;
     if (!x || !xrows) return ABED_EINVAL;
-    return fic_input_rows(desc, pl, x, nullptr, xrows, nullptr, false, (hipStream_t)stream);
+    return fic_input_rows(desc, pl, variant, x, nullptr, xrows, nullptr, false, (hipStream_t)stream);
 }
 
 abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
@@ -341,45 +349,53 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
     if ((s = abed_fic_get_layout(desc, variant, &lay)) != ABED_OK) return s;
     if (!workspace || (long long)workspace_bytes < lay.workspace_bytes) return ABED_EWORKSPACE;
     const int ntiles = pl.grid_m * pl.grid_b * pl.grid_n;
-    long long *partial = (long long *)workspace;
+    // workspace: 256 bytes kept free, partial output checksums, partial dot products, ConvOut
+    long long *partial = (long long *)((char *)workspace + 256);
     const long long npart_bytes = align256(8LL * (variant == ABED_UNFUSED ? kFicSumBlocks : ntiles));
-    long long *dotpart = (long long *)((char *)workspace + npart_bytes);
-    const long long convout_off = npart_bytes + align256(8LL * fic_rows_blocks(desc));
+    long long *dotpart = (long long *)((char *)workspace + 256 + npart_bytes);
+    const int rows_blocks = fic_rows_blocks(desc, variant);
+    const long long convout_off = 256 + npart_bytes + align256(8LL * rows_blocks);
 
-    // tasks 2 and 3: input fmap checksum generation and its partial dot products with the filter checksum
-    if ((s = fic_input_rows(desc, pl, x, wsum, xrows, dotpart, !compute_xrows, st)) != ABED_OK) return s;
-
-    // tasks 4 to 6: convolution, output fmap checksum generation, epilog
     ConvParams cp;
     fill_params(cp, desc, pl);
     cp.x = x; cp.w = w; cp.mode = MODE_PLAIN;
     set_injection(cp, desc, pl, inject);
     const int grid = (ntiles + 7) / 8 * 8;
-    int npartial;
     if (variant == ABED_FUSED_OCG) {
-        cp.y = y; cp.fic_ocs = partial; npartial = ntiles;
+        // Two launches (tasks 2 to 7 of Sec. 4.3).  First: the leading workgroups make the input checksum
+        // and its partial dot products while the tile workgroups convolve, apply the epilog and reduce
+        // their accumulators.  Second: a one-workgroup kernel adds up the partial sums and compares.
+        const int lead = (rows_blocks + 7) / 8 * 8;      // keeps the tiles' block index aligned to the 8 XCDs
+        cp.y = y; cp.fic_ocs = partial;
+        cp.fic_wsum = wsum; cp.fic_xrows = xrows; cp.fic_dotpart = dotpart;
+        cp.fic_parts = lay.xrows_parts; cp.fic_rows_blocks = rows_blocks; cp.fic_rows_lead = lead; cp.fic_from_rows = compute_xrows ? 0 : 1;
         if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
-        if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
-        LAUNCH_CHECK("conv_kernel (FIC, fused output checksum)");
-    } else {
-        int32_t *convout = int8_out ? (int32_t *)((char *)workspace + convout_off) : (int32_t *)y;
-        cp.y = convout;
-        if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
-        LAUNCH_CHECK("conv_kernel (unchecked)");
-        if (inject && inject->site == 2) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)convout, inject->index, 1u << inject->bit);
-        npartial = kFicSumBlocks;
-        fic_output_sum_kernel<<<dim3(kFicSumBlocks), dim3(256), 0, st>>>(convout, npqk, partial);
-        LAUNCH_CHECK("fic_output_sum_kernel");
-        if (int8_out) {
-            epilog_i8_kernel<<<dim3((unsigned)((npqk / 4 + 256) / 256)), dim3(256), 0, st>>>(convout, (int8_t *)y, epi->scale, epi->bias, epi->relu, npqk, desc->K);
-            LAUNCH_CHECK("epilog_i8_kernel");
-        }
+        if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, lead + grid, st)) return ABED_EUNSUPPORTED;
+        LAUNCH_CHECK("conv_kernel (FIC, fused)");
+        FicVerifyParams vp;
+        vp.dotpart = dotpart; vp.partial = partial; vp.result = (long long *)result; vp.flag = flag;
+        vp.ndot = rows_blocks; vp.npartial = ntiles;
+        fic_verify_kernel<<<1, 1024, 0, st>>>(vp);
+        LAUNCH_CHECK("fic_verify_kernel");
+        return ABED_OK;
     }
 
-    // tasks 3 and 7: dot product of the two checksums, comparison
+    // unfused option: one kernel per task
+    if ((s = fic_input_rows(desc, pl, variant, x, wsum, xrows, dotpart, !compute_xrows, st)) != ABED_OK) return s;
+    int32_t *convout = int8_out ? (int32_t *)((char *)workspace + convout_off) : (int32_t *)y;
+    cp.y = convout;
+    if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
+    LAUNCH_CHECK("conv_kernel (unchecked)");
+    if (inject && inject->site == 2) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)convout, inject->index, 1u << inject->bit);
+    fic_output_sum_kernel<<<dim3(kFicSumBlocks), dim3(256), 0, st>>>(convout, npqk, partial);
+    LAUNCH_CHECK("fic_output_sum_kernel");
+    if (int8_out) {
+        epilog_i8_kernel<<<dim3((unsigned)((npqk / 4 + 256) / 256)), dim3(256), 0, st>>>(convout, (int8_t *)y, epi->scale, epi->bias, epi->relu, npqk, desc->K);
+        LAUNCH_CHECK("epilog_i8_kernel");
+    }
     FicVerifyParams vp;
     vp.dotpart = dotpart; vp.partial = partial; vp.result = (long long *)result; vp.flag = flag;
-    vp.ndot = fic_rows_blocks(desc); vp.npartial = npartial;
+    vp.ndot = rows_blocks; vp.npartial = kFicSumBlocks;
     fic_verify_kernel<<<1, 1024, 0, st>>>(vp);
     LAUNCH_CHECK("fic_verify_kernel");
     return ABED_OK;

@@ -38,6 +38,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <type_traits>
+#include "fic_device.h"
 
 namespace abed {
 
@@ -85,7 +86,15 @@ struct ConvParams {
     int dbg;
     int out_fp32;      // fp16 path: 1 = fp32 output
     float rtol, atol;  // fp16 path: threshold of the checks
-    long long *fic_ocs;            // FIC scheme (Sec. 3.3): per-tile sums of all accumulators [ntiles], or null
+    // FIC scheme (Sec. 3.3).  fic_ocs: per-tile sums of all accumulators [ntiles], or null.  With
+    // fic_rows_blocks > 0 the first fic_rows_lead (= that count rounded up to a multiple of 8)
+    // workgroups of the launch make the input checksum and its partial dot products instead of
+    // a tile; they depend on nothing the tiles produce and nothing waits for them inside the launch.
+    long long *fic_ocs;
+    const int32_t *fic_wsum;       // filter checksum [R][S][C]
+    int32_t *fic_xrows;            // row-wise input checksum [fic_parts][H][S][C]
+    long long *fic_dotpart;        // [fic_rows_blocks]
+    int fic_parts, fic_rows_blocks, fic_rows_lead, fic_from_rows;
 };
 
 __device__ __forceinline__ int lds_off(int row, int chunk)
@@ -153,7 +162,9 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     constexpr int STAGE = KG * SUB;
     constexpr int EPI_BYTES = (F16 ? 8 : 4) * WK * 1024 + 128;
     constexpr int RED_BYTES = (KG - 1) * 4 * WM * WK * 1024;   // accumulators of groups 1..KG-1
-    constexpr int LDS_MIN = EPI_BYTES > RED_BYTES ? EPI_BYTES : RED_BYTES;
+    constexpr int FIC_BYTES = F16 ? 0 : kFicRowsLdsBytes;      // the input checksum workgroups of the FIC scheme
+    constexpr int LDS_MIN0 = EPI_BYTES > RED_BYTES ? EPI_BYTES : RED_BYTES;
+    constexpr int LDS_MIN = LDS_MIN0 > FIC_BYTES ? LDS_MIN0 : FIC_BYTES;
     constexpr int LDS_BYTES = (NST * STAGE > LDS_MIN) ? NST * STAGE : LDS_MIN;
     static_assert((NST - 1) * L <= 63, "vmcnt is a 6-bit counter");
     __shared__ __attribute__((aligned(1024))) int8_t lds[LDS_BYTES];
@@ -173,8 +184,25 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     // operand: filter tile slowest when the filters outweigh the activations, pixel group slowest
     // otherwise.  (Only locality depends on how the hardware places blocks, never the result.)
     const int ntiles = p.grid_m * p.grid_b * p.grid_n;
+    int blk = (int)blockIdx.x;
+    if constexpr (!F16) {
+        // FIC scheme: the leading workgroups make the input checksum (Sec. 3.3) beside the tiles
+        if (blk < p.fic_rows_lead) {
+            if (tid >= 256 || blk >= p.fic_rows_blocks) return;
+            FicRowsParams rp;
+            rp.x = p.x; rp.wsum = p.fic_wsum; rp.xrows = p.fic_xrows; rp.dotpart = p.fic_dotpart;
+            rp.N = p.N; rp.H = p.H; rp.W = p.W; rp.C = p.C; rp.R = p.R; rp.S = p.S; rp.P = p.P; rp.Q = p.Q;
+            rp.sh = p.sh; rp.sw = p.sw; rp.ph = p.ph; rp.pw = p.pw; rp.parts = p.fic_parts; rp.from_rows = p.fic_from_rows;
+            int (*cols)[64] = reinterpret_cast<int (*)[64]>(lds);
+            unsigned char (*meets)[64] = reinterpret_cast<unsigned char (*)[64]>(lds + 64 * 64 * 4);
+            long long *dsum = reinterpret_cast<long long *>(lds + 64 * 64 * 4 + 7 * 64);
+            fic_rows_body<7>(rp, blk, tid, cols, meets, dsum);
+            return;
+        }
+        blk -= p.fic_rows_lead;
+    }
     const int per_xcd = (ntiles + 7) >> 3;
-    int bid = ((int)blockIdx.x & 7) * per_xcd + ((int)blockIdx.x >> 3);
+    int bid = (blk & 7) * per_xcd + (blk >> 3);
     if (bid >= ntiles) return;                   // the grid is rounded up to a multiple of 8
     int kt, nt, pg;
     if (p.kt_slowest) {

@@ -36,6 +36,7 @@ class GpuFic:
         self.result = torch.full((2,), -12345, dtype=torch.int64, device=DEV)
         self.flag = torch.full((1,), 77, dtype=torch.int32, device=DEV)
         self.ws = torch.empty((max(256, self.lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
+        abed.workspace_init(self.ws)
 
     def prepare(self, w):
         self.w = torch.from_numpy(w).to(DEV)
@@ -126,7 +127,7 @@ def test_stored_flip_filter_flip_input_flip(oracle):
     # an input corrupted after its checksum was made
     g = GpuFic(s, 4)
     g.prepare(w)
-    g.abed.fic_input_checksum_int8(g.desc, torch.from_numpy(x).to(DEV), g.xrows)
+    g.abed.fic_input_checksum_int8(g.desc, 4, torch.from_numpy(x).to(DEV), g.xrows)
     x2 = x.copy(); x2[7, 4, 4, 17] ^= 0x08
     ref = oracle.abed_fic_int8(x2, w, s, xpatch=clean["xpatch"])
     y, ocs, dot, flag = g.run(x2, compute=False)
