@@ -261,6 +261,7 @@ int fic_parts(const abed_conv_desc_t *d, int variant)
         const int nsub = d->W >= 64 ? 1 : 64 / d->W;      // image subsets a workgroup takes side by side
         parts = (d->N + 16 * nsub - 1) / (16 * nsub);
     }
+    if (parts < (d->N + 255) / 256) parts = (d->N + 255) / 256;   // a lane sums at most 256 images in its 16-bit fields
     if (parts > d->N) parts = d->N;
     return parts < 1 ? 1 : parts;
 }

@@ -73,6 +73,35 @@ class Int8Layer:
                        inject=inject, y2=self.y2)
 
 
+class FicLayer:
+    """Device buffers of one int8 convolution checked by the FIC scheme (Sec. 3.3)."""
+
+    def __init__(self, s, seed, variant, epilogue=False):
+        from synth import int8_tensors, requant_params
+        self.s, self.variant = s, Variant(variant)
+        self.desc = abed.desc_from_shape(s)
+        lay = abed.fic_get_layout(self.desc, self.variant)
+        xh, wh = int8_tensors(s, seed)
+        self.x = torch.from_numpy(xh).to(DEV)
+        self.w = torch.from_numpy(wh).to(DEV)
+        self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int8 if epilogue else torch.int32, device=DEV)
+        self.wsum = torch.empty((s.R, s.S, s.C), dtype=torch.int32, device=DEV)
+        self.xrows = torch.empty((lay.xrows_parts, s.H, s.S, s.C), dtype=torch.int32, device=DEV)
+        self.result = torch.zeros((2,), dtype=torch.int64, device=DEV)
+        self.flag = torch.zeros((1,), dtype=torch.int32, device=DEV)
+        self.ws = torch.zeros((max(256, lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
+        self.epi = None
+        if epilogue:
+            sc, bi = requant_params(s, seed)
+            self.scale, self.bias = torch.from_numpy(sc).to(DEV), torch.from_numpy(bi).to(DEV)
+            self.epi = (self.scale, self.bias, True)
+        abed.fic_filter_prepare_int8(self.desc, self.w, self.wsum)
+
+    def run(self):
+        abed.fic_conv_int8(self.desc, self.x, self.w, self.wsum, self.xrows, True, self.y, self.variant, self.result,
+                           self.flag, epilogue=self.epi, workspace=self.ws)
+
+
 def cmd_layers(args):
     from synth import CONFIG2, CONFIG3, seed_for
     layers = {2: CONFIG2, 3: CONFIG3}[args.config]
@@ -89,8 +118,13 @@ def cmd_layers(args):
                 t[v] = _graph_time(lambda: L.run(), stream)
                 if v == Variant.FUSED_OCG:
                     assert int(L.flags.abs().max().item()) == 0
+            F = FicLayer(s, seed_for(args.config, i), Variant.FUSED_OCG, epilogue=epi)
+            F.run()
+            t_fic = _graph_time(lambda: F.run(), stream)
+            assert int(F.flag.item()) == 0
             nbytes = s.min_bytes(1, 1, 1 if epi else 4)
             row[tag] = dict(unchecked_us=t[Variant.NONE] * 1e6, checked_us=t[Variant.FUSED_OCG] * 1e6,
+                            fic_fused_us=t_fic * 1e6, fic_fused_overhead_pct=100.0 * (t_fic / t[Variant.NONE] - 1.0),
                             duplicate_us=t[Variant.DUPLICATE] * 1e6,
                             unchecked_tops=s.ops / t[Variant.NONE] / 1e12, checked_tops=s.ops / t[Variant.FUSED_OCG] / 1e12,
                             overhead_pct=100.0 * (t[Variant.FUSED_OCG] / t[Variant.NONE] - 1.0),
@@ -98,7 +132,7 @@ def cmd_layers(args):
                             checked_hbm_gbs=nbytes / t[Variant.FUSED_OCG] / 1e9,
                             unchecked_frac_of_hbm_peak=nbytes / t[Variant.NONE] / 1e9 / PEAK_HBM_GBS)
         rows.append(row)
-    print(json.dumps(dict(config=args.config, note="checked = FusedOCG incl. the ICG kernel; GB/s = algorithmic minimum bytes / time",
+    print(json.dumps(dict(config=args.config, note="checked = FC + batch-checksum IC, FusedOCG incl. the ICG kernel; fic_fused = the FIC scheme of Sec. 3.3, fused option; GB/s = algorithmic minimum bytes / time",
                           layers=rows)))
 
 
@@ -223,6 +257,25 @@ def cmd_resnet50(args):
         result[mode] = dict(ms=t * 1e3, tops=total_ops / t / 1e12)
         del objs
         torch.cuda.empty_cache()
+    # the FIC scheme (Sec. 3.3), fused option, every layer with its own input checksum generation
+    objs = []
+    for i, s in enumerate(layers):
+        if s.C % 16:
+            s = ConvShape(s.N, s.H, s.W, 16, s.K, s.R, s.S, s.stride_h, s.stride_w, s.pad_h, s.pad_w, s.name)
+        objs.append(FicLayer(s, 5000 + i, Variant.FUSED_OCG, epilogue=True))
+
+    def fic_step():
+        for L in objs:
+            L.run()
+    fic_step()
+    torch.cuda.synchronize()
+    bad = [L.s.name for L in objs if int(L.flag.item()) != 0]
+    assert not bad, "FIC flag set on a clean run: %s" % bad
+    t = _graph_time(fic_step, stream, reps=2, replays=5)
+    result["fic_fused"] = dict(ms=t * 1e3, tops=total_ops / t / 1e12)
+    result["fic_fused_overhead_pct"] = 100.0 * (result["fic_fused"]["ms"] / result["unchecked"]["ms"] - 1.0)
+    del objs
+    torch.cuda.empty_cache()
     result["overhead_pct"] = 100.0 * (result["checked"]["ms"] / result["unchecked"]["ms"] - 1.0)
     result["duplicate_overhead_pct"] = 100.0 * (result["duplicate"]["ms"] / result["unchecked"]["ms"] - 1.0)
     print(json.dumps(result))
