@@ -3,7 +3,7 @@
   rocprofv3 --kernel-trace --stats ... -- python3 -m paper_2006_04984_amd.profile_run --config 2 --layer 3 --variant 4
   rocprofv3 --pmc FETCH_SIZE ...      -- python3 -m paper_2006_04984_amd.profile_run ... --copy-mb 256
 
-Launches the chosen int8 layer `--reps` times through abed_conv_int8 (eager launches, so that every
+Launches the chosen int8 layer `--reps` times through abed_conv_int8 (or abed_fic_conv_int8 with --scheme fic) (eager launches, so that every
 dispatch is seen by the profiler) and, with --copy-mb, one device-to-device copy of that many MiB,
 whose known size calibrates the FETCH_SIZE / WRITE_SIZE counters.
 """
@@ -23,10 +23,16 @@ def main():
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--int8-out", action="store_true")
     ap.add_argument("--copy-mb", type=int, default=0)
+    ap.add_argument("--scheme", default="fcic", choices=["fcic", "fic"],
+                    help="fcic: filter + batch checksums (abed_conv_int8); fic: the scalar scheme (abed_fic_conv_int8)")
     args = ap.parse_args()
     from synth import CONFIG2, CONFIG3, seed_for
     s = {2: CONFIG2, 3: CONFIG3}[args.config][args.layer]
-    L = Int8Layer(s, seed_for(args.config, args.layer), Variant(args.variant), epilogue=args.int8_out)
+    if args.scheme == "fic":
+        from .evaluate import FicLayer
+        L = FicLayer(s, seed_for(args.config, args.layer), Variant(args.variant), epilogue=args.int8_out)
+    else:
+        L = Int8Layer(s, seed_for(args.config, args.layer), Variant(args.variant), epilogue=args.int8_out)
     for _ in range(args.reps):
         L.run()
     torch.cuda.synchronize()
@@ -38,8 +44,11 @@ def main():
         for _ in range(3):
             b.copy_(a)
         torch.cuda.synchronize()
-    print("profiled", s.name, "variant", args.variant, "grid", L.lay.grid_m, L.lay.grid_b, L.lay.grid_n,
-          "flags", int(L.flags.abs().max().item()))
+    if args.scheme == "fic":
+        print("profiled", s.name, "FIC variant", args.variant, "flag", int(L.flag.item()))
+    else:
+        print("profiled", s.name, "variant", args.variant, "grid", L.lay.grid_m, L.lay.grid_b, L.lay.grid_n,
+              "flags", int(L.flags.abs().max().item()))
 
 
 if __name__ == "__main__":
