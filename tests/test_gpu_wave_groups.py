@@ -79,3 +79,23 @@ def test_fp16(oracle, wave_groups, variant):
     assert np.all(np.abs(y.astype(np.float64) - yr) <= 1e-2 * np.abs(yr) + 1e-3)
     if variant:
         assert not flags.any()
+
+
+@pytest.mark.parametrize("s", [SHAPES[1], SHAPES[2], SHAPES[3]], ids=lambda s: s.name)
+def test_fic_fused(oracle, wave_groups, s):
+    """The FIC scheme's fused option hosts its input checksum workgroups in the convolution's launch:
+    with 2 or 4 wave groups those workgroups are 512 or 1024 threads wide and only 256 of them work."""
+    from test_gpu_fic import GpuFic
+    if wave_groups == 4:
+        os.environ["ABED_TILE_WM"], os.environ["ABED_TILE_WK"] = "2", "4"
+    print("case", s.name, "groups", wave_groups, flush=True)
+    x, w = int8_tensors(s, 5454)
+    ref = oracle.abed_fic_int8(x, w, s)
+    g = GpuFic(s, 4)
+    g.prepare(w)
+    y, ocs, dot, flag = g.run(x)
+    assert np.array_equal(y, ref["y"]) and (ocs, dot, flag) == (ref["ocs"], ref["dot"], 0)
+    idx, bit = y.size // 5, 30
+    ref2 = oracle.abed_fic_int8(x, w, s, acc_flip=(idx, bit))
+    y2, ocs2, dot2, flag2 = g.run(x, inject=(1, idx, bit))
+    assert np.array_equal(y2, ref2["y"]) and (ocs2, dot2, flag2) == (ref2["ocs"], ref2["dot"], 1)
