@@ -271,10 +271,20 @@ def patch_checksum(x, shape):
     tensor of the size of one filter, X[r,s,c] = sum over the batch and over all
     output positions (p,q) of the input element that filter element (r,s,c) meets
     there, zero where the window hangs over the padding.  Exact, int64[R,S,C];
-    each entry is a sum of N*P*Q int8 values (8 + log2(PQN) bits, Sec. 4.1)."""
+    each entry is a sum of N*P*Q int8 values (8 + log2(PQN) bits, Sec. 4.1).
+
+    x may also be the batch-summed image sum_n x[n] (three axes [H,W,C], any integer
+    type): the previous layer's fused kernel can emit that sum of its own output
+    (Sec. 4.3, the option that generates the next layer's input checksum), and the
+    checksum is linear in x."""
     sh = shape
-    xp = np.zeros((sh.N, sh.H + 2 * sh.pad_h, sh.W + 2 * sh.pad_w, sh.C), dtype=np.int64)
-    xp[:, sh.pad_h:sh.pad_h + sh.H, sh.pad_w:sh.pad_w + sh.W] = np.asarray(x, dtype=np.int8)
+    x = np.asarray(x)
+    if x.ndim == 3:
+        x = x[None].astype(np.int64)
+    else:
+        x = x.astype(np.int8)
+    xp = np.zeros((x.shape[0], sh.H + 2 * sh.pad_h, sh.W + 2 * sh.pad_w, sh.C), dtype=np.int64)
+    xp[:, sh.pad_h:sh.pad_h + sh.H, sh.pad_w:sh.pad_w + sh.W] = x
     X = np.zeros((sh.R, sh.S, sh.C), dtype=np.int64)
     for r in range(sh.R):
         for s_ in range(sh.S):
@@ -311,6 +321,9 @@ def abed_fic_int8(x, w, shape, wsum=None, xpatch=None, acc_flip=None, epilog=Non
     if epilog is not None:
         scale, bias, relu = epilog
         res["out8"] = epilog_int8(y, scale, bias, relu)
+        # what the next layer's input checksum is made from when this layer's kernel emits it
+        # (Sec. 4.3): the batch sum of the epilog's output
+        res["xsum_next"] = batch_checksum(res["out8"])
     return res
 
 

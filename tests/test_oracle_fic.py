@@ -110,3 +110,29 @@ def test_single_faults_are_detected_and_cancelling_pairs_are_not(oracle):
     oracle.flip_bit(y2, i, b)
     oracle.flip_bit(y2, j, b)
     assert not np.array_equal(y2, clean["y"]) and int(y2.astype(np.int64).sum()) == clean["dot"]
+
+
+@pytest.mark.parametrize("s", SHAPES, ids=lambda s: s.name)
+def test_patch_checksum_from_the_batch_sum(oracle, s):
+    """The input checksum is linear in x: made from the batch-summed image it equals the one made
+    from the images (brute force again as the witness), which is what lets a layer's fused kernel
+    hand the next layer the batch sum of its own output (Sec. 4.3)."""
+    x, _ = int8_tensors(s, 9)
+    xsum = x.astype(np.int64).sum(axis=0)
+    assert np.array_equal(oracle.patch_checksum(xsum, s), brute_patch(x, s))
+
+
+def test_next_layer_checksum_from_the_epilog_output(oracle):
+    """Two chained layers: the batch sum of the first layer's int8 output, handed over, gives the
+    second layer the same dot product as its own pass over that output."""
+    from synth import requant_params
+    s1 = ConvShape(6, 8, 8, 16, 32, 3, 3, 1, 1, 1, 1, "a")
+    s2 = ConvShape(6, 8, 8, 32, 16, 3, 3, 2, 2, 1, 1, "b")
+    x, w1 = int8_tensors(s1, 41)
+    _, w2 = int8_tensors(s2, 42)
+    scale, bias = requant_params(s1, 41)
+    r1 = oracle.abed_fic_int8(x, w1, s1, epilog=(scale, bias, True))
+    assert np.array_equal(r1["xsum_next"], r1["out8"].astype(np.int64).sum(axis=0))
+    direct = oracle.abed_fic_int8(r1["out8"], w2, s2)
+    handed = oracle.abed_fic_int8(r1["out8"], w2, s2, xpatch=oracle.patch_checksum(r1["xsum_next"], s2))
+    assert handed["dot"] == direct["dot"] == direct["ocs"] and not handed["bad"]
