@@ -207,10 +207,14 @@ typedef struct {
     int64_t wsum_bytes;    /* R*S*C int32 */
     int64_t xrows_bytes;   /* xrows_parts*H*S*C int32 */
     int32_t xrows_parts;   /* parts of the batch summed separately */
+    int64_t xsum_bytes;      /* H*W*C int32: batch sum of the input, handed over by the previous layer */
+    int64_t xsum_next_bytes; /* P*Q*K int32: batch sum of this layer's int8 output, for the next layer */
 } abed_fic_layout_t;
 
-/* Host only.  variant: ABED_UNFUSED (one kernel per task) or ABED_FUSED_OCG (output fmap checksum
- * generation fused into the convolution + epilog kernel); ABED_EUNSUPPORTED otherwise. */
+/* Host only.  variant: ABED_UNFUSED (one kernel per task), ABED_FUSED_OCG (output fmap checksum
+ * generation fused into the convolution + epilog kernel) or ABED_FUSED_IOCG (as FUSED_OCG, and the
+ * kernel also prepares the next layer's input checksum from its own epilog output, Sec. 4.3);
+ * ABED_EUNSUPPORTED otherwise. */
 abed_status_t abed_fic_get_layout(const abed_conv_desc_t *desc, int32_t variant, abed_fic_layout_t *out);
 
 /* Offline (task 1 of Sec. 4.3): the filter checksum. */
@@ -229,6 +233,13 @@ abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, int32_t
  *   y, epilogue   as for abed_conv_int8.
  *   result        two int64 on the device: [0] = ocs, [1] = dot.
  *   flag          one word on the device: 1 if ocs != dot, else 0 (written on every call).
+ *   xsum_in       ABED_FUSED_IOCG only, else NULL: int32 [H][W][C], the batch sum of this layer's input that
+ *                 the previous layer's call produced as its xsum_next.  If non-NULL the input checksum is
+ *                 made from it instead of a pass over x (compute_xrows is ignored), and the call leaves the
+ *                 buffer zero again.
+ *   xsum_next     ABED_FUSED_IOCG with an epilogue, else NULL: int32 [P][Q][K]; the call ADDS the batch sum of
+ *                 its int8 output to it.  The buffer must be zero on entry: zero it once when it is
+ *                 allocated; the consuming call (its xsum_in) restores the zeros.
  *   workspace     workspace_bytes of scratch, 256-byte aligned (partial sums, ConvOut of the unfused option).
  * ABED_FUSED_OCG is two launches: the input checksum workgroups ride in front of the convolution's
  * tiles in one launch (they do not depend on each other), then a one-workgroup kernel adds up the
@@ -240,6 +251,7 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
                                  const int32_t *wsum, int32_t *xrows, int32_t compute_xrows,
                                  void *y, const abed_epilogue_t *epilogue, int32_t variant,
                                  int64_t *result, uint32_t *flag,
+                                 int32_t *xsum_in, int32_t *xsum_next,
                                  void *workspace, size_t workspace_bytes,
                                  const abed_inject_t *inject, void *stream);
 

@@ -46,7 +46,7 @@ class Layout(ctypes.Structure):
 
 
 class FicLayout(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int64) for n in ("workspace_bytes", "wsum_bytes", "xrows_bytes")] + [("xrows_parts", ctypes.c_int32)]
+    _fields_ = [(n, ctypes.c_int64) for n in ("workspace_bytes", "wsum_bytes", "xrows_bytes")] + [("xrows_parts", ctypes.c_int32), ("xsum_bytes", ctypes.c_int64), ("xsum_next_bytes", ctypes.c_int64)]
 
 
 EXPORTS = ["abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
@@ -88,7 +88,7 @@ def lib():
         L.abed_fic_filter_prepare_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
         L.abed_fic_input_checksum_int8.argtypes = [ctypes.POINTER(ConvDesc), i32, vp, vp, vp]
         L.abed_fic_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
-                                         vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp]
+                                         vp, vp, vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp]
         _LIB = L
     return _LIB
 
@@ -187,7 +187,7 @@ def fic_input_checksum_int8(desc, variant, x, xrows, stream=None):
 
 
 def fic_conv_int8(desc, x, w, wsum, xrows, compute_xrows, y, variant, result, flag, epilogue=None,
-                  workspace=None, inject=None, stream=None):
+                  workspace=None, inject=None, stream=None, xsum_in=None, xsum_next=None):
     """abed_fic_conv_int8.  result: int64[2] tensor, flag: int32[1] tensor (device)."""
     epi = None
     if epilogue is not None:
@@ -197,5 +197,5 @@ def fic_conv_int8(desc, x, w, wsum, xrows, compute_xrows, y, variant, result, fl
         inj = ctypes.byref(_Inject(int(inject[0]), int(inject[1]), int(inject[2])))
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().abed_fic_conv_int8(ctypes.byref(desc), _p(x), _p(w), _p(wsum), _p(xrows), int(bool(compute_xrows)),
-                                    _p(y), epi, int(variant), _p(result), _p(flag), _p(workspace), nbytes,
-                                    inj, _stream(stream)))
+                                    _p(y), epi, int(variant), _p(result), _p(flag), _p(xsum_in), _p(xsum_next),
+                                    _p(workspace), nbytes, inj, _stream(stream)))

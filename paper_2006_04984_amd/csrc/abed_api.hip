@@ -239,7 +239,7 @@ namespace {
 
 abed_status_t fic_plan(const abed_conv_desc_t *desc, int variant, Plan &pl, bool int8_out)
 {
-    if (variant != ABED_UNFUSED && variant != ABED_FUSED_OCG) return desc ? ABED_EUNSUPPORTED : ABED_EINVAL;
+    if (variant != ABED_UNFUSED && variant != ABED_FUSED_OCG && variant != ABED_FUSED_IOCG) return desc ? ABED_EUNSUPPORTED : ABED_EINVAL;
     abed_status_t s = make_plan(desc, ABED_INT8, ABED_NONE, int8_out, pl);
     if (s != ABED_OK) return s;
     if (128LL * desc->N * pl.PQ >= (1LL << 31)) return ABED_ERANGE;     // input checksum entries are int32 (Sec. 4.1)
@@ -275,6 +275,7 @@ abed_status_t fic_input_rows(const abed_conv_desc_t *d, const Plan &pl, int vari
 {
     FicRowsParams rp;
     rp.x = x; rp.wsum = wsum; rp.xrows = xrows; rp.dotpart = dotpart; rp.parts = fic_parts(d, variant); rp.from_rows = from_rows ? 1 : 0;
+    rp.xsum = nullptr;
     rp.N = d->N; rp.H = d->H; rp.W = d->W; rp.C = d->C; rp.R = wsum ? d->R : 0; rp.S = d->S; rp.P = pl.P; rp.Q = pl.Q;
     rp.sh = d->stride_h; rp.sw = d->stride_w; rp.ph = d->pad_h; rp.pw = d->pad_w;
     const dim3 grid((unsigned)fic_rows_blocks(d, variant));
@@ -303,6 +304,8 @@ abed_status_t abed_fic_get_layout(const abed_conv_desc_t *desc, int32_t variant,
     const long long partials = align256(8LL * (variant == ABED_UNFUSED ? kFicSumBlocks : (long long)pl.grid_m * pl.grid_b * pl.grid_n));
     const long long dotparts = align256(8LL * fic_rows_blocks(desc, variant));
     out->workspace_bytes = 256 + partials + dotparts + (variant == ABED_UNFUSED ? align256(4LL * desc->N * pl.PQ * desc->K) : 0);
+    out->xsum_bytes = 4LL * desc->H * desc->W * desc->C;
+    out->xsum_next_bytes = 4LL * pl.PQ * desc->K;
     return ABED_OK;
 }
 
@@ -330,6 +333,7 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
                                  const int32_t *wsum, int32_t *xrows, int32_t compute_xrows,
                                  void *y, const abed_epilogue_t *epi, int32_t variant,
                                  int64_t *result, uint32_t *flag,
+                                 int32_t *xsum_in, int32_t *xsum_next,
                                  void *workspace, size_t workspace_bytes,
                                  const abed_inject_t *inject, void *stream)
 {
@@ -340,6 +344,11 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
     if (s != ABED_OK) return s;
     if (!x || !w || !wsum || !xrows || !y || !result || !flag) return ABED_EINVAL;
     if (epi && (!epi->scale || !epi->bias)) return ABED_EINVAL;
+    // handing the batch sum from layer to layer belongs to the input-and-output-fused option only,
+    // and the sum handed on is that of the epilog's int8 output
+    if (variant != ABED_FUSED_IOCG && (xsum_in || xsum_next)) return ABED_EINVAL;
+    if (xsum_next && !int8_out) return ABED_EINVAL;
+    if (xsum_in && xsum_in == xsum_next) return ABED_EINVAL;
     const long long npqk = (long long)desc->N * pl.PQ * desc->K;
     if (inject && inject->site != 0) {
         if (inject->site != 1 && inject->site != 2) return ABED_EINVAL;
@@ -362,14 +371,15 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
     cp.x = x; cp.w = w; cp.mode = MODE_PLAIN;
     set_injection(cp, desc, pl, inject);
     const int grid = (ntiles + 7) / 8 * 8;
-    if (variant == ABED_FUSED_OCG) {
+    if (variant == ABED_FUSED_OCG || variant == ABED_FUSED_IOCG) {
         // Two launches (tasks 2 to 7 of Sec. 4.3).  First: the leading workgroups make the input checksum
         // and its partial dot products while the tile workgroups convolve, apply the epilog and reduce
         // their accumulators.  Second: a one-workgroup kernel adds up the partial sums and compares.
         const int lead = (rows_blocks + 7) / 8 * 8;      // keeps the tiles' block index aligned to the 8 XCDs
         cp.y = y; cp.fic_ocs = partial;
         cp.fic_wsum = wsum; cp.fic_xrows = xrows; cp.fic_dotpart = dotpart;
-        cp.fic_parts = lay.xrows_parts; cp.fic_rows_blocks = rows_blocks; cp.fic_rows_lead = lead; cp.fic_from_rows = compute_xrows ? 0 : 1;
+        cp.fic_parts = lay.xrows_parts; cp.fic_rows_blocks = rows_blocks; cp.fic_rows_lead = lead; cp.fic_from_rows = xsum_in ? 2 : (compute_xrows ? 0 : 1);
+        cp.fic_xsum_in = xsum_in; cp.fic_xsum_next = xsum_next;
         if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
         if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, lead + grid, st)) return ABED_EUNSUPPORTED;
         LAUNCH_CHECK("conv_kernel (FIC, fused)");

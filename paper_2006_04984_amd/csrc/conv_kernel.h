@@ -95,6 +95,8 @@ struct ConvParams {
     int32_t *fic_xrows;            // row-wise input checksum [fic_parts][H][S][C]
     long long *fic_dotpart;        // [fic_rows_blocks]
     int fic_parts, fic_rows_blocks, fic_rows_lead, fic_from_rows;
+    int32_t *fic_xsum_in;          // batch-summed input image [H][W][C] handed over by the previous layer (fic_from_rows == 2)
+    int32_t *fic_xsum_next;        // batch sum of this layer's int8 output [P][Q][K], added to (must start at zero), or null
 };
 
 __device__ __forceinline__ int lds_off(int row, int chunk)
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             FicRowsParams rp;
             rp.x = p.x; rp.wsum = p.fic_wsum; rp.xrows = p.fic_xrows; rp.dotpart = p.fic_dotpart;
             rp.N = p.N; rp.H = p.H; rp.W = p.W; rp.C = p.C; rp.R = p.R; rp.S = p.S; rp.P = p.P; rp.Q = p.Q;
-            rp.sh = p.sh; rp.sw = p.sw; rp.ph = p.ph; rp.pw = p.pw; rp.parts = p.fic_parts; rp.from_rows = p.fic_from_rows;
+            rp.sh = p.sh; rp.sw = p.sw; rp.ph = p.ph; rp.pw = p.pw; rp.parts = p.fic_parts; rp.from_rows = p.fic_from_rows; rp.xsum = p.fic_xsum_in;
             int (*cols)[64] = reinterpret_cast<int (*)[64]>(lds);
             unsigned char (*meets)[64] = reinterpret_cast<unsigned char (*)[64]>(lds + 64 * 64 * 4);
             long long *dsum = reinterpret_cast<long long *>(lds + 64 * 64 * 4 + 7 * 64);
@@ -694,6 +696,15 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 } else {
                     st_dev4(p.ws_ic + part, c);
                 }
+            } else if (pass == 2) {
+                // FIC scheme, next layer's input checksum source (Sec. 4.3): the batch sum of the int8
+                // outputs, added to an int32 image that starts at zero (tiles of other batch parts add too)
+                const int k = fb * 16 + lg * 4;
+                if (pvalid && fb < p.kblk)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        if (k + v < p.K && c[v] != 0)
+                            __hip_atomic_fetch_add(&p.fic_xsum_next[(long long)pix * p.K + k + v], c[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             } else if (fb < p.kblk) {
                 if (ic_local) {
                     // digits of the next layer's batch checksum: xchk_next[d][pix][k..k+3]
@@ -803,6 +814,10 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 }
             }
         }
+    }
+    if (p.fic_xsum_next && p.out_int8) {
+        __syncthreads();
+        ic_pass(2);
     }
     if (!reduce) return;
     if (want_next) {

@@ -27,7 +27,9 @@ struct FicRowsParams {
     int32_t *xrows;               // [parts][H][S][C]
     long long *dotpart;           // one partial dot product per workgroup [parts * H * ceil(C/64)], or null (then R = 0)
     int N, H, W, C, R, S, P, Q, sh, sw, ph, pw, parts;
-    int from_rows;                // 1: xrows is given, only the partial dot products are formed
+    int from_rows;                // 0: from the images x; 1: xrows is given, only the partial dot products are
+                                  // formed; 2: from the batch-summed image xsum, which is cleared after use
+    int32_t *xsum;                // [H][W][C] int32 (from_rows == 2)
 };
 
 // sum of wsum[r][rest] over the filter rows r that meet input row h:  h = q*sh - ph + r for an output row q
@@ -71,7 +73,37 @@ __device__ __forceinline__ void fic_rows_body(const FicRowsParams &p, const int 
         const int s = e >> 6, c = cg * 64 + (e & 63);
         wv[j] = (e < SMAX * 64 && s < p.S && c < p.C) ? fic_wsum_meeting_row(p.wsum, s * p.C + c, sc, h, p.R, p.P, p.sh, p.ph) : 0;
     }
-    if (!p.from_rows) {
+    if (p.from_rows == 2) {
+        // The previous layer's kernel has left sum_n x[n] here (Sec. 4.3, the option that generates the
+        // next layer's input checksum): only the columns remain to be added.  Part 0 does it; the slice
+        // of xsum this workgroup owns is cleared afterwards, ready for the producer's next additions.
+        int32_t *src = p.xsum + (long long)h * p.W * p.C + cg * 64;
+        if (part == 0) {
+            for (int w0 = 0; w0 < p.W; w0 += 64) {
+                for (int e = tid; e < SMAX * 64; e += 256) {
+                    const int s = e >> 6, wc = w0 + (e & 63);
+                    const int t = wc + p.pw - s;
+                    meets[s][e & 63] = (s < p.S && wc < p.W && t >= 0 && t % p.sw == 0 && t / p.sw < p.Q) ? 1 : 0;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int j = 0; j < (SMAX * 64 + 255) / 256; ++j) {
+                    const int e = tid + 256 * j;
+                    const int s = e >> 6, c = e & 63;
+                    if (e < SMAX * 64 && s < p.S && cg * 64 + c < p.C) {
+                        int a = 0;
+                        for (int sl = 0; sl < 64 && w0 + sl < p.W; ++sl) a += meets[s][sl] ? src[(long long)(w0 + sl) * p.C + c] : 0;
+                        acc[j] += a;
+                    }
+                }
+                __syncthreads();
+            }
+            for (int i = tid; i < p.W * 64; i += 256) {
+                const int wc = i >> 6, c = i & 63;
+                if (cg * 64 + c < p.C) src[(long long)wc * p.C + c] = 0;
+            }
+        }
+    } else if (!p.from_rows) {
         const int chunk = tid & 3, slot = tid >> 2;
         const int c0 = cg * 64 + chunk * 16;
         const int n_lo = p.N * part / p.parts, n_hi = p.N * (part + 1) / p.parts;
@@ -139,7 +171,7 @@ __device__ __forceinline__ void fic_rows_body(const FicRowsParams &p, const int 
         const int s = e >> 6, c = cg * 64 + (e & 63);
         if (e < SMAX * 64 && s < p.S && c < p.C) {
             int xr;
-            if (p.from_rows) xr = rows[s * p.C + c];
+            if (p.from_rows == 1) xr = rows[s * p.C + c];
             else { xr = acc[j]; rows[s * p.C + c] = xr; }
             dot += (long long)xr * wv[j];
         }

@@ -42,14 +42,15 @@ class GpuFic:
         self.w = torch.from_numpy(w).to(DEV)
         self.abed.fic_filter_prepare_int8(self.desc, self.w, self.wsum)
 
-    def run(self, x, compute=True, epilogue=None, inject=None):
-        self.x = torch.from_numpy(x).to(DEV)
+    def run(self, x, compute=True, epilogue=None, inject=None, xsum_in=None, xsum_next=None):
+        self.x = x if torch.is_tensor(x) else torch.from_numpy(x).to(DEV)
         epi = None
         if epilogue is not None:
             self.scale, self.bias = torch.from_numpy(epilogue[0]).to(DEV), torch.from_numpy(epilogue[1]).to(DEV)
             epi = (self.scale, self.bias, epilogue[2])
         self.abed.fic_conv_int8(self.desc, self.x, self.w, self.wsum, self.xrows, compute, self.y, self.variant,
-                                self.result, self.flag, epilogue=epi, workspace=self.ws, inject=inject)
+                                self.result, self.flag, epilogue=epi, workspace=self.ws, inject=inject,
+                                xsum_in=xsum_in, xsum_next=xsum_next)
         torch.cuda.synchronize()
         r = self.result.cpu().numpy()
         return self.y.cpu().numpy(), int(r[0]), int(r[1]), int(self.flag.item())
@@ -154,7 +155,44 @@ def test_full_size_layer_scalars(oracle):
 def test_unsupported_variants_are_refused():
     import paper_2006_04984_amd as abed
     d = abed.desc_from_shape(SHAPES[1])
-    for v in (0, 2, 3, 5, 6):
+    for v in (0, 2, 3, 6):
         with pytest.raises(abed.AbedError) as e:
             abed.fic_get_layout(d, v)
         assert e.value.status == 2
+
+
+CHAINS = [
+    (ConvShape(6, 8, 8, 16, 32, 3, 3, 1, 1, 1, 1, "a3x3"), ConvShape(6, 8, 8, 32, 48, 3, 3, 2, 2, 1, 1, "b3x3s2")),
+    (ConvShape(40, 9, 7, 64, 80, 1, 1, 1, 1, 0, 0, "a1x1_n40"), ConvShape(40, 9, 7, 80, 64, 3, 3, 1, 1, 1, 1, "b3x3_n40")),
+    (ConvShape(3, 12, 12, 16, 16, 7, 7, 2, 2, 3, 3, "a7x7s2"), ConvShape(3, 6, 6, 16, 32, 1, 1, 1, 1, 0, 0, "b1x1")),
+]
+
+
+@pytest.mark.parametrize("sa,sb", CHAINS, ids=lambda s: s.name)
+def test_next_layer_checksum_is_handed_over(oracle, sa, sb):
+    """The option that also fuses the next layer's input checksum generation (Sec. 4.3): layer A adds
+    the batch sum of its int8 output to xsum; layer B makes its input checksum from xsum instead of a
+    pass over A's output, and leaves xsum zero.  Twice in a row on the same buffers."""
+    print("case", sa.name, "->", sb.name, flush=True)
+    x, wa = int8_tensors(sa, 7171)
+    _, wb = int8_tensors(sb, 7272)
+    scale, bias = requant_params(sa, 7171)
+    ra = oracle.abed_fic_int8(x, wa, sa, epilog=(scale, bias, True))
+    rb = oracle.abed_fic_int8(ra["out8"], wb, sb)
+    ga, gb = GpuFic(sa, 5, int8_out=True), GpuFic(sb, 5)
+    ga.prepare(wa); gb.prepare(wb)
+    xsum = torch.zeros((sa.P, sa.Q, sa.K), dtype=torch.int32, device=DEV)
+    for rep in range(2):
+        ya, ocs, dot, flag = ga.run(x, epilogue=(scale, bias, True), xsum_next=xsum)
+        assert np.array_equal(ya, ra["out8"]) and (ocs, dot, flag) == (ra["ocs"], ra["dot"], 0)
+        assert np.array_equal(xsum.cpu().numpy(), ra["xsum_next"])
+        yb, ocs, dot, flag = gb.run(ga.y, xsum_in=xsum)
+        assert np.array_equal(yb, rb["y"]) and (ocs, dot, flag) == (rb["ocs"], rb["dot"], 0)
+        assert not xsum.any()
+    # B's input corrupted after A made the sum: B's check fires
+    ga.run(x, epilogue=(scale, bias, True), xsum_next=xsum)
+    bad = ga.y.clone()
+    bad.view(-1)[bad.numel() // 2] ^= 0x10
+    ref = oracle.abed_fic_int8(bad.cpu().numpy(), wb, sb, xpatch=rb["xpatch"])
+    yb, ocs, dot, flag = gb.run(bad, xsum_in=xsum)
+    assert np.array_equal(yb, ref["y"]) and (ocs, dot, flag) == (ref["ocs"], ref["dot"], int(ref["bad"])) and ref["bad"]
