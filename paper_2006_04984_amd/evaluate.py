@@ -76,13 +76,14 @@ class Int8Layer:
 class FicLayer:
     """Device buffers of one int8 convolution checked by the FIC scheme (Sec. 3.3)."""
 
-    def __init__(self, s, seed, variant, epilogue=False):
+    def __init__(self, s, seed, variant, epilogue=False, x=None):
         from synth import int8_tensors, requant_params
         self.s, self.variant = s, Variant(variant)
         self.desc = abed.desc_from_shape(s)
         lay = abed.fic_get_layout(self.desc, self.variant)
         xh, wh = int8_tensors(s, seed)
-        self.x = torch.from_numpy(xh).to(DEV)
+        self.x = torch.from_numpy(xh).to(DEV) if x is None else x
+        self.xsum_in = self.xsum_next = None
         self.w = torch.from_numpy(wh).to(DEV)
         self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int8 if epilogue else torch.int32, device=DEV)
         self.wsum = torch.empty((s.R, s.S, s.C), dtype=torch.int32, device=DEV)
@@ -99,7 +100,7 @@ class FicLayer:
 
     def run(self):
         abed.fic_conv_int8(self.desc, self.x, self.w, self.wsum, self.xrows, True, self.y, self.variant, self.result,
-                           self.flag, epilogue=self.epi, workspace=self.ws)
+                           self.flag, epilogue=self.epi, workspace=self.ws, xsum_in=self.xsum_in, xsum_next=self.xsum_next)
 
 
 def cmd_layers(args):
@@ -118,6 +119,15 @@ def cmd_layers(args):
                 t[v] = _graph_time(lambda: L.run(), stream)
                 if v == Variant.FUSED_OCG:
                     assert int(L.flags.abs().max().item()) == 0
+                if v == Variant.NONE and args.config == 3:
+                    # HBM figure: rotate through buffer sets that together exceed the 256 MB last-level
+                    # cache twice over, so that no launch finds its operands cached
+                    sets = [L]
+                    while sum(o.x.numel() + 4 * o.y.numel() // (4 if epi else 1) for o in sets) < (600 << 20) and len(sets) < 12:
+                        sets.append(Int8Layer(s, seed_for(args.config, i) + len(sets), v, epilogue=epi))
+                    t_rot = _graph_time(lambda: [o.run() for o in sets], stream, reps=4, replays=5) / len(sets)
+                    rot = dict(buffer_sets=len(sets), unchecked_us=t_rot * 1e6)
+                    del sets
             F = FicLayer(s, seed_for(args.config, i), Variant.FUSED_OCG, epilogue=epi)
             F.run()
             t_fic = _graph_time(lambda: F.run(), stream)
@@ -131,6 +141,10 @@ def cmd_layers(args):
                             min_bytes=nbytes, unchecked_hbm_gbs=nbytes / t[Variant.NONE] / 1e9,
                             checked_hbm_gbs=nbytes / t[Variant.FUSED_OCG] / 1e9,
                             unchecked_frac_of_hbm_peak=nbytes / t[Variant.NONE] / 1e9 / PEAK_HBM_GBS)
+            if args.config == 3:
+                rot.update(unchecked_hbm_gbs=nbytes / (rot["unchecked_us"] * 1e-6) / 1e9,
+                           frac_of_hbm_peak=nbytes / (rot["unchecked_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS)
+                row[tag]["rotating_buffers"] = rot
         rows.append(row)
     print(json.dumps(dict(config=args.config, note="checked = FC + batch-checksum IC, FusedOCG incl. the ICG kernel; fic_fused = the FIC scheme of Sec. 3.3, fused option; GB/s = algorithmic minimum bytes / time",
                           layers=rows)))
@@ -210,6 +224,15 @@ def cmd_fp16(args):
             abed.conv_fp16(desc, x, w, wchk, xchk, False, y, Variant.FUSED_OCG, rt, at, flags=flags, workspace=ws,
                            inject=(1, idx, bit))
             det[(rt, at)][bit] += int((flags != 0).any().item())
+    # throughput of the same layer: unchecked, checked (ICG + augmented convolution), duplicated
+    stream = torch.cuda.Stream()
+    y2 = torch.empty_like(y)
+    t_plain = _graph_time(lambda: abed.conv_fp16(desc, x, w, None, None, False, y, Variant.NONE, 1e-3, 1e-3), stream)
+    t_chk = _graph_time(lambda: abed.conv_fp16(desc, x, w, wchk, xchk, True, y, Variant.FUSED_OCG, 1e-3, 1e-3, flags=flags, workspace=ws), stream)
+    t_dup = _graph_time(lambda: abed.conv_fp16(desc, x, w, None, None, False, y, Variant.DUPLICATE, 1e-3, 1e-3, flags=flags, workspace=ws, y2=y2), stream)
+    res["timing"] = dict(gflop=s.ops / 1e9, unchecked_us=t_plain * 1e6, checked_us=t_chk * 1e6, duplicate_us=t_dup * 1e6,
+                         unchecked_tflops=s.ops / t_plain / 1e12, checked_tflops=s.ops / t_chk / 1e12,
+                         overhead_pct=100.0 * (t_chk / t_plain - 1.0), frac_of_fp16_peak=s.ops / t_plain / 1e12 / 2500.0)
     for st in settings:
         res["thresholds"].append(dict(rtol=st[0], atol=st[1], clean_runs_with_a_flag=clean_fp[st],
                                       flagged_tiles_per_clean_run=tiles_fp[st] / args.trials,
@@ -274,6 +297,32 @@ def cmd_resnet50(args):
     t = _graph_time(fic_step, stream, reps=2, replays=5)
     result["fic_fused"] = dict(ms=t * 1e3, tops=total_ops / t / 1e12)
     result["fic_fused_overhead_pct"] = 100.0 * (result["fic_fused"]["ms"] / result["unchecked"]["ms"] - 1.0)
+    del objs
+    torch.cuda.empty_cache()
+    # FIC with the next layer's input checksum generation fused in (Sec. 4.3): inside a bottleneck the
+    # second and third convolutions take the batch sum of their input from the previous kernel
+    objs, prev = [], None
+    for i, s in enumerate(layers):
+        if s.C % 16:
+            s = ConvShape(s.N, s.H, s.W, 16, s.K, s.R, s.S, s.stride_h, s.stride_w, s.pad_h, s.pad_w, s.name)
+        chain = prev is not None and s.name.split(".")[-1] in ("c2", "c3") and prev.s.name.split(".")[0] == s.name.split(".")[0]
+        L = FicLayer(s, 5000 + i, Variant.FUSED_IOCG, epilogue=True, x=prev.y if chain else None)
+        if chain:
+            prev.xsum_next = torch.zeros((prev.s.P, prev.s.Q, prev.s.K), dtype=torch.int32, device=DEV)
+            L.xsum_in = prev.xsum_next
+        objs.append(L)
+        prev = L
+
+    def fic_chain_step():
+        for L in objs:
+            L.run()
+    fic_chain_step()
+    torch.cuda.synchronize()
+    bad = [L.s.name for L in objs if int(L.flag.item()) != 0]
+    assert not bad, "FIC (chained) flag set on a clean run: %s" % bad
+    t = _graph_time(fic_chain_step, stream, reps=2, replays=5)
+    result["fic_iocg"] = dict(ms=t * 1e3, tops=total_ops / t / 1e12, chained_layers=sum(1 for L in objs if L.xsum_in is not None))
+    result["fic_iocg_overhead_pct"] = 100.0 * (result["fic_iocg"]["ms"] / result["unchecked"]["ms"] - 1.0)
     del objs
     torch.cuda.empty_cache()
     result["overhead_pct"] = 100.0 * (result["checked"]["ms"] / result["unchecked"]["ms"] - 1.0)
