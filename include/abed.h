@@ -64,6 +64,19 @@ typedef enum {
     ABED_DUPLICATE = 6                 /* unchecked convolution twice + element-wise compare           */
 } abed_variant_t;
 
+/* Which checksums a checked variant (1..5) carries.  By default both: the filter checksum (FC,
+ * Sec. 3.1) and the batch checksum image (IC option 1, Sec. 3.2), which also check each other.
+ * OR one of these into the `variant` argument of abed_get_layout / abed_conv_int8 / abed_conv_fp16 to
+ * run one scheme alone, with the protection Table 1 (Sec. 3.4) lists for it:
+ *   ABED_ONLY_FC  the K filters and the block of checksum filters, no checksum images: d_i = 0, xchk is
+ *                 not read and no input checksum kernel runs; only flag bit 0 can be set.  Not with
+ *                 ABED_FUSED_IOCG (there is no batch checksum to hand on).
+ *   ABED_ONLY_IC  the N images and the d_i checksum images, no checksum filters: d_f = 0, wchk is not
+ *                 read; only flag bit 1 can be set.
+ * Both at once, or either with ABED_NONE / ABED_DUPLICATE, is ABED_EINVAL. */
+#define ABED_ONLY_FC 0x100
+#define ABED_ONLY_IC 0x200
+
 typedef enum { ABED_INT8 = 0, ABED_FP16 = 1 } abed_dtype_t;
 
 typedef struct {
@@ -107,7 +120,7 @@ typedef struct {
     int32_t grid_m;        /* ceil(P*Q / tile_pixels)                                        */
     int32_t grid_b;        /* ceil(batch entries / tile_batch)                               */
     int32_t grid_n;        /* ceil(filter blocks * 16 / tile_n)                              */
-    int32_t d_f, d_i;      /* checksum tensors per filter / batch checksum                   */
+    int32_t d_f, d_i;      /* checksum tensors per filter / batch checksum (0: scheme not selected) */
     int64_t n_flag_words;  /* grid_m * grid_b * grid_n uint32 words                          */
     int64_t workspace_bytes;
     int64_t wchk_bytes;    /* d_f * R*S*C elements                                           */

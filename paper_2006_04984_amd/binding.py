@@ -25,6 +25,11 @@ class Variant(enum.IntEnum):
     DUPLICATE = 6
 
 
+# OR one of these into a checked variant to run one scheme alone (include/abed.h)
+ONLY_FC = 0x100
+ONLY_IC = 0x200
+
+
 class ConvDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w")]

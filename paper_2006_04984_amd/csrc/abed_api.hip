@@ -52,6 +52,7 @@ struct Plan {
     int n_entries, kblk, n_fblk;          // batch entries, real filter blocks, filter blocks incl. the digit block
     int wm, wk, mb;                       // entries per wave, filter blocks per tile, entries per tile
     int kg;                               // groups of 4 waves along the reduction axis
+    int variant;                          // the variant without the scheme selection bits
     int grid_m, grid_b, grid_n;
     // workspace offsets in bytes (-1 = unused)
     long long off_cnt_fc, off_cnt_ic, off_convout, off_yf, off_yi, off_yfi, off_fc, off_ic, off_nx, ws_bytes;
@@ -122,7 +123,14 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
         d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0)
         return ABED_EINVAL;
     if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return ABED_EINVAL;
+    // scheme selection bits: one of FC alone / IC alone, with a checked variant only
+    const int only = variant & ~0xff;
+    variant &= 0xff;
     if (variant < ABED_NONE || variant > ABED_DUPLICATE) return ABED_EINVAL;
+    if (only != 0 && only != ABED_ONLY_FC && only != ABED_ONLY_IC) return ABED_EINVAL;
+    if (only != 0 && !(variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG)) return ABED_EINVAL;
+    if (only == ABED_ONLY_FC && variant == ABED_FUSED_IOCG) return ABED_EINVAL;
+    pl.variant = variant;
     if (dtype != ABED_INT8 && dtype != ABED_FP16) return ABED_EINVAL;
     const bool f16 = dtype == ABED_FP16;
     pl.esize = f16 ? 2 : 1;
@@ -143,9 +151,11 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     // Variants 1..5 report flags on the tile grid of the augmented problem (N + d_i batch
     // entries, one extra filter block); the unchecked kernels get the plain problem's grid.
     const bool checked = variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG;
+    if (only == ABED_ONLY_FC) pl.d_i = 0;
+    if (only == ABED_ONLY_IC) pl.d_f = 0;
     pl.kblk = (d->K + 15) / 16;
     pl.n_entries = d->N + (checked ? pl.d_i : 0);
-    pl.n_fblk = pl.kblk + (checked ? 1 : 0);
+    pl.n_fblk = pl.kblk + (checked && pl.d_f ? 1 : 0);
     choose_tile(pl);
 
     // workspace: the two counter arrays come first and must be zero before the first call
@@ -508,10 +518,11 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     Plan pl;
     abed_status_t s = make_plan(desc, ABED_INT8, variant, int8_out, pl);
     if (s != ABED_OK) return s;
+    variant = pl.variant;                       // scheme selection is in pl.d_f / pl.d_i from here on
     if (!x || !w || !y) return ABED_EINVAL;
     if (int8_out && (!epi->scale || !epi->bias)) return ABED_EINVAL;
     const bool checked = variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG;
-    if (checked && (!wchk || !xchk || !flags)) return ABED_EINVAL;
+    if (checked && ((pl.d_f && !wchk) || (pl.d_i && !xchk) || !flags)) return ABED_EINVAL;
     if (variant == ABED_DUPLICATE && (!y2 || !flags)) return ABED_EINVAL;
     if (variant == ABED_FUSED_IOCG && int8_out && !xchk_next) return ABED_EINVAL;
     if (checked && (!workspace || (long long)workspace_bytes < pl.ws_bytes)) return ABED_EWORKSPACE;
@@ -526,7 +537,7 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     const long long npqk = (long long)desc->N * pl.PQ * desc->K;
     const bool stored_flip = inject && inject->site == 2;
 
-    if (checked && compute_xchk) {
+    if (checked && compute_xchk && pl.d_i) {
         s = abed_input_checksum_int8(desc, x, xchk, stream);
         if (s != ABED_OK) return s;
     }
@@ -562,11 +573,11 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
             // one kernel per task (Sec. 4.3): the convolution, then the three checksum convolutions
             if ((s = plain_conv(desc, x, w, convout, nullptr, inject, st)) != ABED_OK) return s;
             abed_conv_desc_t df = *desc; df.K = pl.d_f;               // x * checksum filters
-            if ((s = plain_conv(&df, x, wchk, yf, nullptr, nullptr, st)) != ABED_OK) return s;
+            if (pl.d_f && (s = plain_conv(&df, x, wchk, yf, nullptr, nullptr, st)) != ABED_OK) return s;
             abed_conv_desc_t di = *desc; di.N = pl.d_i;               // checksum images * w
-            if ((s = plain_conv(&di, xchk, w, yi, nullptr, nullptr, st)) != ABED_OK) return s;
+            if (pl.d_i && (s = plain_conv(&di, xchk, w, yi, nullptr, nullptr, st)) != ABED_OK) return s;
             abed_conv_desc_t dfi = di; dfi.K = pl.d_f;                // checksum images * checksum filters
-            if ((s = plain_conv(&dfi, xchk, wchk, yfi, nullptr, nullptr, st)) != ABED_OK) return s;
+            if (pl.d_f && pl.d_i && (s = plain_conv(&dfi, xchk, wchk, yfi, nullptr, nullptr, st)) != ABED_OK) return s;
         } else {
             cp.y = convout;
             cp.out_int8 = 0;
@@ -604,7 +615,7 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     if (stored_flip) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)y, inject->index, 1u << inject->bit);
     if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
         FinishParams fp;
-        fp.fc = cp.ws_fc; fp.ic = cp.ws_ic; fp.flags = flags;
+        fp.fc = pl.d_f ? cp.ws_fc : nullptr; fp.ic = pl.d_i ? cp.ws_ic : nullptr; fp.flags = flags;
         fp.N = desc->N; fp.kblk = pl.kblk; fp.tile_batch = pl.mb; fp.wk = pl.wk; fp.grid_b = pl.grid_b; fp.grid_n = pl.grid_n;
         finish_i8_kernel<<<dim3(pl.grid_m * (pl.grid_b + pl.grid_n)), dim3(256), 0, st>>>(fp);
         LAUNCH_CHECK("finish_i8_kernel");
@@ -622,9 +633,10 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
     Plan pl;
     abed_status_t s = make_plan(desc, ABED_FP16, variant, false, pl);
     if (s != ABED_OK) return s;
+    variant = pl.variant;
     if (!x || !w || !y) return ABED_EINVAL;
     const bool checked = variant == ABED_FUSED_OCG;
-    if (checked && (!wchk || !xchk || !flags)) return ABED_EINVAL;
+    if (checked && ((pl.d_f && !wchk) || (pl.d_i && !xchk) || !flags)) return ABED_EINVAL;
     if (checked && !(rtol >= 0.f && atol >= 0.f)) return ABED_EINVAL;
     if (variant == ABED_DUPLICATE && (!y2 || !flags)) return ABED_EINVAL;
     if (checked && (!workspace || (long long)workspace_bytes < pl.ws_bytes)) return ABED_EWORKSPACE;
@@ -635,7 +647,7 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
     }
     char *ws = (char *)workspace;
     auto wsp = [&](long long off) { return off < 0 ? (int32_t *)nullptr : (int32_t *)(ws + off); };
-    if (checked && compute_xchk) {
+    if (checked && compute_xchk && pl.d_i) {
         s = abed_input_checksum_fp16(desc, x, xchk, stream);
         if (s != ABED_OK) return s;
     }

@@ -174,15 +174,15 @@ __global__ __launch_bounds__(256) void verify_i8_kernel(const VerifyParams p)
         }
     }
     __syncthreads();
-    // FC: every image's row sum against the recombined checksum-filter fmap
-    for (int n = tid; n < p.N; n += 256) {
+    // FC: every image's row sum against the recombined checksum-filter fmap (d_f = 0: FC not selected)
+    for (int n = tid; n < (p.d_f ? p.N : 0); n += 256) {
         unsigned c = 0;
         for (int d = 0; d < p.d_f; ++d) c += (unsigned)p.yf[((long long)n * p.PQ + pix) * p.d_f + d] << (8 * d);
         if ((unsigned)rowsum[n] != c) atomicOr(&p.flags[((long long)tm * p.grid_b + n / p.tile_batch) * p.grid_n], 1u);
         atomicAdd(&misc[0], (int)c);
     }
-    // IC: every filter's column sum against the recombined checksum-image fmap
-    for (int k = tid; k < p.K; k += 256) {
+    // IC: every filter's column sum against the recombined checksum-image fmap (d_i = 0: IC not selected)
+    for (int k = tid; k < (p.d_i ? p.K : 0); k += 256) {
         unsigned c = 0;
         for (int j = 0; j < p.d_i; ++j) c += (unsigned)p.yi[((long long)j * p.PQ + pix) * p.K + k] << (8 * j);
         if ((unsigned)colsum[k] != c) atomicOr(&p.flags[(long long)tm * p.grid_b * p.grid_n + k / p.tile_n], 2u);
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void verify_i8_kernel(const VerifyParams p)
     }
     __syncthreads();
     // corner: sum_n yf and sum_k yi against conv(xsum, wsum)
-    if (tid == 0) {
+    if (tid == 0 && p.d_f && p.d_i) {
         unsigned c = 0;
         for (int j = 0; j < p.d_i; ++j)
             for (int d = 0; d < p.d_f; ++d) c += (unsigned)p.yfi[((long long)j * p.PQ + pix) * p.d_f + d] << (8 * (j + d));
@@ -217,6 +217,7 @@ __global__ __launch_bounds__(256) void finish_i8_kernel(const FinishParams p)
     const int mb16 = p.tile_batch * 16, wk256 = p.wk * 256;
     unsigned found = 0;
     if (j < p.grid_b) {
+        if (!p.fc) return;                  // FC not selected
         const int nt = j;
         const int32_t *src = p.fc + ((long long)pg * p.grid_b + nt) * p.grid_n * mb16;
         for (int r = tid; r < mb16; r += 256) {
@@ -227,6 +228,7 @@ __global__ __launch_bounds__(256) void finish_i8_kernel(const FinishParams p)
         }
         if (found) atomicOr(&p.flags[((long long)pg * p.grid_b + nt) * p.grid_n], found);
     } else {
+        if (!p.ic) return;                  // IC not selected
         const int kt = j - p.grid_b;
         const int4 *src = reinterpret_cast<const int4 *>(p.ic + ((long long)pg * p.grid_n + kt) * p.grid_b * wk256);
         for (int r = tid; r < wk256 / 4; r += 256) {

@@ -14,6 +14,8 @@
 // both mod 2^32; a non-zero residual is an error.  Digit rows and the digit
 // block get the same treatment, which checks the checksums against each other
 // (the corner of the row+column scheme, Sec. 2.1).
+// Either scheme can run alone (Table 1 of Sec. 3.4 compares them): with d_i = 0 there are no digit
+// images and no IC residual, with d_f = 0 no digit block and no FC residual; the corner needs both.
 //
 // Tile = 16 consecutive output pixels x MB batch entries x WK filter blocks.
 // MFMA operand roles: filters are the "A" operand (rows of D), the 16 pixels of
@@ -414,7 +416,8 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         int *e_misc = reinterpret_cast<int *>(e_ic + 8 * WK * 256);
         if (tid < 16) e_misc[tid] = 0;
         uint32_t my_flag = 0;
-        const bool fc_local = p.grid_n == 1, ic_local = p.grid_b == 1;
+        // a scheme that is not selected (d_f or d_i zero) has nothing to exchange
+        const bool fc_local = p.grid_n == 1 || p.d_f == 0, ic_local = p.grid_b == 1 || p.d_i == 0;
         const bool checking = p.mode == MODE_CHECK;
         auto bad = [&](float sum, float chk) {
             return !(fabsf(sum - chk) <= p.rtol * fmaxf(fabsf(sum), fabsf(chk)) + p.atol);   // NaN counts as a mismatch
@@ -435,7 +438,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                         }
         }
         // (2) FC: sum over the real filters of every row against hi + lo of the checksum-filter fmaps
-        if (aug) {
+        if (aug && p.d_f) {
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
                 const int e = nt * MB + wave * WM + i;
@@ -463,6 +466,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         const long long word = ((long long)pg * p.grid_b + nt) * p.grid_n + kt;
         if (aug) {
             // (3) IC: sum over the real images of every (pixel, filter) against hi + lo of the checksum-image fmaps
+            if (p.d_i) {
 #pragma unroll
             for (int kb = 0; kb < WK; ++kb) {
                 f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
@@ -495,6 +499,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                     st_dev4(dst, __builtin_bit_cast(i32x4, sum));
                     st_dev4(dst + WK * 256, __builtin_bit_cast(i32x4, chk));
                 }
+            }
             }
             if (checking) {
                 // (4) flags of this tile; when sums span several tiles, count this tile's arrival (the
@@ -588,7 +593,8 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     int *e_misc = e_ic + 4 * WK * 256;                        // [0] flag bits, [1] last for FC, [2] last for IC
     if (tid < 16) e_misc[tid] = 0;
     uint32_t my_flag = 0;
-    const bool fc_local = p.grid_n == 1, ic_local = p.grid_b == 1;
+    // a scheme that is not selected (d_f or d_i zero) has nothing to exchange
+    const bool fc_local = p.grid_n == 1 || p.d_f == 0, ic_local = p.grid_b == 1 || p.d_i == 0;
     const bool checking = p.mode == MODE_CHECK || p.mode == MODE_CHECK_NEXT;
     const bool reduce = aug && p.mode != MODE_WRITE;          // residuals are formed in this kernel
     const bool want_next = p.mode == MODE_CHECK_NEXT && p.out_int8 && p.xchk_next != nullptr;
@@ -623,7 +629,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     }
 
     // (2) FC residual of every row of the tile (Sec. 3.1; digit shifts of Sec. 4.1)
-    if (reduce) {
+    if (reduce && p.d_f) {
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             const int e = nt * MB + wave * WM + i;
@@ -752,7 +758,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     // (3) residuals first (they are small), then the output stores; variant 5 needs the
     // requantised outputs for its second pass, so there the order is the other way round
     if (reduce && !want_next) {
-        ic_pass(0);
+        if (p.d_i) ic_pass(0);
         if (checking) arrive();
         else if (tid == 0) p.flags[tile] = 0;    // partial-reduction variant: the finish kernel ORs its findings in
     }

@@ -18,12 +18,13 @@ class GpuConv:
     """Buffers and calls for one convolution shape on the GPU."""
 
     def __init__(self, shape, variant, int8_out=False):
-        self.shape, self.variant, self.int8_out = shape, Variant(variant), int8_out
+        # variant may carry a scheme selection bit (abed.ONLY_FC / abed.ONLY_IC)
+        self.shape, self.variant, self.int8_out = shape, int(variant), int8_out
         self.desc = abed.desc_from_shape(shape)
         self.lay = abed.get_layout(self.desc, 0, self.variant)
         s = shape
         self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int8 if int8_out else torch.int32, device=DEV)
-        self.y2 = torch.empty_like(self.y) if self.variant == Variant.DUPLICATE else None
+        self.y2 = torch.empty_like(self.y) if self.variant == int(Variant.DUPLICATE) else None
         self.flags = torch.full((max(1, self.lay.n_flag_words),), 0xdeadbeef, dtype=torch.int64, device=DEV).to(torch.int32)
         self.ws = torch.empty((max(256, self.lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
         abed.workspace_init(self.ws)
@@ -33,7 +34,8 @@ class GpuConv:
 
     def prepare(self, w):
         self.w = w if torch.is_tensor(w) else to_dev(w)
-        abed.filter_prepare_int8(self.desc, self.w, self.wchk)
+        if self.lay.d_f:                       # none with the batch checksum scheme alone
+            abed.filter_prepare_int8(self.desc, self.w, self.wchk)
 
     def run(self, x, compute_xchk=True, epilogue=None, inject=None):
         self.x = x if torch.is_tensor(x) else to_dev(x)
@@ -50,7 +52,8 @@ class GpuConv:
 
 def fold_flags(res, shape, lay):
     """Oracle mismatch maps -> expected flag words [grid_m][grid_b][grid_n] for bits 0 and 1,
-    and the per-pixel-group corner bit [grid_m] (bit 2 may sit on any word of the group)."""
+    and the per-pixel-group corner bit [grid_m] (bit 2 may sit on any word of the group).  With one
+    scheme alone (lay.d_i or lay.d_f zero) only that scheme's map is folded and there is no corner."""
     s = shape
     out = np.zeros((lay.grid_m, lay.grid_b, lay.grid_n), dtype=np.uint32)
     corner = np.zeros((lay.grid_m,), dtype=bool)
@@ -60,11 +63,11 @@ def fold_flags(res, shape, lay):
     co = res["corner_bad"].reshape(PQ)
     for tm in range(lay.grid_m):
         lo, hi = tm * lay.tile_pixels, min(PQ, (tm + 1) * lay.tile_pixels)
-        corner[tm] = co[lo:hi].any()
-        for tb in range(lay.grid_b):
+        corner[tm] = co[lo:hi].any() and lay.d_f > 0 and lay.d_i > 0
+        for tb in range(lay.grid_b if lay.d_f > 0 else 0):
             if fc[tb * lay.tile_batch:(tb + 1) * lay.tile_batch, lo:hi].any():
                 out[tm, tb, 0] |= 1
-        for tn in range(lay.grid_n):
+        for tn in range(lay.grid_n if lay.d_i > 0 else 0):
             if ic[lo:hi, tn * lay.tile_n:(tn + 1) * lay.tile_n].any():
                 out[tm, 0, tn] |= 2
     return out, corner

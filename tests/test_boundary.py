@@ -75,3 +75,26 @@ def test_layout_consistency(L, s):
         assert lay.d_f == (2 if s.K <= 257 else 3) and lay.d_i == (2 if s.N > 1 else 1)
         assert lay.wchk_bytes == lay.d_f * s.R * s.S * s.C
         assert lay.xchk_bytes == lay.d_i * s.H * s.W * s.C
+
+
+@pytest.mark.parametrize("s", CONFIG1 + CONFIG2, ids=lambda s: s.name)
+def test_layout_of_one_scheme_alone(L, s):
+    """FC alone has no checksum images, IC alone no checksum filter block (Sec. 3.1 / 3.2, Table 1)."""
+    d = abed.desc_from_shape(s)
+    both = abed.get_layout(d, 0, 4)
+    fc = abed.get_layout(d, 0, 4 | abed.ONLY_FC)
+    ic = abed.get_layout(d, 0, 4 | abed.ONLY_IC)
+    assert (fc.d_f, fc.d_i) == (both.d_f, 0) and fc.xchk_bytes == 0 and fc.wchk_bytes == both.wchk_bytes
+    assert (ic.d_f, ic.d_i) == (0, both.d_i) and ic.wchk_bytes == 0 and ic.xchk_bytes == both.xchk_bytes
+    assert fc.grid_b * fc.tile_batch >= s.N > (fc.grid_b - 1) * fc.tile_batch
+    assert fc.grid_n * fc.tile_n >= ((s.K + 15) // 16 + 1) * 16 > (fc.grid_n - 1) * fc.tile_n
+    assert ic.grid_b * ic.tile_batch >= s.N + ic.d_i > (ic.grid_b - 1) * ic.tile_batch
+    assert ic.grid_n * ic.tile_n >= (s.K + 15) // 16 * 16 > (ic.grid_n - 1) * ic.tile_n
+
+
+def test_scheme_selection_errors(L):
+    d = abed.desc_from_shape(CONFIG1[0])
+    for v in (0 | abed.ONLY_FC, 6 | abed.ONLY_IC, 4 | abed.ONLY_FC | abed.ONLY_IC, 5 | abed.ONLY_FC, 4 | 0x400):
+        with pytest.raises(AbedError) as e:
+            abed.get_layout(d, 0, v)
+        assert e.value.status == 1
