@@ -28,6 +28,8 @@ What is computed, each step following the paper:
 * FIC, the filter and input fmap checksum scheme, Sec. 3.3: the input is reduced
   to a checksum of the size of one filter, its dot product with the filter
   checksum (int64) must equal the sum of all outputs (int64);
+* IC option 2 (Sec. 3.2): that same input checksum convolved with the K filters gives
+  K values, which the outputs reduced over batch, height and width must equal;
 * fp16 (Sec. 7): double-precision reference, checksums stored as a hi/lo pair
   of fp16 tensors, comparison against a threshold.
 
@@ -324,6 +326,36 @@ def abed_fic_int8(x, w, shape, wsum=None, xpatch=None, acc_flip=None, epilog=Non
         # what the next layer's input checksum is made from when this layer's kernel emits it
         # (Sec. 4.3): the batch sum of the epilog's output
         res["xsum_next"] = batch_checksum(res["out8"])
+    return res
+
+
+def abed_ic2_int8(x, w, shape, xpatch=None, acc_flip=None, epilog=None):
+    """IC option 2 of Sec. 3.2: the input fmaps are reduced to a checksum tensor of the
+    size of one filter (patch_checksum), that tensor is convolved with the K filters,
+    which gives exactly K values, and the output fmaps, reduced over height, width and
+    batch, must equal those K values element by element.  Sums are exact (int64,
+    widths of Sec. 4.1).  xpatch may be passed in to model a checksum made before x was
+    corrupted; acc_flip as in abed_fic_int8.
+
+    Returns dict: y int32[N,P,Q,K] as stored, osum int64[K] (reduced outputs), chk
+    int64[K] (checksum tensor convolved with the filters), bad bool[K] = osum != chk,
+    xpatch, out8 when an epilog is given."""
+    x = np.asarray(x, dtype=np.int8)
+    w = np.asarray(w, dtype=np.int8)
+    if xpatch is None:
+        xpatch = patch_checksum(x, shape)
+    y = wrap32(conv_int(x, w, shape)).copy()
+    if acc_flip is not None:
+        flip_bit(y, *acc_flip)
+    osum = y.astype(np.int64).sum(axis=(0, 1, 2))
+    # the checksum tensor has the extent of one filter, so its convolution with filter k
+    # has a single output position: the sum of the element-wise products
+    X = np.asarray(xpatch, dtype=np.int64)
+    chk = np.array([int((X * w[k].astype(np.int64)).sum()) for k in range(shape.K)], dtype=np.int64)
+    res = dict(y=y, osum=osum, chk=chk, bad=osum != chk, xpatch=np.asarray(xpatch))
+    if epilog is not None:
+        scale, bias, relu = epilog
+        res["out8"] = epilog_int8(y, scale, bias, relu)
     return res
 
 

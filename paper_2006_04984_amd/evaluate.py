@@ -4,6 +4,7 @@
   python -m paper_2006_04984_amd.evaluate fp16                      false-positive / detection rates (fp16 layer)
   python -m paper_2006_04984_amd.evaluate detect                    int8 single-bit detection rates
   python -m paper_2006_04984_amd.evaluate resnet50 --batch 128      the 53 convolution layers back to back
+  python -m paper_2006_04984_amd.evaluate ksweep                    filter-count sweep on one 3x3 layer
 
 All inputs are seeded and synthetic (synth/).  Each command prints one JSON object.
 Times are GPU times of HIP-graph replays measured with events on the launch stream.
@@ -46,14 +47,14 @@ class Int8Layer:
 
     def __init__(self, s, seed, variant, epilogue=False, x=None):
         from synth import int8_tensors, requant_params
-        self.s, self.variant = s, Variant(variant)
+        self.s, self.variant = s, int(variant)           # may carry abed.ONLY_FC / abed.ONLY_IC
         self.desc = abed.desc_from_shape(s)
         self.lay = abed.get_layout(self.desc, 0, self.variant)
         xh, wh = int8_tensors(s, seed)
         self.x = torch.from_numpy(xh).to(DEV) if x is None else x
         self.w = torch.from_numpy(wh).to(DEV)
         self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int8 if epilogue else torch.int32, device=DEV)
-        self.y2 = torch.empty_like(self.y) if self.variant == Variant.DUPLICATE else None
+        self.y2 = torch.empty_like(self.y) if self.variant == int(Variant.DUPLICATE) else None
         self.flags = torch.zeros((max(1, self.lay.n_flag_words),), dtype=torch.int32, device=DEV)
         self.ws = torch.zeros((max(256, self.lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
         self.wchk = torch.empty((self.lay.d_f, s.R, s.S, s.C), dtype=torch.int8, device=DEV)
@@ -65,7 +66,8 @@ class Int8Layer:
             self.scale, self.bias = torch.from_numpy(sc).to(DEV), torch.from_numpy(bi).to(DEV)
             self.epi = (self.scale, self.bias, True)
         abed.workspace_init(self.ws)
-        abed.filter_prepare_int8(self.desc, self.w, self.wchk)
+        if self.lay.d_f:
+            abed.filter_prepare_int8(self.desc, self.w, self.wchk)
 
     def run(self, compute_xchk=True, inject=None):
         abed.conv_int8(self.desc, self.x, self.w, self.wchk, self.xchk, compute_xchk, self.y, self.variant,
@@ -113,11 +115,12 @@ def cmd_layers(args):
         for epi in (False, True):
             tag = "i8out" if epi else "i32out"
             t = {}
-            for v in (Variant.NONE, Variant.FUSED_OCG, Variant.DUPLICATE):
+            FC_ONLY, IC_ONLY = Variant.FUSED_OCG | abed.ONLY_FC, Variant.FUSED_OCG | abed.ONLY_IC
+            for v in (Variant.NONE, Variant.FUSED_OCG, Variant.DUPLICATE, FC_ONLY, IC_ONLY):
                 L = Int8Layer(s, seed_for(args.config, i), v, epilogue=epi)
                 L.run()
                 t[v] = _graph_time(lambda: L.run(), stream)
-                if v == Variant.FUSED_OCG:
+                if v not in (Variant.NONE, Variant.DUPLICATE):
                     assert int(L.flags.abs().max().item()) == 0
                 if v == Variant.NONE and args.config == 3:
                     # HBM figure: rotate through buffer sets that together exceed the 256 MB last-level
@@ -136,6 +139,8 @@ def cmd_layers(args):
             row[tag] = dict(unchecked_us=t[Variant.NONE] * 1e6, checked_us=t[Variant.FUSED_OCG] * 1e6,
                             fic_fused_us=t_fic * 1e6, fic_fused_overhead_pct=100.0 * (t_fic / t[Variant.NONE] - 1.0),
                             duplicate_us=t[Variant.DUPLICATE] * 1e6,
+                            fc_only_us=t[FC_ONLY] * 1e6, fc_only_overhead_pct=100.0 * (t[FC_ONLY] / t[Variant.NONE] - 1.0),
+                            ic_only_us=t[IC_ONLY] * 1e6, ic_only_overhead_pct=100.0 * (t[IC_ONLY] / t[Variant.NONE] - 1.0),
                             unchecked_tops=s.ops / t[Variant.NONE] / 1e12, checked_tops=s.ops / t[Variant.FUSED_OCG] / 1e12,
                             overhead_pct=100.0 * (t[Variant.FUSED_OCG] / t[Variant.NONE] - 1.0),
                             min_bytes=nbytes, unchecked_hbm_gbs=nbytes / t[Variant.NONE] / 1e9,
@@ -146,7 +151,7 @@ def cmd_layers(args):
                            frac_of_hbm_peak=nbytes / (rot["unchecked_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS)
                 row[tag]["rotating_buffers"] = rot
         rows.append(row)
-    print(json.dumps(dict(config=args.config, note="checked = FC + batch-checksum IC, FusedOCG incl. the ICG kernel; fic_fused = the FIC scheme of Sec. 3.3, fused option; GB/s = algorithmic minimum bytes / time",
+    print(json.dumps(dict(config=args.config, note="checked = FC + batch-checksum IC, FusedOCG incl. the ICG kernel; fc_only / ic_only = one of the two alone (FusedOCG; ic_only incl. the ICG kernel); fic_fused = the FIC scheme of Sec. 3.3, fused option; GB/s = algorithmic minimum bytes / time",
                           layers=rows)))
 
 
@@ -251,7 +256,8 @@ def cmd_resnet50(args):
     stream = torch.cuda.Stream()
     total_ops = sum(s.ops for s in layers)
     result = dict(batch=args.batch, layers=len(layers), gop=total_ops / 1e9)
-    for mode, variant in (("unchecked", Variant.NONE), ("checked", Variant.FUSED_IOCG), ("duplicate", Variant.DUPLICATE)):
+    for mode, variant in (("unchecked", Variant.NONE), ("checked", Variant.FUSED_IOCG), ("duplicate", Variant.DUPLICATE),
+                          ("fc_only", Variant.FUSED_OCG | abed.ONLY_FC)):
         objs, chained = [], []
         prev = None
         for i, s in enumerate(layers):
@@ -273,7 +279,7 @@ def cmd_resnet50(args):
                     L.xchk = objs[j - 1].xchk_next
         step()
         torch.cuda.synchronize()
-        if variant == Variant.FUSED_IOCG:
+        if variant not in (Variant.NONE, Variant.DUPLICATE):
             bad = [L.s.name for L in objs if int(L.flags.abs().max().item()) != 0]
             assert not bad, "flags set on a clean run: %s" % bad
         t = _graph_time(step, stream, reps=2, replays=5)
@@ -327,7 +333,34 @@ def cmd_resnet50(args):
     torch.cuda.empty_cache()
     result["overhead_pct"] = 100.0 * (result["checked"]["ms"] / result["unchecked"]["ms"] - 1.0)
     result["duplicate_overhead_pct"] = 100.0 * (result["duplicate"]["ms"] / result["unchecked"]["ms"] - 1.0)
+    result["fc_only_overhead_pct"] = 100.0 * (result["fc_only"]["ms"] / result["unchecked"]["ms"] - 1.0)
     print(json.dumps(result))
+
+
+def cmd_ksweep(args):
+    """Filter-count sweep on one layer (Sec. 6.2's tile-boundary study): 3x3, C=64, stride 1, pad 1 on a
+    112x112 input, K from 8 upwards in steps of 8; unchecked, the filter checksum scheme alone (its extra
+    block of checksum filters is what a tile boundary makes expensive), and FC + IC.  int32 ConvOut."""
+    from synth import ConvShape
+    stream = torch.cuda.Stream()
+    rows = []
+    for K in range(8, args.kmax + 1, 8):
+        s = ConvShape(args.batch, 112, 112, 64, K, 3, 3, 1, 1, 1, 1, "3x3_c64_112_k%d" % K)
+        t, tile = {}, {}
+        for name, v in (("unchecked", Variant.NONE), ("fc_only", Variant.FUSED_OCG | abed.ONLY_FC), ("fc_ic", Variant.FUSED_OCG)):
+            L = Int8Layer(s, 9000 + K, v)
+            L.run()
+            t[name] = _graph_time(lambda: L.run(), stream, reps=5, replays=4)
+            tile[name] = "%dx%d, grid %dx%dx%d" % (L.lay.tile_batch, L.lay.tile_n, L.lay.grid_m, L.lay.grid_b, L.lay.grid_n)
+            if v != Variant.NONE:
+                assert int(L.flags.abs().max().item()) == 0
+            del L
+        rows.append(dict(K=K, gop=s.ops / 1e9, unchecked_us=t["unchecked"] * 1e6, fc_only_us=t["fc_only"] * 1e6, fc_ic_us=t["fc_ic"] * 1e6,
+                         fc_only_overhead_pct=100.0 * (t["fc_only"] / t["unchecked"] - 1.0),
+                         fc_ic_overhead_pct=100.0 * (t["fc_ic"] / t["unchecked"] - 1.0),
+                         unchecked_tops=s.ops / t["unchecked"] / 1e12, tile_unchecked=tile["unchecked"], tile_fc_only=tile["fc_only"]))
+        print("K", K, "done", file=sys.stderr, flush=True)
+    print(json.dumps(dict(layer="3x3 C=64 112x112 s1 p1", batch=args.batch, rows=rows)))
 
 
 def main():
@@ -337,12 +370,13 @@ def main():
     a = sub.add_parser("detect"); a.add_argument("--trials", type=int, default=1000); a.add_argument("--clean", type=int, default=100); a.add_argument("--seed", type=int, default=1)
     a = sub.add_parser("fp16"); a.add_argument("--trials", type=int, default=1000); a.add_argument("--seed", type=int, default=1)
     a = sub.add_parser("resnet50"); a.add_argument("--batch", type=int, default=128)
+    a = sub.add_parser("ksweep"); a.add_argument("--batch", type=int, default=16); a.add_argument("--kmax", type=int, default=144)
     args = ap.parse_args()
     if not torch.cuda.is_available():
         print("no GPU visible", file=sys.stderr)
         sys.exit(1)
     abed.lib()
-    {"layers": cmd_layers, "detect": cmd_detect, "fp16": cmd_fp16, "resnet50": cmd_resnet50}[args.cmd](args)
+    {"layers": cmd_layers, "detect": cmd_detect, "fp16": cmd_fp16, "resnet50": cmd_resnet50, "ksweep": cmd_ksweep}[args.cmd](args)
 
 
 if __name__ == "__main__":
