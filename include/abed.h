@@ -272,6 +272,42 @@ const char *abed_status_string(abed_status_t status);
 /* Text of the last HIP error seen by this thread's most recent failing call. */
 const char *abed_last_hip_error(void);
 
+/* ------------------------------------------------------------------------------------------
+ * IC option 2 (Sec. 3.2): the input fmaps are reduced to a checksum tensor of the size of one filter
+ * (the same X[r,s,c] as in the FIC scheme above, in the same row-wise form xrows), that tensor is
+ * convolved with the K filters, which gives K values chk[k] = sum_{r,s,c} X[r,s,c] * w[k,r,s,c], and
+ * the output fmaps reduced over batch, height and width, osum[k] = sum_{n,p,q} y[n,p,q,k], must equal
+ * them element by element.  All sums int64 (Sec. 4.1).  Protects the computation and the input and
+ * output fmaps, not the filters (Table 1 of Sec. 3.4).  int8 only.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    int64_t workspace_bytes;
+    int64_t xrows_bytes;   /* xrows_parts*H*S*C int32 */
+    int32_t xrows_parts;
+    int32_t n_values;      /* K: flag words; result holds 2*K int64 */
+} abed_ic2_layout_t;
+
+/* Host only.  variant: ABED_UNFUSED (one kernel per task) or ABED_FUSED_OCG (the output sums are formed
+ * in the convolution + epilog kernel); ABED_EUNSUPPORTED otherwise. */
+abed_status_t abed_ic2_get_layout(const abed_conv_desc_t *desc, int32_t variant, abed_ic2_layout_t *out);
+
+/* Convolution checked by IC option 2.
+ *   xrows       xrows_bytes, caller-provided, in the layout abed_fic_input_checksum_int8 writes for the
+ *               same variant; if compute_xrows != 0 the call makes it first (ABED_FUSED_OCG: by workgroups
+ *               that ride in front of the convolution's tiles), else it uses the contents as given.
+ *   y, epilogue as for abed_conv_int8.
+ *   result      2*K int64 on the device: [0..K) = osum, [K..2K) = chk.
+ *   flags       K words on the device: 1 where osum[k] != chk[k], else 0 (all written on every call).
+ *   workspace   workspace_bytes of scratch, 256-byte aligned.
+ *   inject      site 1 for both variants; site 2 (stored ConvOut) for ABED_UNFUSED.
+ * Errors as for abed_fic_conv_int8. */
+abed_status_t abed_ic2_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+                                 int32_t *xrows, int32_t compute_xrows,
+                                 void *y, const abed_epilogue_t *epilogue, int32_t variant,
+                                 int64_t *result, uint32_t *flags,
+                                 void *workspace, size_t workspace_bytes,
+                                 const abed_inject_t *inject, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -54,7 +54,11 @@ class FicLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("workspace_bytes", "wsum_bytes", "xrows_bytes")] + [("xrows_parts", ctypes.c_int32), ("xsum_bytes", ctypes.c_int64), ("xsum_next_bytes", ctypes.c_int64)]
 
 
-EXPORTS = ["abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
+class Ic2Layout(ctypes.Structure):
+    _fields_ = [("workspace_bytes", ctypes.c_int64), ("xrows_bytes", ctypes.c_int64), ("xrows_parts", ctypes.c_int32), ("n_values", ctypes.c_int32)]
+
+
+EXPORTS = ["abed_ic2_get_layout", "abed_ic2_conv_int8", "abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
            "abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_fp16",
            "abed_input_checksum_int8", "abed_input_checksum_fp16", "abed_workspace_init",
            "abed_conv_int8", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error"]
@@ -94,6 +98,9 @@ def lib():
         L.abed_fic_input_checksum_int8.argtypes = [ctypes.POINTER(ConvDesc), i32, vp, vp, vp]
         L.abed_fic_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
                                          vp, vp, vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp]
+        L.abed_ic2_get_layout.argtypes = [ctypes.POINTER(ConvDesc), i32, ctypes.POINTER(Ic2Layout)]
+        L.abed_ic2_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
+                                         vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp]
         _LIB = L
     return _LIB
 
@@ -204,3 +211,24 @@ def fic_conv_int8(desc, x, w, wsum, xrows, compute_xrows, y, variant, result, fl
     _check(lib().abed_fic_conv_int8(ctypes.byref(desc), _p(x), _p(w), _p(wsum), _p(xrows), int(bool(compute_xrows)),
                                     _p(y), epi, int(variant), _p(result), _p(flag), _p(xsum_in), _p(xsum_next),
                                     _p(workspace), nbytes, inj, _stream(stream)))
+
+
+def ic2_get_layout(desc, variant):
+    out = Ic2Layout()
+    _check(lib().abed_ic2_get_layout(ctypes.byref(desc), int(variant), ctypes.byref(out)))
+    return out
+
+
+def ic2_conv_int8(desc, x, w, xrows, compute_xrows, y, variant, result, flags, epilogue=None,
+                  workspace=None, inject=None, stream=None):
+    """abed_ic2_conv_int8.  epilogue = (scale, bias, relu) or None; inject = (site, index, bit) or None."""
+    epi = None
+    if epilogue is not None:
+        epi = ctypes.byref(_Epilogue(epilogue[0].data_ptr(), epilogue[1].data_ptr(), int(bool(epilogue[2]))))
+    inj = None
+    if inject is not None:
+        inj = ctypes.byref(_Inject(int(inject[0]), int(inject[1]), int(inject[2])))
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().abed_ic2_conv_int8(ctypes.byref(desc), _p(x), _p(w), _p(xrows), int(bool(compute_xrows)),
+                                    _p(y), epi, int(variant), _p(result), _p(flags), _p(workspace), nbytes,
+                                    inj, _stream(stream)))

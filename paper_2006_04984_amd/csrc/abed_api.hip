@@ -9,6 +9,7 @@
 #include "../../include/abed.h"
 #include "aux_kernels.h"
 #include "fic_kernels.h"
+#include "ic2_kernels.h"
 #include "conv_launch.h"
 
 using namespace abed;
@@ -419,6 +420,107 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
     vp.ndot = rows_blocks; vp.npartial = kFicSumBlocks;
     fic_verify_kernel<<<1, 1024, 0, st>>>(vp);
     LAUNCH_CHECK("fic_verify_kernel");
+    return ABED_OK;
+}
+
+// ---------------------------------------------------------------------------
+// IC option 2 (Sec. 3.2): K values
+// ---------------------------------------------------------------------------
+namespace {
+
+const int kIc2SumBlocks = 512;    // workgroups (= partial sums per filter) of the separate output checksum pass
+
+abed_status_t ic2_plan(const abed_conv_desc_t *desc, int variant, Plan &pl, bool int8_out)
+{
+    if (variant != ABED_UNFUSED && variant != ABED_FUSED_OCG) return desc ? ABED_EUNSUPPORTED : ABED_EINVAL;
+    return fic_plan(desc, variant, pl, int8_out);      // same input checksum, same limits
+}
+
+}  // namespace
+
+abed_status_t abed_ic2_get_layout(const abed_conv_desc_t *desc, int32_t variant, abed_ic2_layout_t *out)
+{
+    if (!out) return ABED_EINVAL;
+    Plan pl;
+    abed_status_t s = ic2_plan(desc, variant, pl, false);
+    if (s != ABED_OK) return s;
+    out->xrows_parts = fic_parts(desc, variant);
+    out->xrows_bytes = 4LL * out->xrows_parts * desc->H * desc->S * desc->C;
+    out->n_values = desc->K;
+    const long long partials = variant == ABED_UNFUSED ? 8LL * kIc2SumBlocks * desc->K
+                                                       : 8LL * pl.grid_m * pl.grid_b * pl.grid_n * pl.wk * 16;
+    out->workspace_bytes = 256 + align256(partials) + (variant == ABED_UNFUSED ? align256(4LL * desc->N * pl.PQ * desc->K) : 0);
+    return ABED_OK;
+}
+
+abed_status_t abed_ic2_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+                                 int32_t *xrows, int32_t compute_xrows,
+                                 void *y, const abed_epilogue_t *epi, int32_t variant,
+                                 int64_t *result, uint32_t *flags,
+                                 void *workspace, size_t workspace_bytes,
+                                 const abed_inject_t *inject, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    const bool int8_out = epi != nullptr;
+    Plan pl;
+    abed_status_t s = ic2_plan(desc, variant, pl, int8_out);
+    if (s != ABED_OK) return s;
+    if (!x || !w || !xrows || !y || !result || !flags) return ABED_EINVAL;
+    if (epi && (!epi->scale || !epi->bias)) return ABED_EINVAL;
+    const long long npqk = (long long)desc->N * pl.PQ * desc->K;
+    if (inject && inject->site != 0) {
+        if (inject->site != 1 && inject->site != 2) return ABED_EINVAL;
+        if (inject->index < 0 || inject->index >= npqk || inject->bit < 0 || inject->bit > 31) return ABED_EINVAL;
+        if (inject->site == 2 && variant != ABED_UNFUSED) return ABED_EUNSUPPORTED;
+    }
+    abed_ic2_layout_t lay;
+    if ((s = abed_ic2_get_layout(desc, variant, &lay)) != ABED_OK) return s;
+    if (!workspace || (long long)workspace_bytes < lay.workspace_bytes) return ABED_EWORKSPACE;
+    const int ntiles = pl.grid_m * pl.grid_b * pl.grid_n;
+    long long *part = (long long *)((char *)workspace + 256);
+    const int rows_blocks = fic_rows_blocks(desc, variant);
+
+    ConvParams cp;
+    fill_params(cp, desc, pl);
+    cp.x = x; cp.w = w; cp.mode = MODE_PLAIN;
+    set_injection(cp, desc, pl, inject);
+    const int grid = (ntiles + 7) / 8 * 8;
+    Ic2VerifyParams vp;
+    vp.w = w; vp.xrows = xrows; vp.part = part; vp.result = (long long *)result; vp.flags = flags;
+    vp.K = desc->K; vp.H = desc->H; vp.C = desc->C; vp.R = desc->R; vp.S = desc->S; vp.P = pl.P;
+    vp.sh = desc->stride_h; vp.ph = desc->pad_h; vp.parts = lay.xrows_parts;
+    if (variant == ABED_FUSED_OCG) {
+        // Two launches: the input checksum workgroups lead the convolution's launch, whose tiles reduce
+        // their accumulators per filter; then one workgroup per filter convolves the checksum tensor
+        // with its filter, adds up the partial output sums and compares.
+        const int lead = compute_xrows ? (rows_blocks + 7) / 8 * 8 : 0;
+        cp.y = y; cp.ic2_part = part;
+        cp.fic_xrows = xrows; cp.fic_parts = lay.xrows_parts; cp.fic_rows_blocks = compute_xrows ? rows_blocks : 0; cp.fic_rows_lead = lead;
+        if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
+        if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, lead + grid, st)) return ABED_EUNSUPPORTED;
+        LAUNCH_CHECK("conv_kernel (IC option 2, fused)");
+        vp.nrows = pl.grid_m * pl.grid_b; vp.kstride = pl.grid_n * pl.wk * 16;
+        ic2_verify_kernel<<<dim3(desc->K), dim3(256), 0, st>>>(vp);
+        LAUNCH_CHECK("ic2_verify_kernel");
+        return ABED_OK;
+    }
+    // unfused option: one kernel per task
+    if (compute_xrows && (s = fic_input_rows(desc, pl, variant, x, nullptr, xrows, nullptr, false, st)) != ABED_OK) return s;
+    int32_t *convout = int8_out ? (int32_t *)((char *)workspace + 256 + align256(8LL * kIc2SumBlocks * desc->K)) : (int32_t *)y;
+    cp.y = convout;
+    if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
+    LAUNCH_CHECK("conv_kernel (unchecked)");
+    if (inject && inject->site == 2) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)convout, inject->index, 1u << inject->bit);
+    if ((size_t)desc->K * 8 > 64 * 1024) return ABED_EUNSUPPORTED;
+    ic2_output_sums_kernel<<<dim3(kIc2SumBlocks), dim3(256), (size_t)desc->K * 8, st>>>(convout, (long long)desc->N * pl.PQ, desc->K, part);
+    LAUNCH_CHECK("ic2_output_sums_kernel");
+    if (int8_out) {
+        epilog_i8_kernel<<<dim3((unsigned)((npqk / 4 + 256) / 256)), dim3(256), 0, st>>>(convout, (int8_t *)y, epi->scale, epi->bias, epi->relu, npqk, desc->K);
+        LAUNCH_CHECK("epilog_i8_kernel");
+    }
+    vp.nrows = kIc2SumBlocks; vp.kstride = desc->K;
+    ic2_verify_kernel<<<dim3(desc->K), dim3(256), 0, st>>>(vp);
+    LAUNCH_CHECK("ic2_verify_kernel");
     return ABED_OK;
 }
 

@@ -99,6 +99,9 @@ struct ConvParams {
     int fic_parts, fic_rows_blocks, fic_rows_lead, fic_from_rows;
     int32_t *fic_xsum_in;          // batch-summed input image [H][W][C] handed over by the previous layer (fic_from_rows == 2)
     int32_t *fic_xsum_next;        // batch sum of this layer's int8 output [P][Q][K], added to (must start at zero), or null
+    // IC option 2 (Sec. 3.2): per-filter sums of a tile's accumulators over its pixels and entries,
+    // [grid_m * grid_b][grid_n * WK * 16] int64, or null
+    long long *ic2_part;
 };
 
 __device__ __forceinline__ int lds_off(int row, int chunk)
@@ -195,7 +198,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             if (tid >= 256 || blk >= p.fic_rows_blocks) return;
             FicRowsParams rp;
             rp.x = p.x; rp.wsum = p.fic_wsum; rp.xrows = p.fic_xrows; rp.dotpart = p.fic_dotpart;
-            rp.N = p.N; rp.H = p.H; rp.W = p.W; rp.C = p.C; rp.R = p.R; rp.S = p.S; rp.P = p.P; rp.Q = p.Q;
+            rp.N = p.N; rp.H = p.H; rp.W = p.W; rp.C = p.C; rp.R = p.fic_wsum ? p.R : 0; rp.S = p.S; rp.P = p.P; rp.Q = p.Q;
             rp.sh = p.sh; rp.sw = p.sw; rp.ph = p.ph; rp.pw = p.pw; rp.parts = p.fic_parts; rp.from_rows = p.fic_from_rows; rp.xsum = p.fic_xsum_in;
             int (*cols)[64] = reinterpret_cast<int (*)[64]>(lds);
             unsigned char (*meets)[64] = reinterpret_cast<unsigned char (*)[64]>(lds + 64 * 64 * 4);
@@ -626,6 +629,37 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         if (lane == 0) e64[wave] = t;
         __syncthreads();
         if (tid == 0) p.fic_ocs[tile] = e64[0] + e64[1] + e64[2] + e64[3];
+    }
+
+    // (1c) IC option 2 (Sec. 3.2): the output fmaps reduced over batch, height and width, one 64-bit sum
+    // per filter (Sec. 4.1); this tile's share.  Two passes through the LDS area of the IC pass, one with
+    // the low and one with the high 16 bits of the accumulators (a tile sums at most 16 * MB of them,
+    // so neither half overflows 32 bits): a lane adds its entries in registers, then thread f of the
+    // first 16 * WK adds filter f's values over the 4 waves and the 16 pixels.
+    if (p.ic2_part) {
+        const i32x4 low16 = {0xffff, 0xffff, 0xffff, 0xffff};
+        long long total = 0;
+        for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+            for (int kb = 0; kb < WK; ++kb) {
+                i32x4 c = zero4;
+#pragma unroll
+                for (int i = 0; i < WM; ++i) c += pass ? (acc[i][kb] >> 16) : (acc[i][kb] & low16);
+                *reinterpret_cast<i32x4 *>(e_ic + ((wave * WK + kb) * 64 + lane) * 4) = c;
+            }
+            __syncthreads();
+            if (tid < WK * 16) {
+                const int kb = tid >> 4, g = (tid >> 2) & 3, v = tid & 3;
+                long long sum = 0;
+                for (int w = 0; w < 4; ++w)
+#pragma unroll 4
+                    for (int j = 0; j < 16; ++j) sum += e_ic[((w * WK + kb) * 64 + g * 16 + j) * 4 + v];
+                total += pass ? sum * 65536 : sum;
+            }
+            __syncthreads();
+        }
+        if (tid < WK * 16)
+            p.ic2_part[((long long)pg * p.grid_b + nt) * (p.grid_n * WK * 16) + kt * (WK * 16) + tid] = total;
     }
 
     // (2) FC residual of every row of the tile (Sec. 3.1; digit shifts of Sec. 4.1)
