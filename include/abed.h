@@ -76,6 +76,13 @@ typedef enum {
  * Both at once, or either with ABED_NONE / ABED_DUPLICATE, is ABED_EINVAL. */
 #define ABED_ONLY_FC 0x100
 #define ABED_ONLY_IC 0x200
+/* Space reserved for the checksum filters (Sec. 6.2: a layer whose filter count leaves room, as pruned
+ * networks do, pays nothing for the larger convolution).  OR into ABED_FUSED_OCG / ABED_FUSED_IOCG (int8,
+ * with or without ABED_ONLY_FC): the d_f checksum filters ride in the free rows of the last block of 16
+ * filters instead of a block of their own.  Needs K % 16 != 0 and K % 16 + d_f <= 16 (else
+ * ABED_EUNSUPPORTED), and the caller must keep filters and checksum filters in ONE buffer, wchk ==
+ * w + K*R*S*C (else ABED_EINVAL).  Outputs and flags are those of the plain layout. */
+#define ABED_PACKED_FC 0x400
 
 typedef enum { ABED_INT8 = 0, ABED_FP16 = 1 } abed_dtype_t;
 

@@ -54,6 +54,7 @@ struct Plan {
     int wm, wk, mb;                       // entries per wave, filter blocks per tile, entries per tile
     int kg;                               // groups of 4 waves along the reduction axis
     int variant;                          // the variant without the scheme selection bits
+    int packed;                           // digit filters in the free rows of the last real filter block
     int grid_m, grid_b, grid_n;
     // workspace offsets in bytes (-1 = unused)
     long long off_cnt_fc, off_cnt_ic, off_convout, off_yf, off_yi, off_yfi, off_fc, off_ic, off_nx, ws_bytes;
@@ -125,13 +126,16 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
         return ABED_EINVAL;
     if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return ABED_EINVAL;
     // scheme selection bits: one of FC alone / IC alone, with a checked variant only
-    const int only = variant & ~0xff;
+    const int packed = variant & ABED_PACKED_FC;
+    const int only = variant & ~0xff & ~ABED_PACKED_FC;
     variant &= 0xff;
     if (variant < ABED_NONE || variant > ABED_DUPLICATE) return ABED_EINVAL;
     if (only != 0 && only != ABED_ONLY_FC && only != ABED_ONLY_IC) return ABED_EINVAL;
     if (only != 0 && !(variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG)) return ABED_EINVAL;
     if (only == ABED_ONLY_FC && variant == ABED_FUSED_IOCG) return ABED_EINVAL;
+    if (packed && (only == ABED_ONLY_IC || dtype != ABED_INT8 || !(variant == ABED_FUSED_OCG || variant == ABED_FUSED_IOCG))) return ABED_EINVAL;
     pl.variant = variant;
+    pl.packed = 0;
     if (dtype != ABED_INT8 && dtype != ABED_FP16) return ABED_EINVAL;
     const bool f16 = dtype == ABED_FP16;
     pl.esize = f16 ? 2 : 1;
@@ -156,7 +160,12 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     if (only == ABED_ONLY_IC) pl.d_f = 0;
     pl.kblk = (d->K + 15) / 16;
     pl.n_entries = d->N + (checked ? pl.d_i : 0);
-    pl.n_fblk = pl.kblk + (checked && pl.d_f ? 1 : 0);
+    if (packed) {
+        // room for the digit filters behind the last real filter of its block?
+        if (d->K % 16 == 0 || d->K % 16 + pl.d_f > 16) return ABED_EUNSUPPORTED;
+        pl.packed = 1;
+    }
+    pl.n_fblk = pl.kblk + (checked && pl.d_f && !pl.packed ? 1 : 0);
     choose_tile(pl);
 
     // workspace: the two counter arrays come first and must be zero before the first call
@@ -190,6 +199,7 @@ void fill_params(ConvParams &cp, const abed_conv_desc_t *d, const Plan &pl)
     cp.cb = d->C * pl.esize; cp.crsb = pl.crs * pl.esize; cp.nsteps = (cp.crsb + 63) / 64;
     cp.n_entries = pl.n_entries; cp.n_fblk = pl.n_fblk; cp.kblk = pl.kblk;
     cp.d_f = pl.d_f; cp.d_i = pl.d_i;
+    cp.packed_df = pl.packed ? pl.d_f : 0;
     cp.grid_m = pl.grid_m; cp.grid_b = pl.grid_b; cp.grid_n = pl.grid_n;
     cp.kt_slowest = env_int("ABED_KT_SLOWEST", (long long)d->K * pl.crs > (long long)d->N * d->H * d->W * d->C ? 1 : 0);
     cp.dbg = env_int("ABED_DBG", 0);
@@ -625,6 +635,7 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     if (int8_out && (!epi->scale || !epi->bias)) return ABED_EINVAL;
     const bool checked = variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG;
     if (checked && ((pl.d_f && !wchk) || (pl.d_i && !xchk) || !flags)) return ABED_EINVAL;
+    if (pl.packed && wchk != w + (long long)desc->K * pl.crs) return ABED_EINVAL;   // the digit filters must follow w in memory
     if (variant == ABED_DUPLICATE && (!y2 || !flags)) return ABED_EINVAL;
     if (variant == ABED_FUSED_IOCG && int8_out && !xchk_next) return ABED_EINVAL;
     if (checked && (!workspace || (long long)workspace_bytes < pl.ws_bytes)) return ABED_EWORKSPACE;

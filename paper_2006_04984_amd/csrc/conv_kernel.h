@@ -16,6 +16,9 @@
 // (the corner of the row+column scheme, Sec. 2.1).
 // Either scheme can run alone (Table 1 of Sec. 3.4 compares them): with d_i = 0 there are no digit
 // images and no IC residual, with d_f = 0 no digit block and no FC residual; the corner needs both.
+// When K is not a multiple of 16 and the last real block has d_f free rows, the digit filters can
+// take those rows instead of a block of their own (the caller stores them behind the K filters in
+// one buffer): the layer then costs no more matrix work than without FC.
 //
 // Tile = 16 consecutive output pixels x MB batch entries x WK filter blocks.
 // MFMA operand roles: filters are the "A" operand (rows of D), the 16 pixels of
@@ -78,6 +81,7 @@ struct ConvParams {
     int n_fblk;       // ceil(K/16), or that + 1 when checked
     int kblk;         // ceil(K/16): index of the digit block
     int d_f, d_i;
+    int packed_df;    // d_f when the digit filters are rows K..K+d_f-1 of the last real block (and of w's buffer), else 0
     int grid_m, grid_b, grid_n;
     int kt_slowest;   // order of the tile list: 1 = filter tile slowest, 0 = pixel group slowest
     int mode;
@@ -234,7 +238,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     const int ld_chunk = (lane & 3) ^ ((ld_row >> 1) & 3);   // which 16 bytes of the 64-byte step this lane fetches
     const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, p.N * (int)HWC, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_xc = __builtin_amdgcn_make_buffer_rsrc((void *)p.xchk, 0, p.xchk ? p.d_i * (int)HWC : 0, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, p.K * p.crsb, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, (p.K + p.packed_df) * p.crsb, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_wc = __builtin_amdgcn_make_buffer_rsrc((void *)p.wchk, 0, p.wchk ? p.d_f * p.crsb : 0, 0x00020000);
     // pixel of this lane's row (the same for every entry block)
     int h0 = INT_MIN / 2, w0 = 0;
@@ -265,7 +269,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         if (b < WK) {
             const int fb = kt * WK + b;                       // global filter block
             const int f = fb * 16 + ld_row;
-            if (fb < p.kblk) { blk_rs[i] = rs_w; if (f < p.K) blk_voff[i] = f * p.crsb + ld_chunk * 16; }
+            if (fb < p.kblk) { blk_rs[i] = rs_w; if (f < p.K + p.packed_df) blk_voff[i] = f * p.crsb + ld_chunk * 16; }
             else if (fb == p.kblk && fb < p.n_fblk) { blk_rs[i] = rs_wc; if (ld_row < p.d_f) blk_voff[i] = ld_row * p.crsb + ld_chunk * 16; }
         } else {
             const int e = nt * MB + (b - WK);
@@ -672,7 +676,17 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             for (int kb = 0; kb < WK; ++kb) {
                 const int fb = kt * WK + kb;
                 if (fb < p.kblk) {
-                    r += (unsigned)acc[i][kb][0] + (unsigned)acc[i][kb][1] + (unsigned)acc[i][kb][2] + (unsigned)acc[i][kb][3];
+                    if (p.packed_df && fb == p.kblk - 1) {
+                        // the digit filters share this block with the last real filters
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int k = fb * 16 + lg * 4 + v;
+                            if (k < p.K) r += (unsigned)acc[i][kb][v];
+                            else if (k < p.K + p.packed_df) r -= (unsigned)acc[i][kb][v] << (8 * (k - p.K));
+                        }
+                    } else {
+                        r += (unsigned)acc[i][kb][0] + (unsigned)acc[i][kb][1] + (unsigned)acc[i][kb][2] + (unsigned)acc[i][kb][3];
+                    }
                 } else if (fb == p.kblk) {
                     if (lg == 0)
                         r -= (unsigned)acc[i][kb][0] + ((unsigned)acc[i][kb][1] << 8) + ((unsigned)acc[i][kb][2] << 16) + ((unsigned)acc[i][kb][3] << 24);
@@ -688,6 +702,19 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         }
     }
     if (p.dbg & 1) return;
+
+    // flag bits of a non-zero IC residual vector: a real filter's column is an IC mismatch, a digit
+    // filter's column a disagreement of the checksums with each other
+    auto ic_bits = [&](const i32x4 c, int fb, int g) -> uint32_t {
+        if ((c[0] | c[1] | c[2] | c[3]) == 0) return 0u;
+        if (fb >= p.kblk) return 4u;
+        if (!p.packed_df || fb != p.kblk - 1) return 2u;
+        uint32_t b = 0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (c[v] != 0) b |= (fb * 16 + g * 4 + v < p.K) ? 2u : 4u;
+        return b;
+    };
 
     int nx[WK][4];   // batch sums of the int8 outputs (variant 5)
 #pragma unroll
@@ -732,7 +759,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             const long long part = ((((long long)pg * p.grid_n + kt) * p.grid_b + nt) * WK + kb) * 256 + lane * 4;
             if (pass == 0) {
                 if (checking && ic_local) {
-                    if ((c[0] | c[1] | c[2] | c[3]) != 0) my_flag |= (fb < p.kblk) ? 2u : 4u;
+                    my_flag |= ic_bits(c, fb, lg);
                 } else {
                     st_dev4(p.ws_ic + part, c);
                 }
@@ -901,7 +928,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 s += ld_dev4(rs_ic, off);
                 if (want_next) sn += ld_dev4(rs_nx, off);
             }
-            if ((s[0] | s[1] | s[2] | s[3]) != 0) late |= (fb < p.kblk) ? 2u : 4u;
+            late |= ic_bits(s, fb, ln >> 4);
             if (want_next && fb < p.kblk) {
                 const int px = pg * 16 + (ln & 15), k = fb * 16 + (ln >> 4) * 4;
                 if (px < PQ) {

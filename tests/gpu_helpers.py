@@ -34,6 +34,11 @@ class GpuConv:
 
     def prepare(self, w):
         self.w = w if torch.is_tensor(w) else to_dev(w)
+        if self.variant & abed.PACKED_FC:
+            # filters and checksum filters in one buffer, the checksum filters right behind the K filters
+            both = torch.empty((self.shape.K + self.lay.d_f, self.shape.R, self.shape.S, self.shape.C), dtype=torch.int8, device=DEV)
+            both[: self.shape.K].copy_(self.w)
+            self.w, self.wchk = both[: self.shape.K], both[self.shape.K:]
         if self.lay.d_f:                       # none with the batch checksum scheme alone
             abed.filter_prepare_int8(self.desc, self.w, self.wchk)
 

@@ -94,7 +94,26 @@ def test_layout_of_one_scheme_alone(L, s):
 
 def test_scheme_selection_errors(L):
     d = abed.desc_from_shape(CONFIG1[0])
-    for v in (0 | abed.ONLY_FC, 6 | abed.ONLY_IC, 4 | abed.ONLY_FC | abed.ONLY_IC, 5 | abed.ONLY_FC, 4 | 0x400):
+    for v in (0 | abed.ONLY_FC, 6 | abed.ONLY_IC, 4 | abed.ONLY_FC | abed.ONLY_IC, 5 | abed.ONLY_FC, 4 | 0x800,
+              4 | abed.PACKED_FC | abed.ONLY_IC, 3 | abed.PACKED_FC):
         with pytest.raises(AbedError) as e:
             abed.get_layout(d, 0, v)
         assert e.value.status == 1
+
+
+def test_packed_checksum_filters_layout(L):
+    """Checksum filters in the free rows of the last block of 16 filters (Sec. 6.2, reserved space):
+    one filter block fewer than the plain layout when there is room, unsupported when there is not."""
+    from synth import ConvShape
+    for K, ok in ((60, True), (62, True), (63, False), (64, False), (13, True), (15, False), (77, True)):
+        d = abed.desc_from_shape(ConvShape(8, 6, 6, 16, K, 3, 3, 1, 1, 1, 1))
+        if not ok:
+            with pytest.raises(AbedError) as e:
+                abed.get_layout(d, 0, 4 | abed.PACKED_FC)
+            assert e.value.status == 2
+            continue
+        plain = abed.get_layout(d, 0, 4)
+        packed = abed.get_layout(d, 0, 4 | abed.PACKED_FC)
+        assert packed.d_f == plain.d_f and packed.wchk_bytes == plain.wchk_bytes
+        assert packed.grid_n * packed.tile_n >= (K + 15) // 16 * 16 > (packed.grid_n - 1) * packed.tile_n
+        assert packed.grid_n * packed.tile_n <= plain.grid_n * plain.tile_n

@@ -118,3 +118,60 @@ def test_fp16(oracle, only):
     idx = y.size // 2
     y2, flags2 = g.run(x, rtol=1e-3, atol=1e-3, inject=(1, idx, 14))       # exponent bit: far beyond the threshold
     assert flags2.any() and not (flags2 & ~np.uint32(1 if only == "fc" else 2)).any()
+
+
+PACKED_SHAPES = [
+    ConvShape(32, 9, 9, 32, 60, 3, 3, 1, 1, 1, 1, "k60"),                  # digits in rows 12, 13 of block 3
+    ConvShape(37, 7, 6, 16, 205, 3, 3, 2, 2, 1, 1, "k205_stride2"),         # several filter tiles; digits in rows 13, 14
+    ConvShape(9, 6, 6, 128, 13, 1, 1, 1, 1, 0, 0, "k13_1x1"),               # one block
+    ConvShape(20, 5, 5, 64, 30, 3, 3, 1, 1, 1, 1, "k30"),                   # digits fill the block (rows 14, 15)
+]
+
+
+@pytest.mark.parametrize("scheme", ["fc", "both"])
+@pytest.mark.parametrize("variant", [4, 5])
+@pytest.mark.parametrize("s", PACKED_SHAPES, ids=lambda s: s.name)
+def test_packed_checksum_filters(oracle, s, variant, scheme):
+    """The checksum filters in the free rows of the last block of 16 filters (Sec. 6.2: reserved space
+    for the filter checksums): outputs and flags are those of the plain layout."""
+    from gpu_helpers import GpuConv, flags_match
+    if variant == 5 and scheme == "fc":
+        pytest.skip("no batch checksum to hand on with FC alone")
+    print("case", s.name, "variant", variant, scheme, flush=True)
+    x, w = int8_tensors(s, 6767)
+    ref = oracle.abed_int8(x, w, s)
+    v = variant | abed.PACKED_FC | (abed.ONLY_FC if scheme == "fc" else 0)
+    g = GpuConv(s, v)
+    g.prepare(w)
+    assert g.wchk.data_ptr() == g.w.data_ptr() + s.K * s.R * s.S * s.C
+    y, flags = g.run(x)
+    assert np.array_equal(y, ref["y"]) and not flags.any()
+    assert np.array_equal(g.wchk.cpu().numpy(), ref["wchk"])
+    for idx, bit in ((y.size // 3, 21), (y.size - 1, 31), (s.K - 1, 0)):
+        ref2 = oracle.abed_int8(x, w, s, acc_flip=(idx, bit))
+        y2, f2 = g.run(x, inject=(1, idx, bit))
+        assert np.array_equal(y2, ref2["y"]) and f2.any() and flags_match(f2, ref2, s, g.lay)
+    if scheme == "both":
+        # a corrupted checksum image disagrees with the checksum filters too: IC bit and corner bit,
+        # the latter from the digit columns that now sit among the real filters' columns
+        g.xchk.view(torch.uint8).view(-1)[5] ^= 0x04
+        xc = ref["xchk"].copy(); oracle.flip_bit(xc, 5, 2)
+        ref3 = oracle.abed_int8(x, w, s, xchk=xc)
+        y3, f3 = g.run(x, compute_xchk=False)
+        assert np.array_equal(y3, ref["y"]) and flags_match(f3, ref3, s, g.lay) and (f3 & 4).any()
+    # a filter corrupted after its checksum was made
+    g.w.view(torch.uint8).view(-1)[77] ^= 0x10
+    w2 = w.copy(); oracle.flip_bit(w2, 77, 4)
+    ref4 = oracle.abed_int8(x, w2, s, wchk=ref["wchk"])
+    y4, f4 = g.run(x)
+    assert np.array_equal(y4, ref4["y"]) and flags_match(f4, ref4, s, g.lay) and (f4 & 1).any()
+
+
+def test_packed_needs_one_buffer():
+    from gpu_helpers import GpuConv
+    s = PACKED_SHAPES[0]
+    g = GpuConv(s, 4 | abed.PACKED_FC)
+    g.w = torch.zeros((s.K, s.R, s.S, s.C), dtype=torch.int8, device="cuda:0")     # wchk elsewhere
+    with pytest.raises(abed.AbedError) as e:
+        g.run(torch.zeros((s.N, s.H, s.W, s.C), dtype=torch.int8, device="cuda:0"))
+    assert e.value.status == 1
