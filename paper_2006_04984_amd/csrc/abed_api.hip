@@ -459,7 +459,8 @@ abed_status_t abed_ic2_get_layout(const abed_conv_desc_t *desc, int32_t variant,
     out->n_values = desc->K;
     const long long partials = variant == ABED_UNFUSED ? 8LL * kIc2SumBlocks * desc->K
                                                        : 8LL * pl.grid_m * pl.grid_b * pl.grid_n * pl.wk * 16;
-    out->workspace_bytes = 256 + align256(partials) + (variant == ABED_UNFUSED ? align256(4LL * desc->N * pl.PQ * desc->K) : 0);
+    // 256 bytes kept free, the filter-sized input checksum, the partial output sums, ConvOut of the unfused option
+    out->workspace_bytes = 256 + align256(4LL * pl.crs) + align256(partials) + (variant == ABED_UNFUSED ? align256(4LL * desc->N * pl.PQ * desc->K) : 0);
     return ABED_OK;
 }
 
@@ -487,7 +488,8 @@ abed_status_t abed_ic2_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
     if ((s = abed_ic2_get_layout(desc, variant, &lay)) != ABED_OK) return s;
     if (!workspace || (long long)workspace_bytes < lay.workspace_bytes) return ABED_EWORKSPACE;
     const int ntiles = pl.grid_m * pl.grid_b * pl.grid_n;
-    long long *part = (long long *)((char *)workspace + 256);
+    int32_t *X = (int32_t *)((char *)workspace + 256);
+    long long *part = (long long *)((char *)workspace + 256 + align256(4LL * pl.crs));
     const int rows_blocks = fic_rows_blocks(desc, variant);
 
     ConvParams cp;
@@ -495,14 +497,17 @@ abed_status_t abed_ic2_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
     cp.x = x; cp.w = w; cp.mode = MODE_PLAIN;
     set_injection(cp, desc, pl, inject);
     const int grid = (ntiles + 7) / 8 * 8;
+    Ic2FoldParams fp;
+    fp.xrows = xrows; fp.X = X; fp.H = desc->H; fp.C = desc->C; fp.R = desc->R; fp.S = desc->S; fp.P = pl.P;
+    fp.sh = desc->stride_h; fp.ph = desc->pad_h; fp.parts = lay.xrows_parts;
     Ic2VerifyParams vp;
-    vp.w = w; vp.xrows = xrows; vp.part = part; vp.result = (long long *)result; vp.flags = flags;
-    vp.K = desc->K; vp.H = desc->H; vp.C = desc->C; vp.R = desc->R; vp.S = desc->S; vp.P = pl.P;
-    vp.sh = desc->stride_h; vp.ph = desc->pad_h; vp.parts = lay.xrows_parts;
+    vp.w = w; vp.X = X; vp.part = part; vp.result = (long long *)result; vp.flags = flags;
+    vp.K = desc->K; vp.crs = pl.crs;
     if (variant == ABED_FUSED_OCG) {
-        // Two launches: the input checksum workgroups lead the convolution's launch, whose tiles reduce
-        // their accumulators per filter; then one workgroup per filter convolves the checksum tensor
-        // with its filter, adds up the partial output sums and compares.
+        // Three launches: the input checksum workgroups lead the convolution's launch, whose tiles reduce
+        // their accumulators per filter; a small kernel folds the row-wise checksum to the filter's
+        // size; then one workgroup per filter convolves the checksum tensor with its filter, adds up
+        // the partial output sums and compares.
         const int lead = compute_xrows ? (rows_blocks + 7) / 8 * 8 : 0;
         cp.y = y; cp.ic2_part = part;
         cp.fic_xrows = xrows; cp.fic_parts = lay.xrows_parts; cp.fic_rows_blocks = compute_xrows ? rows_blocks : 0; cp.fic_rows_lead = lead;
@@ -510,13 +515,15 @@ abed_status_t abed_ic2_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
         if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, lead + grid, st)) return ABED_EUNSUPPORTED;
         LAUNCH_CHECK("conv_kernel (IC option 2, fused)");
         vp.nrows = pl.grid_m * pl.grid_b; vp.kstride = pl.grid_n * pl.wk * 16;
+        ic2_fold_kernel<<<dim3((pl.crs + 63) / 64), dim3(1024), 0, st>>>(fp);
+        LAUNCH_CHECK("ic2_fold_kernel");
         ic2_verify_kernel<<<dim3(desc->K), dim3(256), 0, st>>>(vp);
         LAUNCH_CHECK("ic2_verify_kernel");
         return ABED_OK;
     }
     // unfused option: one kernel per task
     if (compute_xrows && (s = fic_input_rows(desc, pl, variant, x, nullptr, xrows, nullptr, false, st)) != ABED_OK) return s;
-    int32_t *convout = int8_out ? (int32_t *)((char *)workspace + 256 + align256(8LL * kIc2SumBlocks * desc->K)) : (int32_t *)y;
+    int32_t *convout = int8_out ? (int32_t *)((char *)workspace + 256 + align256(4LL * pl.crs) + align256(8LL * kIc2SumBlocks * desc->K)) : (int32_t *)y;
     cp.y = convout;
     if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("conv_kernel (unchecked)");
@@ -529,6 +536,8 @@ abed_status_t abed_ic2_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
         LAUNCH_CHECK("epilog_i8_kernel");
     }
     vp.nrows = kIc2SumBlocks; vp.kstride = desc->K;
+    ic2_fold_kernel<<<dim3((pl.crs + 63) / 64), dim3(1024), 0, st>>>(fp);
+    LAUNCH_CHECK("ic2_fold_kernel");
     ic2_verify_kernel<<<dim3(desc->K), dim3(256), 0, st>>>(vp);
     LAUNCH_CHECK("ic2_verify_kernel");
     return ABED_OK;

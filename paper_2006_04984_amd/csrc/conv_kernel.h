@@ -638,11 +638,14 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     // (1c) IC option 2 (Sec. 3.2): the output fmaps reduced over batch, height and width, one 64-bit sum
     // per filter (Sec. 4.1); this tile's share.  Two passes through the LDS area of the IC pass, one with
     // the low and one with the high 16 bits of the accumulators (a tile sums at most 16 * MB of them,
-    // so neither half overflows 32 bits): a lane adds its entries in registers, then thread f of the
-    // first 16 * WK adds filter f's values over the 4 waves and the 16 pixels.
+    // so neither half overflows 32 bits): a lane adds its entries in registers; then thread (f, w) adds
+    // filter f's values of wave w over the 16 pixels and the 4 threads of a filter add up across lanes.
     if (p.ic2_part) {
+        constexpr int NF = WK * 16, NIT = (4 * NF + 255) / 256;
         const i32x4 low16 = {0xffff, 0xffff, 0xffff, 0xffff};
-        long long total = 0;
+        long long total[NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) total[it] = 0;
         for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
             for (int kb = 0; kb < WK; ++kb) {
@@ -652,18 +655,28 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 *reinterpret_cast<i32x4 *>(e_ic + ((wave * WK + kb) * 64 + lane) * 4) = c;
             }
             __syncthreads();
-            if (tid < WK * 16) {
-                const int kb = tid >> 4, g = (tid >> 2) & 3, v = tid & 3;
-                long long sum = 0;
-                for (int w = 0; w < 4; ++w)
-#pragma unroll 4
-                    for (int j = 0; j < 16; ++j) sum += e_ic[((w * WK + kb) * 64 + g * 16 + j) * 4 + v];
-                total += pass ? sum * 65536 : sum;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int idx = it * 256 + tid, w = idx & 3, f = idx >> 2;
+                int sum = 0;
+                if (f < NF) {
+                    const int kb = f >> 4, g = (f >> 2) & 3, v = f & 3;
+                    const int *src = e_ic + ((w * WK + kb) * 64 + g * 16) * 4 + v;
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) sum += src[((j + g * 4 + w) & 15) * 4];   // rotated: the 64 lanes hit 64 banks
+                }
+                sum += __shfl_xor(sum, 1, 64);
+                sum += __shfl_xor(sum, 2, 64);
+                total[it] += pass ? (long long)sum * 65536 : (long long)sum;
             }
             __syncthreads();
         }
-        if (tid < WK * 16)
-            p.ic2_part[((long long)pg * p.grid_b + nt) * (p.grid_n * WK * 16) + kt * (WK * 16) + tid] = total;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int idx = it * 256 + tid, f = idx >> 2;
+            if (f < NF && (idx & 3) == 0)
+                p.ic2_part[((long long)pg * p.grid_b + nt) * (p.grid_n * NF) + kt * NF + f] = total[it];
+        }
     }
 
     // (2) FC residual of every row of the tile (Sec. 3.1; digit shifts of Sec. 4.1)

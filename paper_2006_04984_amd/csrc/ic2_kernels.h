@@ -4,9 +4,9 @@
 //
 // The input checksum is the one the FIC scheme uses, in its row-wise form xrows[j,h,s,c] (fic_device.h):
 // X[r,s,c] is the sum of xrows over the batch parts j and over the input rows h that filter row r
-// meets.  As there, X is never materialised:
-//   chk[k] = sum_{r,s,c} X[r,s,c] * w[k,r,s,c] = sum_{h,s,c} (sum_j xrows[j,h,s,c]) * (sum of w[k,r,s,c] over the r that meet h).
-// All sums are 64-bit (Sec. 4.1).
+// meets.  Here X is materialised once (a small kernel), because all K dot products
+//   chk[k] = sum_{r,s,c} X[r,s,c] * w[k,r,s,c]
+// need it.  The dot products and the output sums are 64-bit (Sec. 4.1).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -37,39 +37,65 @@ __global__ __launch_bounds__(256) void ic2_output_sums_kernel(const int32_t *y, 
     for (int k = tid; k < K; k += 256) part[(long long)blockIdx.x * K + k] = (long long)colsum[k];
 }
 
+struct Ic2FoldParams {
+    const int32_t *xrows;       // [parts][H][S][C]
+    int32_t *X;                 // [R][S][C]
+    int H, C, R, S, P, sh, ph, parts;
+};
+
+// The filter-sized input checksum from its row-wise form: X[r,s,c] = sum of xrows[j,h,s,c] over the batch
+// parts j and over the input rows h = p*sh - ph + r that filter row r meets at some output row p.
+// (int32 suffices: the host has checked 8 + log2(PQN) <= 31 bits, Sec. 4.1.)
+// A workgroup takes 64 consecutive (r,s,c) elements; its 16 slices of 64 threads share the (j, p) pairs.
+__global__ __launch_bounds__(1024) void ic2_fold_kernel(const Ic2FoldParams p)
+{
+    __shared__ int red[16][64];
+    const int tid = threadIdx.x, slice = tid >> 6, l = tid & 63;
+    const int sc = p.S * p.C, rsc = p.R * sc;
+    const int e = blockIdx.x * 64 + l;
+    int sum = 0;
+    if (e < rsc) {
+        const int r = e / sc, rest = e - r * sc;
+        const long long hsc = (long long)p.H * sc;
+#pragma unroll 4
+        for (int i = slice; i < p.parts * p.P; i += 16) {
+            const int j = i / p.P, op = i - j * p.P;
+            const int h = op * p.sh - p.ph + r;
+            if (h >= 0 && h < p.H) sum += p.xrows[j * hsc + (long long)h * sc + rest];
+        }
+    }
+    red[slice][l] = sum;
+    __syncthreads();
+    if (slice == 0 && e < rsc) {
+        int t = 0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) t += red[q][l];
+        p.X[e] = t;
+    }
+}
+
 struct Ic2VerifyParams {
     const int8_t *w;            // [K][R][S][C]
-    const int32_t *xrows;       // [parts][H][S][C]
+    const int32_t *X;           // [R][S][C] input checksum
     const long long *part;      // [nrows][kstride] partial per-filter output sums
     long long *result;          // [0..K) reduced outputs, [K..2K) checksum tensor convolved with the filters
     uint32_t *flags;            // [K]: 1 = the two differ
-    int K, H, C, R, S, P, sh, ph, parts, nrows, kstride;
+    int K, crs, nrows, kstride;
 };
 
-// One workgroup per filter k: the checksum convolution's value for k, the sum of the partial output
-// sums of k, and the comparison (the element-wise verification of Sec. 3.2 option 2).
+// One workgroup per filter k: the checksum convolution's value for k (the checksum tensor has the
+// extent of one filter, so that is one dot product), the sum of the partial output sums of k, and the
+// comparison (the element-wise verification of Sec. 3.2 option 2).
 __global__ __launch_bounds__(256) void ic2_verify_kernel(const Ic2VerifyParams p)
 {
     __shared__ long long red[2][4];
     const int k = blockIdx.x, tid = threadIdx.x;
-    const int sc = p.S * p.C;
-    const long long hsc = (long long)p.H * sc;
-    const int8_t *wk = p.w + (long long)k * p.R * sc;
+    const int8_t *wk = p.w + (long long)k * p.crs;
     long long chk = 0;
-    for (long long e = tid; e < hsc; e += 256) {
-        const int h = (int)(e / sc), rest = (int)(e - (long long)h * sc);
-        int wsum = 0;                             // filter rows r that meet input row h:  h = q*sh - ph + r
-        for (int r = 0; r < p.R; ++r) {
-            const int t = h + p.ph - r;
-            if (t >= 0 && t % p.sh == 0 && t / p.sh < p.P) wsum += wk[r * sc + rest];
-        }
-        if (wsum != 0) {
-            long long xr = 0;
-            for (int j = 0; j < p.parts; ++j) xr += p.xrows[j * hsc + e];
-            chk += xr * wsum;
-        }
-    }
+#pragma unroll 4
+    for (int e = tid; e < p.crs; e += 256) chk += (long long)p.X[e] * wk[e];
     long long osum = 0;
+#pragma unroll 4
     for (int i = tid; i < p.nrows; i += 256) osum += p.part[(long long)i * p.kstride + k];
     for (int m = 32; m >= 1; m >>= 1) { chk += __shfl_xor(chk, m, 64); osum += __shfl_xor(osum, m, 64); }
     if ((tid & 63) == 0) { red[0][tid >> 6] = chk; red[1][tid >> 6] = osum; }

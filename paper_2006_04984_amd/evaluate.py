@@ -66,6 +66,10 @@ class Int8Layer:
             self.scale, self.bias = torch.from_numpy(sc).to(DEV), torch.from_numpy(bi).to(DEV)
             self.epi = (self.scale, self.bias, True)
         abed.workspace_init(self.ws)
+        if self.variant & abed.PACKED_FC:                 # filters and checksum filters in one buffer
+            both = torch.empty((s.K + self.lay.d_f, s.R, s.S, s.C), dtype=torch.int8, device=DEV)
+            both[: s.K].copy_(self.w)
+            self.w, self.wchk = both[: s.K], both[s.K:]
         if self.lay.d_f:
             abed.filter_prepare_int8(self.desc, self.w, self.wchk)
 
@@ -105,6 +109,32 @@ class FicLayer:
                            self.flag, epilogue=self.epi, workspace=self.ws, xsum_in=self.xsum_in, xsum_next=self.xsum_next)
 
 
+class Ic2Layer:
+    """Device buffers of one int8 convolution checked by IC option 2 (Sec. 3.2)."""
+
+    def __init__(self, s, seed, variant, epilogue=False):
+        from synth import int8_tensors, requant_params
+        self.s, self.variant = s, Variant(variant)
+        self.desc = abed.desc_from_shape(s)
+        lay = abed.ic2_get_layout(self.desc, self.variant)
+        xh, wh = int8_tensors(s, seed)
+        self.x, self.w = torch.from_numpy(xh).to(DEV), torch.from_numpy(wh).to(DEV)
+        self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int8 if epilogue else torch.int32, device=DEV)
+        self.xrows = torch.empty((lay.xrows_parts, s.H, s.S, s.C), dtype=torch.int32, device=DEV)
+        self.result = torch.zeros((2, s.K), dtype=torch.int64, device=DEV)
+        self.flags = torch.zeros((s.K,), dtype=torch.int32, device=DEV)
+        self.ws = torch.zeros((max(256, lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
+        self.epi = None
+        if epilogue:
+            sc, bi = requant_params(s, seed)
+            self.scale, self.bias = torch.from_numpy(sc).to(DEV), torch.from_numpy(bi).to(DEV)
+            self.epi = (self.scale, self.bias, True)
+
+    def run(self):
+        abed.ic2_conv_int8(self.desc, self.x, self.w, self.xrows, True, self.y, self.variant, self.result, self.flags,
+                           epilogue=self.epi, workspace=self.ws)
+
+
 def cmd_layers(args):
     from synth import CONFIG2, CONFIG3, seed_for
     layers = {2: CONFIG2, 3: CONFIG3}[args.config]
@@ -135,10 +165,15 @@ def cmd_layers(args):
             F.run()
             t_fic = _graph_time(lambda: F.run(), stream)
             assert int(F.flag.item()) == 0
+            I2 = Ic2Layer(s, seed_for(args.config, i), Variant.FUSED_OCG, epilogue=epi)
+            I2.run()
+            t_ic2 = _graph_time(lambda: I2.run(), stream)
+            assert int(I2.flags.abs().max().item()) == 0
             nbytes = s.min_bytes(1, 1, 1 if epi else 4)
             row[tag] = dict(unchecked_us=t[Variant.NONE] * 1e6, checked_us=t[Variant.FUSED_OCG] * 1e6,
                             fic_fused_us=t_fic * 1e6, fic_fused_overhead_pct=100.0 * (t_fic / t[Variant.NONE] - 1.0),
                             duplicate_us=t[Variant.DUPLICATE] * 1e6,
+                            ic2_fused_us=t_ic2 * 1e6, ic2_fused_overhead_pct=100.0 * (t_ic2 / t[Variant.NONE] - 1.0),
                             fc_only_us=t[FC_ONLY] * 1e6, fc_only_overhead_pct=100.0 * (t[FC_ONLY] / t[Variant.NONE] - 1.0),
                             ic_only_us=t[IC_ONLY] * 1e6, ic_only_overhead_pct=100.0 * (t[IC_ONLY] / t[Variant.NONE] - 1.0),
                             unchecked_tops=s.ops / t[Variant.NONE] / 1e12, checked_tops=s.ops / t[Variant.FUSED_OCG] / 1e12,
@@ -151,7 +186,7 @@ def cmd_layers(args):
                            frac_of_hbm_peak=nbytes / (rot["unchecked_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS)
                 row[tag]["rotating_buffers"] = rot
         rows.append(row)
-    print(json.dumps(dict(config=args.config, note="checked = FC + batch-checksum IC, FusedOCG incl. the ICG kernel; fc_only / ic_only = one of the two alone (FusedOCG; ic_only incl. the ICG kernel); fic_fused = the FIC scheme of Sec. 3.3, fused option; GB/s = algorithmic minimum bytes / time",
+    print(json.dumps(dict(config=args.config, note="checked = FC + batch-checksum IC, FusedOCG incl. the ICG kernel; fc_only / ic_only = one of the two alone (FusedOCG; ic_only incl. the ICG kernel); fic_fused = the FIC scheme of Sec. 3.3, fused option; ic2_fused = IC option 2 of Sec. 3.2 (K values), fused option; GB/s = algorithmic minimum bytes / time",
                           layers=rows)))
 
 
@@ -347,7 +382,10 @@ def cmd_ksweep(args):
     for K in range(8, args.kmax + 1, 8):
         s = ConvShape(args.batch, 112, 112, 64, K, 3, 3, 1, 1, 1, 1, "3x3_c64_112_k%d" % K)
         t, tile = {}, {}
-        for name, v in (("unchecked", Variant.NONE), ("fc_only", Variant.FUSED_OCG | abed.ONLY_FC), ("fc_ic", Variant.FUSED_OCG)):
+        runs = [("unchecked", Variant.NONE), ("fc_only", Variant.FUSED_OCG | abed.ONLY_FC), ("fc_ic", Variant.FUSED_OCG)]
+        if K % 16 and K % 16 + 2 <= 16:      # room for the two checksum filters in the last block of 16
+            runs.append(("fc_only_packed", Variant.FUSED_OCG | abed.ONLY_FC | abed.PACKED_FC))
+        for name, v in runs:
             L = Int8Layer(s, 9000 + K, v)
             L.run()
             t[name] = _graph_time(lambda: L.run(), stream, reps=5, replays=4)
@@ -359,6 +397,8 @@ def cmd_ksweep(args):
                          fc_only_overhead_pct=100.0 * (t["fc_only"] / t["unchecked"] - 1.0),
                          fc_ic_overhead_pct=100.0 * (t["fc_ic"] / t["unchecked"] - 1.0),
                          unchecked_tops=s.ops / t["unchecked"] / 1e12, tile_unchecked=tile["unchecked"], tile_fc_only=tile["fc_only"]))
+        if "fc_only_packed" in t:
+            rows[-1].update(fc_only_packed_us=t["fc_only_packed"] * 1e6, fc_only_packed_overhead_pct=100.0 * (t["fc_only_packed"] / t["unchecked"] - 1.0))
         print("K", K, "done", file=sys.stderr, flush=True)
     print(json.dumps(dict(layer="3x3 C=64 112x112 s1 p1", batch=args.batch, rows=rows)))
 
