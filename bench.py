@@ -61,20 +61,21 @@ def main():
 
     def setup(s, idx, variant, int8_out=False):
         L = Layer()
-        L.s, L.variant = s, Variant(variant)
+        L.s, L.variant = s, int(variant)                  # may carry abed.ONLY_FC / abed.ONLY_IC
         L.desc = abed.desc_from_shape(s)
         L.lay = abed.get_layout(L.desc, 0, L.variant)
         x, w = int8_tensors(s, seed_for(2, idx))
         L.x = torch.from_numpy(x).to(dev)
         L.w = torch.from_numpy(w).to(dev)
         L.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int32, device=dev)
-        L.y2 = torch.empty_like(L.y) if L.variant == Variant.DUPLICATE else None
+        L.y2 = torch.empty_like(L.y) if L.variant == int(Variant.DUPLICATE) else None
         L.flags = torch.zeros((max(1, L.lay.n_flag_words),), dtype=torch.int32, device=dev)
         L.ws = torch.zeros((max(256, L.lay.workspace_bytes),), dtype=torch.uint8, device=dev)
         abed.workspace_init(L.ws)
         L.wchk = torch.empty((L.lay.d_f, s.R, s.S, s.C), dtype=torch.int8, device=dev)
         L.xchk = torch.empty((L.lay.d_i, s.H, s.W, s.C), dtype=torch.int8, device=dev)
-        abed.filter_prepare_int8(L.desc, L.w, L.wchk)      # offline step, not timed (Sec. 3.4: filter checksums are made offline)
+        if L.lay.d_f:
+            abed.filter_prepare_int8(L.desc, L.w, L.wchk)  # offline step, not timed (Sec. 3.4: filter checksums are made offline)
         return L
 
     def setup_fic(s, idx, variant):
@@ -186,6 +187,14 @@ def main():
         for L in Ls:
             r = L.result.cpu().numpy()
             assert int(L.flag.item()) == 0 and r[0] == r[1], "FIC mismatch on a fault-free run"
+    # each of the two checksum schemes of the headline path alone (Table 1 of Sec. 3.4), FusedOCG
+    t_single = {}
+    for name, bit in (("fc_only", abed.ONLY_FC), ("ic_only", abed.ONLY_IC)):
+        Ls = [setup(s, i, int(Variant.FUSED_OCG) | bit) for i, s in enumerate(layers)]
+        t_single[name] = time_steps(lambda: [run_layer(L) for L in Ls], max(20, args.steps // 2 // 10 * 10), max(10, args.warmup // 2))
+        for L in Ls:
+            assert int(L.flags.abs().max().item()) == 0, "error flag set on a fault-free run"
+        del Ls
     t_checked_eager = time_eager(step_of(Variant.FUSED_OCG), max(20, args.steps // 4), 5)
     t_dup = t_var[Variant.DUPLICATE]
 
@@ -233,6 +242,11 @@ def main():
                         fused_overhead_pct=100.0 * (t_fic[Variant.FUSED_OCG] / t_unchecked - 1.0),
                         unfused_tops=total_ops / t_fic[Variant.UNFUSED] / 1e12,
                         unfused_overhead_pct=100.0 * (t_fic[Variant.UNFUSED] / t_unchecked - 1.0)),
+               single_scheme=dict(note="the headline path carries FC (Sec. 3.1) and the batch-checksum IC (Sec. 3.2 option 1) together; here each alone, FusedOCG",
+                                  fc_only_tops=total_ops / t_single["fc_only"] / 1e12,
+                                  fc_only_overhead_pct=100.0 * (t_single["fc_only"] / t_unchecked - 1.0),
+                                  ic_only_tops=total_ops / t_single["ic_only"] / 1e12,
+                                  ic_only_overhead_pct=100.0 * (t_single["ic_only"] / t_unchecked - 1.0)),
                per_layer=per_layer, roofline=roofline)
 
     if not args.no_cpu_baseline:

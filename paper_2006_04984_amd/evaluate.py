@@ -138,6 +138,9 @@ class Ic2Layer:
 def cmd_layers(args):
     from synth import CONFIG2, CONFIG3, seed_for
     layers = {2: CONFIG2, 3: CONFIG3}[args.config]
+    if args.batch:        # the same layers at another batch size (the asymptote of a configuration's small layers)
+        import dataclasses
+        layers = [dataclasses.replace(s, N=args.batch) for s in layers]
     stream = torch.cuda.Stream()
     rows = []
     for i, s in enumerate(layers):
@@ -186,7 +189,7 @@ def cmd_layers(args):
                            frac_of_hbm_peak=nbytes / (rot["unchecked_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS)
                 row[tag]["rotating_buffers"] = rot
         rows.append(row)
-    print(json.dumps(dict(config=args.config, note="checked = FC + batch-checksum IC, FusedOCG incl. the ICG kernel; fc_only / ic_only = one of the two alone (FusedOCG; ic_only incl. the ICG kernel); fic_fused = the FIC scheme of Sec. 3.3, fused option; ic2_fused = IC option 2 of Sec. 3.2 (K values), fused option; GB/s = algorithmic minimum bytes / time",
+    print(json.dumps(dict(config=args.config, batch=layers[0].N, note="checked = FC + batch-checksum IC, FusedOCG incl. the ICG kernel; fc_only / ic_only = one of the two alone (FusedOCG; ic_only incl. the ICG kernel); fic_fused = the FIC scheme of Sec. 3.3, fused option; ic2_fused = IC option 2 of Sec. 3.2 (K values), fused option; GB/s = algorithmic minimum bytes / time",
                           layers=rows)))
 
 
@@ -406,7 +409,7 @@ def cmd_ksweep(args):
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
-    a = sub.add_parser("layers"); a.add_argument("--config", type=int, default=3, choices=[2, 3])
+    a = sub.add_parser("layers"); a.add_argument("--config", type=int, default=3, choices=[2, 3]); a.add_argument("--batch", type=int, default=0)
     a = sub.add_parser("detect"); a.add_argument("--trials", type=int, default=1000); a.add_argument("--clean", type=int, default=100); a.add_argument("--seed", type=int, default=1)
     a = sub.add_parser("fp16"); a.add_argument("--trials", type=int, default=1000); a.add_argument("--seed", type=int, default=1)
     a = sub.add_parser("resnet50"); a.add_argument("--batch", type=int, default=128)
