@@ -689,21 +689,24 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             for (int kb = 0; kb < WK; ++kb) {
                 const int fb = kt * WK + kb;
                 if (fb < p.kblk) {
-                    if (p.packed_df && fb == p.kblk - 1) {
-                        // the digit filters share this block with the last real filters
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const int k = fb * 16 + lg * 4 + v;
-                            if (k < p.K) r += (unsigned)acc[i][kb][v];
-                            else if (k < p.K + p.packed_df) r -= (unsigned)acc[i][kb][v] << (8 * (k - p.K));
-                        }
-                    } else {
-                        r += (unsigned)acc[i][kb][0] + (unsigned)acc[i][kb][1] + (unsigned)acc[i][kb][2] + (unsigned)acc[i][kb][3];
-                    }
+                    r += (unsigned)acc[i][kb][0] + (unsigned)acc[i][kb][1] + (unsigned)acc[i][kb][2] + (unsigned)acc[i][kb][3];
                 } else if (fb == p.kblk) {
                     if (lg == 0)
                         r -= (unsigned)acc[i][kb][0] + ((unsigned)acc[i][kb][1] << 8) + ((unsigned)acc[i][kb][2] << 16) + ((unsigned)acc[i][kb][3] << 24);
                 }
+            }
+            if (p.packed_df) {
+                // the digit filters share the last real block: its columns K..K+d_f-1 were added above as
+                // if they were real filters; take them out again and subtract them with their shifts
+#pragma unroll
+                for (int kb = 0; kb < WK; ++kb)
+                    if (kt * WK + kb == p.kblk - 1)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int k = (p.kblk - 1) * 16 + lg * 4 + v;
+                            if (k >= p.K && k < p.K + p.packed_df)
+                                r -= (unsigned)acc[i][kb][v] + ((unsigned)acc[i][kb][v] << (8 * (k - p.K)));
+                        }
             }
             r += (unsigned)__shfl_xor((int)r, 16, 64);
             r += (unsigned)__shfl_xor((int)r, 32, 64);
@@ -718,10 +721,8 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
 
     // flag bits of a non-zero IC residual vector: a real filter's column is an IC mismatch, a digit
     // filter's column a disagreement of the checksums with each other
-    auto ic_bits = [&](const i32x4 c, int fb, int g) -> uint32_t {
-        if ((c[0] | c[1] | c[2] | c[3]) == 0) return 0u;
-        if (fb >= p.kblk) return 4u;
-        if (!p.packed_df || fb != p.kblk - 1) return 2u;
+    // (only called for a non-zero vector of the block that real and digit filters share)
+    auto ic_bits_shared = [&](const i32x4 c, int fb, int g) -> uint32_t {
         uint32_t b = 0;
 #pragma unroll
         for (int v = 0; v < 4; ++v)
@@ -772,7 +773,8 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             const long long part = ((((long long)pg * p.grid_n + kt) * p.grid_b + nt) * WK + kb) * 256 + lane * 4;
             if (pass == 0) {
                 if (checking && ic_local) {
-                    my_flag |= ic_bits(c, fb, lg);
+                    if ((c[0] | c[1] | c[2] | c[3]) != 0)
+                        my_flag |= (p.packed_df && fb == p.kblk - 1) ? ic_bits_shared(c, fb, lg) : ((fb < p.kblk) ? 2u : 4u);
                 } else {
                     st_dev4(p.ws_ic + part, c);
                 }
@@ -941,7 +943,8 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 s += ld_dev4(rs_ic, off);
                 if (want_next) sn += ld_dev4(rs_nx, off);
             }
-            late |= ic_bits(s, fb, ln >> 4);
+            if ((s[0] | s[1] | s[2] | s[3]) != 0)
+                late |= (p.packed_df && fb == p.kblk - 1) ? ic_bits_shared(s, fb, ln >> 4) : ((fb < p.kblk) ? 2u : 4u);
             if (want_next && fb < p.kblk) {
                 const int px = pg * 16 + (ln & 15), k = fb * 16 + (ln >> 4) * 4;
                 if (px < PQ) {
