@@ -3,7 +3,7 @@
   rocprofv3 --kernel-trace --stats ... -- python3 -m paper_2006_04984_amd.profile_run --config 2 --layer 3 --variant 4
   rocprofv3 --pmc FETCH_SIZE ...      -- python3 -m paper_2006_04984_amd.profile_run ... --copy-mb 256
 
-Launches the chosen int8 layer `--reps` times through abed_conv_int8 (or abed_fic_conv_int8 with --scheme fic) (eager launches, so that every
+Launches the chosen int8 layer `--reps` times through abed_conv_int8 (or the entry point of another scheme, --scheme) (eager launches, so that every
 dispatch is seen by the profiler) and, with --copy-mb, one device-to-device copy of that many MiB,
 whose known size calibrates the FETCH_SIZE / WRITE_SIZE counters.
 """
@@ -23,16 +23,26 @@ def main():
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--int8-out", action="store_true")
     ap.add_argument("--copy-mb", type=int, default=0)
-    ap.add_argument("--scheme", default="fcic", choices=["fcic", "fic"],
-                    help="fcic: filter + batch checksums (abed_conv_int8); fic: the scalar scheme (abed_fic_conv_int8)")
+    ap.add_argument("--scheme", default="fcic", choices=["fcic", "fc", "ic", "fic", "ic2"],
+                    help="fcic: filter + batch checksums (abed_conv_int8); fc / ic: one of the two alone; "
+                         "fic: the scalar scheme (abed_fic_conv_int8); ic2: IC option 2, K values (abed_ic2_conv_int8)")
+    ap.add_argument("--batch", type=int, default=0, help="override the configuration's batch size")
     args = ap.parse_args()
     from synth import CONFIG2, CONFIG3, seed_for
     s = {2: CONFIG2, 3: CONFIG3}[args.config][args.layer]
+    if args.batch:
+        import dataclasses
+        s = dataclasses.replace(s, N=args.batch)
     if args.scheme == "fic":
         from .evaluate import FicLayer
         L = FicLayer(s, seed_for(args.config, args.layer), Variant(args.variant), epilogue=args.int8_out)
+    elif args.scheme == "ic2":
+        from .evaluate import Ic2Layer
+        L = Ic2Layer(s, seed_for(args.config, args.layer), Variant(args.variant), epilogue=args.int8_out)
     else:
-        L = Int8Layer(s, seed_for(args.config, args.layer), Variant(args.variant), epilogue=args.int8_out)
+        from . import binding as abed
+        only = {"fcic": 0, "fc": abed.ONLY_FC, "ic": abed.ONLY_IC}[args.scheme] if args.variant in (1, 2, 3, 4, 5) else 0
+        L = Int8Layer(s, seed_for(args.config, args.layer), args.variant | only, epilogue=args.int8_out)
     for _ in range(args.reps):
         L.run()
     torch.cuda.synchronize()
@@ -46,6 +56,8 @@ def main():
         torch.cuda.synchronize()
     if args.scheme == "fic":
         print("profiled", s.name, "FIC variant", args.variant, "flag", int(L.flag.item()))
+    elif args.scheme == "ic2":
+        print("profiled", s.name, "IC option 2 variant", args.variant, "flags", int(L.flags.abs().max().item()))
     else:
         print("profiled", s.name, "variant", args.variant, "grid", L.lay.grid_m, L.lay.grid_b, L.lay.grid_n,
               "flags", int(L.flags.abs().max().item()))
