@@ -730,12 +730,6 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         return b;
     };
 
-    int nx[WK][4];   // batch sums of the int8 outputs (variant 5)
-#pragma unroll
-    for (int kb = 0; kb < WK; ++kb)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) nx[kb][v] = 0;
-
     // IC residual of every (pixel, filter) of the tile (Sec. 3.2 option 1), pass 0: sum over this
     // wave's entries in registers, then over the 4 waves through LDS.  Pass 1 does the same for the
     // int8 outputs (the next layer's batch checksum, Sec. 4.3).
@@ -756,7 +750,21 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                     }
                 }
             } else {
-                c = i32x4{nx[kb][0], nx[kb][1], nx[kb][2], nx[kb][3]};
+                // batch sum of the int8 outputs: requantised again here rather than kept from the store
+                // loop (16 more live registers there cost more than these few operations)
+                const int k = (kt * WK + kb) * 16 + lg * 4;
+                float sc[4], bi[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    sc[v] = (k + v < p.K) ? p.scale[k + v] : 0.f;
+                    bi[v] = (k + v < p.K) ? p.bias[k + v] : 0.f;
+                }
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+                    if (pvalid && nt * MB + wave * WM + i < p.N)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (k + v < p.K) c[v] += requant(acc[i][kb][v], sc[v], bi[v], p.relu);
             }
             *reinterpret_cast<i32x4 *>(e_ic + ((wave * WK + kb) * 64 + lane) * 4) = c;
         }
@@ -857,46 +865,82 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             }
         }
     }
+    // int8 output (the epilog of Sec. 4.3).  A lane holds 4 bytes per (entry, block), far too little for a
+    // store: with whole filter blocks the wave lays its requantised bytes out in LDS as
+    // [entry][pixel][filter of the tile], 4 entries at a time, and writes them back 16 bytes per lane,
+    // 16 * WK contiguous bytes per pixel.  Otherwise the 4 bytes are stored directly, guarded per filter.
+    if (p.out_int8) {
+        const bool staged = (p.K & 15) == 0;
+        __syncthreads();                         // a residual pass of another wave may still be reading this memory
+        int8_t *stage = lds + wave * (WK * 1024);
+        constexpr int ROWB = WK * 16;            // bytes of one (entry, pixel) row of the tile
 #pragma unroll
-    for (int kb = 0; kb < WK; ++kb) {
-        if (whole_blocks) break;
-        const int fb = kt * WK + kb;
-        const int k = fb * 16 + lg * 4;                       // first of this lane's 4 filters
-        if (fb < p.kblk) {
-            float sc[4], bi[4];
-            if (p.out_int8) {
+        for (int i0 = 0; i0 < WM; i0 += 4) {
+#pragma unroll
+            for (int kb = 0; kb < WK; ++kb) {
+                const int fb = kt * WK + kb;
+                const int k = fb * 16 + lg * 4;
+                float sc[4], bi[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     sc[v] = (k + v < p.K) ? p.scale[k + v] : 0.f;
                     bi[v] = (k + v < p.K) ? p.bias[k + v] : 0.f;
                 }
+#pragma unroll
+                for (int il = 0; il < 4; ++il) {
+                    if (i0 + il >= WM) continue;
+                    const int i = i0 + il < WM ? i0 + il : 0;
+                    const int e = nt * MB + wave * WM + i;
+                    const bool real = pvalid && e < p.N;
+                    unsigned pk = 0;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        pk |= ((unsigned)requant(acc[i][kb][v], sc[v], bi[v], p.relu) & 0xffu) << (8 * v);
+                    if (staged) {
+                        *reinterpret_cast<unsigned *>(stage + (il * 16 + lj) * ROWB + kb * 16 + lg * 4) = pk;
+                    } else if (real) {
+                        int8_t *dst = reinterpret_cast<int8_t *>(p.y) + ((long long)e * PQ + pix) * p.K + k;
+                        if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<unsigned *>(dst) = pk;
+                        else
+                            for (int v = 0; v < 4; ++v)
+                                if (k + v < p.K) dst[v] = (int8_t)((pk >> (8 * v)) & 0xff);
+                    }
+                }
             }
+            if (staged) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int it = 0; it < WK; ++it) {
+                    const int q = it * 64 + lane;
+                    const int row = q / WK, c16 = q - row * WK;      // row = entry * 16 + pixel
+                    const int il = row >> 4, px = pg * 16 + (row & 15);
+                    const int e = nt * MB + wave * WM + i0 + il, fb = kt * WK + c16;
+                    const i32x4 v = *reinterpret_cast<const i32x4 *>(stage + row * ROWB + c16 * 16);
+                    if (i0 + il < WM && e < p.N && px < PQ && fb < p.kblk)
+                        *reinterpret_cast<i32x4 *>(reinterpret_cast<int8_t *>(p.y) + ((long long)e * PQ + px) * p.K + fb * 16) = v;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+    }
+#pragma unroll
+    for (int kb = 0; kb < WK; ++kb) {
+        if (whole_blocks || p.out_int8) break;
+        const int fb = kt * WK + kb;
+        const int k = fb * 16 + lg * 4;                       // first of this lane's 4 filters
+        if (fb < p.kblk) {
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
                 const int e = nt * MB + wave * WM + i;
                 if (!pvalid) continue;
                 if (e < p.N) {
-                    const long long o = ((long long)e * PQ + pix) * p.K + k;
-                    if (p.out_int8) {
-                        unsigned pk = 0;
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            const int q8 = requant(acc[i][kb][v], sc[v], bi[v], p.relu);
-                            pk |= ((unsigned)q8 & 0xffu) << (8 * v);
-                            if (k + v < p.K) nx[kb][v] += q8;
-                        }
-                        int8_t *dst = reinterpret_cast<int8_t *>(p.y) + o;
-                        if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<unsigned *>(dst) = pk;
-                        else
-                            for (int v = 0; v < 4; ++v)
-                                if (k + v < p.K) dst[v] = (int8_t)((pk >> (8 * v)) & 0xff);
-                    } else {
-                        int32_t *dst = reinterpret_cast<int32_t *>(p.y) + o;
-                        if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<i32x4 *>(dst) = acc[i][kb];
-                        else
-                            for (int v = 0; v < 4; ++v)
-                                if (k + v < p.K) dst[v] = acc[i][kb][v];
-                    }
+                    int32_t *dst = reinterpret_cast<int32_t *>(p.y) + ((long long)e * PQ + pix) * p.K + k;
+                    if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<i32x4 *>(dst) = acc[i][kb];
+                    else
+                        for (int v = 0; v < 4; ++v)
+                            if (k + v < p.K) dst[v] = acc[i][kb][v];
                 } else if (p.mode == MODE_WRITE && e < p.n_entries) {
                     int32_t *dst = p.ws_yi + ((long long)(e - p.N) * PQ + pix) * p.K + k;
                     for (int v = 0; v < 4; ++v)
