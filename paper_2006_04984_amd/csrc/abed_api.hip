@@ -84,23 +84,26 @@ void choose_tile(Plan &pl)
         const int pad4 = (pl.n_fblk + 3) / 4 * 4, pad5 = (pl.n_fblk + 4) / 5 * 5;
         wk = (pad5 + 2 <= pad4 || pl.n_fblk == 5) ? 5 : 4;   // 5: e.g. 64 filters + the digit block in one tile, FC stays local
     }
+    // tiles 8 blocks wide and 8 entries deep read the activations half as often; they pay when the filter
+    // blocks fill them exactly and the grid stays large (measured: 64->256 1x1 at 56x56, 256->256 3x3 at
+    // 14x14 with 128 images), and lose on small grids
+    bool wide = false;
+    if (pl.n_fblk % 8 == 0 && (long long)((pl.PQ + 15) / 16) * ((pl.n_entries + 7) / 8) * (pl.n_fblk / 8) >= 384) { wk = 8; wide = true; }
     const int grid_m = (pl.PQ + 15) / 16, grid_n = (pl.n_fblk + wk - 1) / wk;
     auto tiles = [&](int wm) { return (long long)grid_m * ((pl.n_entries + 4 * wm - 1) / (4 * wm)) * grid_n; };
     auto waste = [&](int wm) { const int mb = 4 * wm; return (pl.n_entries + mb - 1) / mb * mb - pl.n_entries; };
     static const int cand[] = {5, 3, 2};
     int wm = 0;
-    // the largest tile that leaves at least 1.5 workgroups per CU and pads the batch by at most a
-    // fifth (a smaller one that pads nothing is preferred); failing that, the largest that still gives
+    // among the tiles that leave at least 1.5 workgroups per CU and pad the batch by at most a fifth,
+    // the one that pads least (the larger one on a tie); failing that, the largest that still gives
     // most CUs a workgroup; failing that, the smallest
     for (int c : cand)
-        if (!wm && tiles(c) >= 384 && 5 * waste(c) <= pl.n_entries) wm = c;
-    if (wm)
-        for (int c : cand)
-            if (c < wm && waste(c) == 0 && waste(wm) != 0) { wm = c; break; }
+        if (tiles(c) >= 384 && 5 * waste(c) <= pl.n_entries && (!wm || waste(c) < waste(wm))) wm = c;
     if (!wm)
         for (int c : cand)
             if (!wm && tiles(c) >= 160 && 5 * waste(c) <= pl.n_entries) wm = c;
     if (!wm) wm = 1;
+    if (wide) wm = 2;
     if (pl.n_entries <= 4) wm = 1;
     wm = env_int("ABED_TILE_WM", wm);
     wk = env_int("ABED_TILE_WK", wk);

@@ -839,10 +839,14 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         }
     };
 
-    // (3) residuals first (they are small), then the output stores; variant 5 needs the
-    // requantised outputs for its second pass, so there the order is the other way round
-    if (reduce && !want_next) {
+    // (3) residuals first (they are small), then the output stores, behind which the arrival counter's
+    // round trip hides; variant 5 adds the pass over the requantised outputs
+    if (reduce) {
         if (p.d_i) ic_pass(0);
+        if (want_next) {
+            __syncthreads();
+            ic_pass(1);
+        }
         if (checking) arrive();
         else if (tid == 0) p.flags[tile] = 0;    // partial-reduction variant: the finish kernel ORs its findings in
     }
@@ -964,12 +968,6 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         ic_pass(2);
     }
     if (!reduce) return;
-    if (want_next) {
-        ic_pass(0);
-        __syncthreads();
-        ic_pass(1);
-        arrive();
-    }
     if (!exchange) return;   // MODE_PARTIAL: the finish kernel compares; local sums: done
 
     // (5) residuals that span several tiles are summed by the workgroup that arrives last and
@@ -1010,12 +1008,16 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             if (want_next && fb < p.kblk) {
                 const int px = pg * 16 + (ln & 15), k = fb * 16 + (ln >> 4) * 4;
                 if (px < PQ) {
-                    for (int v = 0; v < 4; ++v) {
-                        int t = sn[v];
-                        for (int d = 0; d < p.d_i; ++d) {
-                            const int dg = next_digit(t);
-                            if (k + v < p.K) p.xchk_next[((long long)d * PQ + px) * p.K + k + v] = (int8_t)dg;
-                        }
+                    int rest[4] = {sn[0], sn[1], sn[2], sn[3]};
+                    for (int d = 0; d < p.d_i; ++d) {
+                        unsigned pk = 0;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) pk |= ((unsigned)next_digit(rest[v]) & 0xffu) << (8 * v);
+                        int8_t *dst = p.xchk_next + ((long long)d * PQ + px) * p.K + k;
+                        if (k + 4 <= p.K && (p.K & 3) == 0) *reinterpret_cast<unsigned *>(dst) = pk;
+                        else
+                            for (int v = 0; v < 4; ++v)
+                                if (k + v < p.K) dst[v] = (int8_t)((pk >> (8 * v)) & 0xff);
                     }
                 }
             }
