@@ -339,7 +339,7 @@ abed_status_t abed_fic_filter_prepare_int8(const abed_conv_desc_t *desc, const i
     abed_status_t s = make_plan(desc, ABED_INT8, ABED_NONE, false, pl);
     if (s != ABED_OK) return s;
     if (!w || !wsum) return ABED_EINVAL;
-    fic_filter_checksum_i8_kernel<<<dim3((pl.crs + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(w, wsum, desc->K, pl.crs);
+    fic_filter_checksum_i8_kernel<<<dim3((pl.crs + 63) / 64), dim3(1024), 0, (hipStream_t)stream>>>(w, wsum, desc->K, pl.crs);
     LAUNCH_CHECK("fic_filter_checksum_i8_kernel");
     return ABED_OK;
 }
@@ -588,7 +588,7 @@ abed_status_t abed_filter_prepare_int8(const abed_conv_desc_t *desc, const int8_
     abed_status_t s = make_plan(desc, ABED_INT8, ABED_NONE, false, pl);
     if (s != ABED_OK) return s;
     if (!w || !wchk) return ABED_EINVAL;
-    filter_checksum_i8_kernel<<<dim3((pl.crs + 255) / 256), dim3(256), 0, (hipStream_t)stream>>>(w, wchk, desc->K, pl.crs, pl.d_f);
+    filter_checksum_i8_kernel<<<dim3((pl.crs + 63) / 64), dim3(1024), 0, (hipStream_t)stream>>>(w, wchk, desc->K, pl.crs, pl.d_f);
     LAUNCH_CHECK("filter_checksum_i8_kernel");
     return ABED_OK;
 }

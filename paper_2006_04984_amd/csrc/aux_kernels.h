@@ -19,14 +19,35 @@ __device__ __forceinline__ int take_digit(int &s)
     return d;
 }
 
-// wsum[e] = sum_k w[k][e]; digits to wchk[d][e].  One thread per element (offline step).
-__global__ void filter_checksum_i8_kernel(const int8_t *w, int8_t *wchk, int K, int crs, int d_f)
+// wsum[e] = sum_k w[k][e] for the 64 elements of this workgroup: 16 slices of 64 threads share the
+// filters (slice j takes k = j, j + 16, ...), then slice 0 adds the 16 partial sums.  1024 threads.
+__device__ __forceinline__ int filter_sum_64(const int8_t *w, int K, int crs, int (*red)[64])
 {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= crs) return;
+    const int slice = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const int e = blockIdx.x * 64 + l;
     int s = 0;
-    for (int k = 0; k < K; ++k) s += w[(long long)k * crs + e];
-    for (int d = 0; d < d_f; ++d) wchk[(long long)d * crs + e] = (int8_t)take_digit(s);
+    if (e < crs) {
+#pragma unroll 4
+        for (int k = slice; k < K; k += 16) s += w[(long long)k * crs + e];
+    }
+    red[slice][l] = s;
+    __syncthreads();
+    int t = 0;
+    if (slice == 0) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) t += red[q][l];
+    }
+    return t;
+}
+
+// Offline step: the filter checksum split into digits, wchk[d][e].  Grid ceil(crs / 64) x 1024 threads.
+__global__ __launch_bounds__(1024) void filter_checksum_i8_kernel(const int8_t *w, int8_t *wchk, int K, int crs, int d_f)
+{
+    __shared__ int red[16][64];
+    int s = filter_sum_64(w, K, crs, red);
+    const int e = blockIdx.x * 64 + (threadIdx.x & 63);
+    if (threadIdx.x < 64 && e < crs)
+        for (int d = 0; d < d_f; ++d) wchk[(long long)d * crs + e] = (int8_t)take_digit(s);
 }
 
 // xsum[e] = sum_n x[n][e] for 16 consecutive elements per group of 8 lanes (each lane sums an

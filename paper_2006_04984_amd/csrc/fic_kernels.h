@@ -7,13 +7,25 @@
 
 namespace abed {
 
-__global__ void fic_filter_checksum_i8_kernel(const int8_t *w, int32_t *wsum, int K, int crs)
+// Offline step: the filter checksum as int32.  Grid ceil(crs / 64) x 1024 threads (16 slices share the filters).
+__global__ __launch_bounds__(1024) void fic_filter_checksum_i8_kernel(const int8_t *w, int32_t *wsum, int K, int crs)
 {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= crs) return;
+    __shared__ int red[16][64];
+    const int slice = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const int e = blockIdx.x * 64 + l;
     int s = 0;
-    for (int k = 0; k < K; ++k) s += w[(long long)k * crs + e];
-    wsum[e] = s;
+    if (e < crs) {
+#pragma unroll 4
+        for (int k = slice; k < K; k += 16) s += w[(long long)k * crs + e];
+    }
+    red[slice][l] = s;
+    __syncthreads();
+    if (slice == 0 && e < crs) {
+        int t = 0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) t += red[q][l];
+        wsum[e] = t;
+    }
 }
 
 template <int SMAX>
