@@ -195,6 +195,17 @@ def main():
         for L in Ls:
             assert int(L.flags.abs().max().item()) == 0, "error flag set on a fault-free run"
         del Ls
+    # FIC fused with the comparisons of the four layers deferred to one launch at the end of the step
+    Ls = fic_sets[Variant.FUSED_OCG]
+    res_all = torch.zeros((len(Ls), 2), dtype=torch.int64, device=dev)
+    flag_all = torch.zeros((len(Ls),), dtype=torch.int32, device=dev)
+
+    def fic_deferred_step():
+        for L in Ls:
+            abed.fic_conv_int8(L.desc, L.x, L.w, L.wsum, L.xrows, True, L.y, L.variant, None, None, workspace=L.ws)
+        abed.fic_verify([L.desc for L in Ls], [L.variant for L in Ls], [L.ws for L in Ls], res_all, flag_all)
+    t_fic_deferred = time_steps(fic_deferred_step, max(20, args.steps // 2 // 10 * 10), max(10, args.warmup // 2))
+    assert int(flag_all.abs().max().item()) == 0 and bool((res_all[:, 0] == res_all[:, 1]).all().item()), "FIC mismatch on a fault-free run"
     t_checked_eager = time_eager(step_of(Variant.FUSED_OCG), max(20, args.steps // 4), 5)
     t_dup = t_var[Variant.DUPLICATE]
 
@@ -237,9 +248,11 @@ def main():
                speedup_vs_duplicate=t_dup / t_checked,
                variant_overhead_pct={v.name: 100.0 * (t / t_unchecked - 1.0) for v, t in t_var.items() if v != Variant.NONE},
                fic=dict(note="FIC scheme of Sec. 3.3 (input patch checksum . filter checksum == sum of ConvOut, int64): "
-                             "fused option = the input checksum workgroups ride in the convolution's launch, then a one-workgroup kernel adds up the partial sums and compares",
+                             "fused option = the input checksum workgroups ride in the convolution's launch, then a one-workgroup kernel adds up the partial sums and compares; fused_deferred = one such launch for the four layers at the end of the step",
                         fused_tops=total_ops / t_fic[Variant.FUSED_OCG] / 1e12,
                         fused_overhead_pct=100.0 * (t_fic[Variant.FUSED_OCG] / t_unchecked - 1.0),
+                        fused_deferred_tops=total_ops / t_fic_deferred / 1e12,
+                        fused_deferred_overhead_pct=100.0 * (t_fic_deferred / t_unchecked - 1.0),
                         unfused_tops=total_ops / t_fic[Variant.UNFUSED] / 1e12,
                         unfused_overhead_pct=100.0 * (t_fic[Variant.UNFUSED] / t_unchecked - 1.0)),
                single_scheme=dict(note="the headline path carries FC (Sec. 3.1) and the batch-checksum IC (Sec. 3.2 option 1) together; here each alone, FusedOCG",

@@ -253,6 +253,9 @@ abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, int32_t
  *   y, epilogue   as for abed_conv_int8.
  *   result        two int64 on the device: [0] = ocs, [1] = dot.
  *   flag          one word on the device: 1 if ocs != dot, else 0 (written on every call).
+ *                 result and flag may both be NULL: the call then leaves its partial sums in the workspace
+ *                 and makes no comparison; abed_fic_verify makes it later, for several layers in one launch
+ *                 (each layer needs a workspace of its own until then).
  *   xsum_in       ABED_FUSED_IOCG only, else NULL: int32 [H][W][C], the batch sum of this layer's input that
  *                 the previous layer's call produced as its xsum_next.  If non-NULL the input checksum is
  *                 made from it instead of a pass over x (compute_xrows is ignored), and the call leaves the
@@ -278,6 +281,14 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
 const char *abed_status_string(abed_status_t status);
 /* Text of the last HIP error seen by this thread's most recent failing call. */
 const char *abed_last_hip_error(void);
+
+/* The final sums and comparisons (last step of tasks 3 and 7 of Sec. 4.3; the paper leaves the comparison
+ * to the host) of n_layers convolutions that were run by abed_fic_conv_int8 with result == flag == NULL, in
+ * one launch per 32 layers.  descs, variants and workspaces are HOST arrays of n_layers entries (the
+ * descriptor, variant and workspace pointer each layer's call was given); results (device, 2 * n_layers
+ * int64: ocs, dot per layer) and flags (device, n_layers words) are written for every layer. */
+abed_status_t abed_fic_verify(int32_t n_layers, const abed_conv_desc_t *descs, const int32_t *variants,
+                              void *const *workspaces, int64_t *results, uint32_t *flags, void *stream);
 
 /* ------------------------------------------------------------------------------------------
  * IC option 2 (Sec. 3.2): the input fmaps are reduced to a checksum tensor of the size of one filter

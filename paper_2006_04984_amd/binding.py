@@ -59,7 +59,7 @@ class Ic2Layout(ctypes.Structure):
     _fields_ = [("workspace_bytes", ctypes.c_int64), ("xrows_bytes", ctypes.c_int64), ("xrows_parts", ctypes.c_int32), ("n_values", ctypes.c_int32)]
 
 
-EXPORTS = ["abed_ic2_get_layout", "abed_ic2_conv_int8", "abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
+EXPORTS = ["abed_fic_verify", "abed_ic2_get_layout", "abed_ic2_conv_int8", "abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
            "abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_fp16",
            "abed_input_checksum_int8", "abed_input_checksum_fp16", "abed_workspace_init",
            "abed_conv_int8", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error"]
@@ -99,6 +99,7 @@ def lib():
         L.abed_fic_input_checksum_int8.argtypes = [ctypes.POINTER(ConvDesc), i32, vp, vp, vp]
         L.abed_fic_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
                                          vp, vp, vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp]
+        L.abed_fic_verify.argtypes = [i32, ctypes.POINTER(ConvDesc), ctypes.POINTER(i32), ctypes.POINTER(vp), vp, vp, vp]
         L.abed_ic2_get_layout.argtypes = [ctypes.POINTER(ConvDesc), i32, ctypes.POINTER(Ic2Layout)]
         L.abed_ic2_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
                                          vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp]
@@ -233,3 +234,12 @@ def ic2_conv_int8(desc, x, w, xrows, compute_xrows, y, variant, result, flags, e
     _check(lib().abed_ic2_conv_int8(ctypes.byref(desc), _p(x), _p(w), _p(xrows), int(bool(compute_xrows)),
                                     _p(y), epi, int(variant), _p(result), _p(flags), _p(workspace), nbytes,
                                     inj, _stream(stream)))
+
+
+def fic_verify(descs, variants, workspaces, results, flags, stream=None):
+    """abed_fic_verify: the deferred comparisons of several layers run with result = flag = None."""
+    n = len(descs)
+    d = (ConvDesc * n)(*descs)
+    v = (ctypes.c_int32 * n)(*[int(x) for x in variants])
+    w = (ctypes.c_void_p * n)(*[t.data_ptr() for t in workspaces])
+    _check(lib().abed_fic_verify(n, d, v, w, _p(results), _p(flags), _stream(stream)))

@@ -366,7 +366,9 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
     Plan pl;
     abed_status_t s = fic_plan(desc, variant, pl, int8_out);
     if (s != ABED_OK) return s;
-    if (!x || !w || !wsum || !xrows || !y || !result || !flag) return ABED_EINVAL;
+    if (!x || !w || !wsum || !xrows || !y) return ABED_EINVAL;
+    if ((result == nullptr) != (flag == nullptr)) return ABED_EINVAL;
+    const bool deferred = result == nullptr;          // the partial sums stay in the workspace for abed_fic_verify
     if (epi && (!epi->scale || !epi->bias)) return ABED_EINVAL;
     // handing the batch sum from layer to layer belongs to the input-and-output-fused option only,
     // and the sum handed on is that of the epilog's int8 output
@@ -407,6 +409,7 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
         if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
         if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, lead + grid, st)) return ABED_EUNSUPPORTED;
         LAUNCH_CHECK("conv_kernel (FIC, fused)");
+        if (deferred) return ABED_OK;
         FicVerifyParams vp;
         vp.dotpart = dotpart; vp.partial = partial; vp.result = (long long *)result; vp.flag = flag;
         vp.ndot = rows_blocks; vp.npartial = ntiles;
@@ -428,11 +431,46 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
         epilog_i8_kernel<<<dim3((unsigned)((npqk / 4 + 256) / 256)), dim3(256), 0, st>>>(convout, (int8_t *)y, epi->scale, epi->bias, epi->relu, npqk, desc->K);
         LAUNCH_CHECK("epilog_i8_kernel");
     }
+    if (deferred) return ABED_OK;
     FicVerifyParams vp;
     vp.dotpart = dotpart; vp.partial = partial; vp.result = (long long *)result; vp.flag = flag;
     vp.ndot = rows_blocks; vp.npartial = kFicSumBlocks;
     fic_verify_kernel<<<1, 1024, 0, st>>>(vp);
     LAUNCH_CHECK("fic_verify_kernel");
+    return ABED_OK;
+}
+
+abed_status_t abed_fic_verify(int32_t n_layers, const abed_conv_desc_t *descs, const int32_t *variants,
+                              void *const *workspaces, int64_t *results, uint32_t *flags, void *stream)
+{
+    if (n_layers < 0 || (n_layers > 0 && (!descs || !variants || !workspaces || !results || !flags))) return ABED_EINVAL;
+    // check everything before the first launch
+    for (int i = 0; i < n_layers; ++i) {
+        Plan pl;
+        abed_status_t s = fic_plan(&descs[i], variants[i], pl, false);
+        if (s != ABED_OK) return s;
+        if (!workspaces[i]) return ABED_EINVAL;
+    }
+    for (int base = 0; base < n_layers; base += kFicVerifyBatch) {
+        FicVerifyBatchParams bp;
+        const int n = n_layers - base < kFicVerifyBatch ? n_layers - base : kFicVerifyBatch;
+        for (int j = 0; j < n; ++j) {
+            const int i = base + j;
+            Plan pl;
+            fic_plan(&descs[i], variants[i], pl, false);
+            // the same carving as in abed_fic_conv_int8: 256 bytes kept free, partial output checksums, partial dot products
+            const int npartial = variants[i] == ABED_UNFUSED ? kFicSumBlocks : pl.grid_m * pl.grid_b * pl.grid_n;
+            FicVerifyParams &vp = bp.layer[j];
+            vp.partial = (const long long *)((const char *)workspaces[i] + 256);
+            vp.dotpart = (const long long *)((const char *)workspaces[i] + 256 + align256(8LL * npartial));
+            vp.ndot = fic_rows_blocks(&descs[i], variants[i]);
+            vp.npartial = npartial;
+            vp.result = (long long *)results + 2 * i;
+            vp.flag = flags + i;
+        }
+        fic_verify_batch_kernel<<<dim3(n), dim3(1024), 0, (hipStream_t)stream>>>(bp);
+        LAUNCH_CHECK("fic_verify_batch_kernel");
+    }
     return ABED_OK;
 }
 

@@ -67,8 +67,8 @@ struct FicVerifyParams {
 };
 
 // Tasks 3 and 7 of Sec. 4.3, last step: add up the partial dot products and the partial output
-// checksums and compare the two 64-bit values.  One workgroup.
-__global__ __launch_bounds__(1024) void fic_verify_kernel(const FicVerifyParams p)
+// checksums and compare the two 64-bit values.  One workgroup of 1024 threads per layer.
+__device__ __forceinline__ void fic_verify_body(const FicVerifyParams &p)
 {
     __shared__ long long part[2][16];
     long long dot = 0, ocs = 0;
@@ -85,5 +85,13 @@ __global__ __launch_bounds__(1024) void fic_verify_kernel(const FicVerifyParams 
         *p.flag = (o != d) ? 1u : 0u;
     }
 }
+
+__global__ __launch_bounds__(1024) void fic_verify_kernel(const FicVerifyParams p) { fic_verify_body(p); }
+
+// The same for several layers in one launch (the comparison deferred to the end of a group of
+// layers): workgroup b verifies layer b.
+constexpr int kFicVerifyBatch = 32;
+struct FicVerifyBatchParams { FicVerifyParams layer[kFicVerifyBatch]; };
+__global__ __launch_bounds__(1024) void fic_verify_batch_kernel(const FicVerifyBatchParams p) { fic_verify_body(p.layer[blockIdx.x]); }
 
 }  // namespace abed

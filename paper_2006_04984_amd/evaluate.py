@@ -343,6 +343,20 @@ def cmd_resnet50(args):
     t = _graph_time(fic_step, stream, reps=2, replays=5)
     result["fic_fused"] = dict(ms=t * 1e3, tops=total_ops / t / 1e12)
     result["fic_fused_overhead_pct"] = 100.0 * (result["fic_fused"]["ms"] / result["unchecked"]["ms"] - 1.0)
+    # the same with the comparisons deferred: every layer leaves its partial sums, two launches verify all 53
+    res_all = torch.zeros((len(objs), 2), dtype=torch.int64, device=DEV)
+    flag_all = torch.zeros((len(objs),), dtype=torch.int32, device=DEV)
+
+    def fic_deferred_step():
+        for L in objs:
+            abed.fic_conv_int8(L.desc, L.x, L.w, L.wsum, L.xrows, True, L.y, L.variant, None, None, epilogue=L.epi, workspace=L.ws)
+        abed.fic_verify([L.desc for L in objs], [L.variant for L in objs], [L.ws for L in objs], res_all, flag_all)
+    fic_deferred_step()
+    torch.cuda.synchronize()
+    assert int(flag_all.abs().max().item()) == 0 and bool((res_all[:, 0] == res_all[:, 1]).all().item())
+    t = _graph_time(fic_deferred_step, stream, reps=2, replays=5)
+    result["fic_fused_deferred"] = dict(ms=t * 1e3, tops=total_ops / t / 1e12)
+    result["fic_fused_deferred_overhead_pct"] = 100.0 * (result["fic_fused_deferred"]["ms"] / result["unchecked"]["ms"] - 1.0)
     del objs
     torch.cuda.empty_cache()
     # FIC with the next layer's input checksum generation fused in (Sec. 4.3): inside a bottleneck the

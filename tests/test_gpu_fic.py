@@ -196,3 +196,40 @@ def test_next_layer_checksum_is_handed_over(oracle, sa, sb):
     ref = oracle.abed_fic_int8(bad.cpu().numpy(), wb, sb, xpatch=rb["xpatch"])
     yb, ocs, dot, flag = gb.run(bad, xsum_in=xsum)
     assert np.array_equal(yb, ref["y"]) and (ocs, dot, flag) == (ref["ocs"], ref["dot"], int(ref["bad"])) and ref["bad"]
+
+
+def test_deferred_verification_of_several_layers(oracle):
+    """The comparisons of several layers made in one launch after all of them ran (the paper leaves the
+    comparison to the host, Sec. 4.3): per layer the two scalars and the flag, one layer with a flip."""
+    import paper_2006_04984_amd as abed
+    picks = [(SHAPES[1], 4, None), (SHAPES[2], 4, (1, 100, 20)), (SHAPES[5], 1, None), (SHAPES[3], 5, None)]
+    layers, refs = [], []
+    for s, variant, inject in picks:
+        x, w = int8_tensors(s, 7070 + len(layers))
+        g = GpuFic(s, variant)
+        g.prepare(w)
+        g.x = torch.from_numpy(x).to(DEV)
+        abed.fic_conv_int8(g.desc, g.x, g.w, g.wsum, g.xrows, True, g.y, variant, None, None, workspace=g.ws, inject=inject)
+        layers.append(g)
+        refs.append(oracle.abed_fic_int8(x, w, s, acc_flip=inject[1:] if inject else None))
+    results = torch.full((len(picks), 2), -1, dtype=torch.int64, device=DEV)
+    flags = torch.full((len(picks),), 99, dtype=torch.int32, device=DEV)
+    abed.fic_verify([g.desc for g in layers], [p[1] for p in picks], [g.ws for g in layers], results, flags)
+    torch.cuda.synchronize()
+    r, f = results.cpu().numpy(), flags.cpu().numpy()
+    for i, (g, ref) in enumerate(zip(layers, refs)):
+        assert np.array_equal(g.y.cpu().numpy(), ref["y"])
+        assert (int(r[i, 0]), int(r[i, 1]), int(f[i])) == (ref["ocs"], ref["dot"], int(ref["bad"]))
+    assert f.tolist() == [0, 1, 0, 0]
+
+
+def test_deferred_needs_both_null():
+    import paper_2006_04984_amd as abed
+    s = SHAPES[1]
+    g = GpuFic(s, 4)
+    x, w = int8_tensors(s, 1)
+    g.prepare(w)
+    g.x = torch.from_numpy(x).to(DEV)
+    with pytest.raises(abed.AbedError) as e:
+        abed.fic_conv_int8(g.desc, g.x, g.w, g.wsum, g.xrows, True, g.y, 4, g.result, None, workspace=g.ws)
+    assert e.value.status == 1
