@@ -10,7 +10,10 @@ BUILD = os.path.join(os.path.dirname(HERE), "_build")
 LIB = os.path.join(HERE, "libabed.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = (["-DABED_STAGES=" + os.environ["ABED_STAGES"]] if "ABED_STAGES" in os.environ else []) + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
+# ABED_STAGES=<n> and ABED_ENABLE_DBG=1 in the environment build experiment variants (pipeline depth; the
+# ABED_DBG run-time switch that cuts the kernel short for timing breakdowns, absent from normal builds)
+FLAGS = (["-DABED_STAGES=" + os.environ["ABED_STAGES"]] if "ABED_STAGES" in os.environ else []) + \
+        (["-DABED_ENABLE_DBG"] if os.environ.get("ABED_ENABLE_DBG") else []) + ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
 UNITS = [("abed_api.hip", [], "abed_api.o"),

@@ -205,7 +205,9 @@ void fill_params(ConvParams &cp, const abed_conv_desc_t *d, const Plan &pl)
     cp.packed_df = pl.packed ? pl.d_f : 0;
     cp.grid_m = pl.grid_m; cp.grid_b = pl.grid_b; cp.grid_n = pl.grid_n;
     cp.kt_slowest = env_int("ABED_KT_SLOWEST", (long long)d->K * pl.crs > (long long)d->N * d->H * d->W * d->C ? 1 : 0);
+#ifdef ABED_ENABLE_DBG
     cp.dbg = env_int("ABED_DBG", 0);
+#endif
 }
 
 void set_injection(ConvParams &cp, const abed_conv_desc_t *d, const Plan &pl, const abed_inject_t *inject)

@@ -89,7 +89,7 @@ struct ConvParams {
     // accumulator fault injection (tests): tile coordinates of the element
     int inj_on, inj_pg, inj_nt, inj_kt, inj_mb, inj_kb, inj_lane, inj_v;
     uint32_t inj_mask;
-    int dbg;
+    int dbg;          // timing experiments (builds with ABED_ENABLE_DBG only): bit 0 ends the kernel before its stores, bit 1 skips the main loop
     int out_fp32;      // fp16 path: 1 = fp32 output
     float rtol, atol;  // fp16 path: threshold of the checks
     // FIC scheme (Sec. 3.3).  fic_ocs: per-tile sums of all accumulators [ntiles], or null.  With
@@ -362,7 +362,12 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s) issue(s, ut);
     int stage = 0;
-    for (int step = 0; step < ((p.dbg & 2) ? 0 : nstages); ++step) {
+#ifdef ABED_ENABLE_DBG
+    const int nloop = (p.dbg & 2) ? 0 : nstages;
+#else
+    const int nloop = nstages;
+#endif
+    for (int step = 0; step < nloop; ++step) {
         ABED_WAIT_VMCNT((NST - 2) * L);          // this wave's loads of `step` have landed
         __builtin_amdgcn_s_barrier();            // everyone's have, and everyone is done with step-1
         {
@@ -468,7 +473,9 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 }
             }
         }
+#ifdef ABED_ENABLE_DBG
         if (p.dbg & 1) return;
+#endif
         const bool exchange = checking && !(fc_local && ic_local);
         const long long word = ((long long)pg * p.grid_b + nt) * p.grid_n + kt;
         if (aug) {
@@ -717,7 +724,9 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             }
         }
     }
+#ifdef ABED_ENABLE_DBG
     if (p.dbg & 1) return;
+#endif
 
     // flag bits of a non-zero IC residual vector: a real filter's column is an IC mismatch, a digit
     // filter's column a disagreement of the checksums with each other
