@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the checked convolution kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs scaled by a copy of known size (profiles/conv_int8_checked_config2.md); None where not measured.
 MEASURED_TRAFFIC_BYTES = {"3x3_c64_56": 16.7e6 + 38.3e6, "3x3_c128_28": 12.8e6 + 20.9e6,
-                          "3x3_c256_14": 12.7e6 + 9.9e6, "3x3_c512_7": 16.2e6 + 7.6e6}
+                          "3x3_c256_14": 12.7e6 + 9.9e6, "3x3_c512_7": 16.2e6 + 7.9e6}
 
 
 def main():
