@@ -29,6 +29,10 @@
  *     y[N][P][Q][K]; P = (H + 2 pad_h - R)/stride_h + 1, Q likewise.
  *     Cross-correlation, dilation 1, one group, zero padding.
  *   - Every call returns an abed_status_t; nothing is thrown.
+ *   - A workspace belongs to one call at a time: calls that may overlap on the device (different
+ *     streams) need workspaces of their own; calls on one stream may share one, unless a call says
+ *     that it leaves results in its workspace for a later call.  A status other than ABED_OK means
+ *     that nothing was enqueued, except for ABED_EHIP, which reports a failed launch.
  */
 #ifndef ABED_H
 #define ABED_H
