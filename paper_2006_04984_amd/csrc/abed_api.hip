@@ -569,13 +569,13 @@ abed_status_t abed_ic2_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
         return ABED_OK;
     }
     // unfused option: one kernel per task
+    if ((size_t)desc->K * 8 > 64 * 1024) return ABED_EUNSUPPORTED;   // the output sum kernel's LDS
     if (compute_xrows && (s = fic_input_rows(desc, pl, variant, x, nullptr, xrows, nullptr, false, st)) != ABED_OK) return s;
     int32_t *convout = int8_out ? (int32_t *)((char *)workspace + 256 + align256(4LL * pl.crs) + align256(8LL * kIc2SumBlocks * desc->K)) : (int32_t *)y;
     cp.y = convout;
     if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("conv_kernel (unchecked)");
     if (inject && inject->site == 2) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)convout, inject->index, 1u << inject->bit);
-    if ((size_t)desc->K * 8 > 64 * 1024) return ABED_EUNSUPPORTED;
     ic2_output_sums_kernel<<<dim3(kIc2SumBlocks), dim3(256), (size_t)desc->K * 8, st>>>(convout, (long long)desc->N * pl.PQ, desc->K, part);
     LAUNCH_CHECK("ic2_output_sums_kernel");
     if (int8_out) {
@@ -706,6 +706,8 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     const long long npqk = (long long)desc->N * pl.PQ * desc->K;
     const bool stored_flip = inject && inject->site == 2;
 
+    if ((variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE) && ((size_t)desc->N + desc->K + 2) * 4 > 64 * 1024)
+        return ABED_EUNSUPPORTED;                                     // the verify kernel keeps N + K sums in LDS
     if (checked && compute_xchk && pl.d_i) {
         s = abed_input_checksum_int8(desc, x, xchk, stream);
         if (s != ABED_OK) return s;
@@ -736,6 +738,7 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
     const int grid = (pl.grid_m * pl.grid_b * pl.grid_n + 7) / 8 * 8;   // whole rounds over the 8 XCDs
 
     if (variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE) {
+        const size_t shm = ((size_t)desc->N + desc->K + 2) * 4;      // the verify kernel's LDS (checked above)
         int32_t *convout = int8_out ? wsp(pl.off_convout) : (int32_t *)y;
         int32_t *yf = wsp(pl.off_yf), *yi = wsp(pl.off_yi), *yfi = wsp(pl.off_yfi);
         if (variant == ABED_UNFUSED) {
@@ -760,8 +763,6 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
         vp.y = convout; vp.yf = yf; vp.yi = yi; vp.yfi = yfi; vp.flags = flags;
         vp.N = desc->N; vp.PQ = pl.PQ; vp.K = desc->K; vp.d_f = pl.d_f; vp.d_i = pl.d_i;
         vp.tile_batch = pl.mb; vp.tile_n = 16 * pl.wk; vp.grid_b = pl.grid_b; vp.grid_n = pl.grid_n;
-        const size_t shm = ((size_t)desc->N + desc->K + 2) * 4;
-        if (shm > 64 * 1024) return ABED_EUNSUPPORTED;
         const long long words = (long long)pl.grid_m * pl.grid_b * pl.grid_n;
         fill_u32_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st>>>(flags, words, 0u);
         LAUNCH_CHECK("fill_u32_kernel");
