@@ -251,7 +251,9 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         }
     }
     const int lane_base = (h0 * p.W + w0) * p.cb + ld_chunk * 16;   // byte offset of tap (0,0), channel chunk of this lane
-    // the L blocks this wave loads each step: block b = wave + 4 i (clamped: a duplicate load is harmless).
+    // the blocks this wave loads each step: block b = wave + 4 i < NB.  When NB is not a multiple of 4 the
+    // waves from NB % 4 on have one load fewer (their last slot is skipped, not duplicated: every
+    // vector-memory instruction per step counts on the small layers), and wait for one fewer.
     // Everything about a block that does not change from step to step is settled here: its
     // descriptor (a descriptor of size 0 masks a whole block), whether it is a filter block, the
     // scalar offset of an entry block's image, the per-lane row offset of a filter block.
@@ -263,7 +265,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
 #pragma unroll
     for (int i = 0; i < L; ++i) {
         int b = wave + 4 * i;
-        if (b > NB - 1) b = NB - 1;
+        if (b > NB - 1) b = NB - 1;                          // (slot unused, see short_wave)
         blk_rs[i] = rs_none; blk_soff[i] = 0; blk_voff[i] = OOB;
         blk_filter[i] = b < WK;
         if (b < WK) {
@@ -316,6 +318,8 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         if (utap) advance(std::true_type{}); else advance(std::false_type{});
     }
 
+    constexpr int REM = NB % 4;
+    const bool short_wave = REM != 0 && wave >= REM;         // this wave's last slot lies beyond the tile's blocks
     auto issue = [&](int stage, auto ut) {
         int voff_x;            // per-lane offset of this step's chunk inside an image, or OOB
         const bool live = s_step < p.crsb;                   // uniform: the step starts inside the reduction axis
@@ -332,8 +336,8 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         int8_t *sbase = lds + stage * STAGE + kg * SUB;
 #pragma unroll
         for (int i = 0; i < L; ++i) {
-            int b = wave + 4 * i;
-            if (b > NB - 1) b = NB - 1;
+            const int b = wave + 4 * i;
+            if (i == L - 1 && short_wave) break;             // wave-uniform
             __attribute__((address_space(3))) void *dst = (__attribute__((address_space(3))) void *)(sbase + b * 1024);
             // filter rows: constant per-lane row offset, the step in the scalar offset (the range check
             // looks at the per-lane offset only, so a step past the end is masked explicitly)
@@ -368,7 +372,8 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     const int nloop = nstages;
 #endif
     for (int step = 0; step < nloop; ++step) {
-        ABED_WAIT_VMCNT((NST - 2) * L);          // this wave's loads of `step` have landed
+        // this wave's loads of `step` have landed (the counter's limit is an immediate: one branch per count)
+        if (short_wave) ABED_WAIT_VMCNT((NST - 2) * (L - 1)); else ABED_WAIT_VMCNT((NST - 2) * L);
         __builtin_amdgcn_s_barrier();            // everyone's have, and everyone is done with step-1
         {
             int st = stage + NST - 1;            // the stage that step-1 used gets refilled
