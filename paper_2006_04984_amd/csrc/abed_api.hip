@@ -146,7 +146,10 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     if (f16 && !(variant == ABED_NONE || variant == ABED_FUSED_OCG || variant == ABED_DUPLICATE)) return ABED_EUNSUPPORTED;
     const long long crs = (long long)d->C * d->R * d->S;
     if (crs > 65536) return ABED_EUNSUPPORTED;             // int32 accumulators are exact up to C*R*S = 64K (Sec. 4.1)
-    if ((long long)d->N * d->H * d->W * d->C >= (1LL << 31)) return ABED_EUNSUPPORTED;
+    // byte offsets inside a tensor are 32-bit (buffer descriptors); the largest offset marks "out of range"
+    const long long kMaxBytes = 0x7ffffff0LL;
+    if ((long long)d->N * d->H * d->W * d->C * pl.esize >= kMaxBytes) return ABED_EUNSUPPORTED;
+    if ((long long)d->K * crs * pl.esize >= kMaxBytes) return ABED_EUNSUPPORTED;
     pl.P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
     pl.Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
     pl.PQ = pl.P * pl.Q;

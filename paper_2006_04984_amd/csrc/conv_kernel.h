@@ -241,16 +241,17 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, (p.K + p.packed_df) * p.crsb, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_wc = __builtin_amdgcn_make_buffer_rsrc((void *)p.wchk, 0, p.wchk ? p.d_f * p.crsb : 0, 0x00020000);
     // pixel of this lane's row (the same for every entry block)
-    int h0 = INT_MIN / 2, w0 = 0;
+    int h0 = -(1 << 20), w0 = 0;                             // a pixel beyond the output: every tap test fails
+    int lane_base = 0;                                       // byte offset of tap (0,0), channel chunk of this lane
     {
         const int pix = pg * 16 + ld_row;
         if (pix < PQ) {
             const int pp = pix / p.Q, qq = pix - pp * p.Q;
             h0 = pp * p.sh - p.ph;
             w0 = qq * p.sw - p.pw;
+            lane_base = (h0 * p.W + w0) * p.cb + ld_chunk * 16;
         }
     }
-    const int lane_base = (h0 * p.W + w0) * p.cb + ld_chunk * 16;   // byte offset of tap (0,0), channel chunk of this lane
     // the blocks this wave loads each step: block b = wave + 4 i < NB.  When NB is not a multiple of 4 the
     // waves from NB % 4 on have one load fewer (their last slot is skipped, not duplicated: every
     // vector-memory instruction per step counts on the small layers), and wait for one fewer.

@@ -117,3 +117,13 @@ def test_packed_checksum_filters_layout(L):
         assert packed.d_f == plain.d_f and packed.wchk_bytes == plain.wchk_bytes
         assert packed.grid_n * packed.tile_n >= (K + 15) // 16 * 16 > (packed.grid_n - 1) * packed.tile_n
         assert packed.grid_n * packed.tile_n <= plain.grid_n * plain.tile_n
+
+
+def test_tensor_size_limits_are_in_bytes(L):
+    """Offsets inside a tensor are 32-bit byte offsets: 2^30 fp16 elements are too many, 2^30 int8 elements are not."""
+    from synth import ConvShape
+    d = abed.desc_from_shape(ConvShape(1024, 64, 64, 256, 16, 1, 1, 1, 1, 0, 0))
+    assert abed.get_layout(d, 0, 0).grid_m == 256
+    with pytest.raises(AbedError) as e:
+        abed.get_layout(d, 1, 0)
+    assert e.value.status == 2
