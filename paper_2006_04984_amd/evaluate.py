@@ -194,35 +194,54 @@ def cmd_layers(args):
 
 
 def cmd_detect(args):
-    """Single-bit flips in accumulators, filters, inputs of an int8 layer (Sec. 5.4 campaigns)."""
+    """Single-bit flips in accumulators, filters, inputs of an int8 layer (Sec. 5.4 campaigns), for every
+    scheme: FC + IC, FC alone, IC alone (abed_conv_int8), FIC (abed_fic_conv_int8), IC option 2
+    (abed_ic2_conv_int8).  Filter and input flips are made after the checksums were generated; only
+    flips that change an output count ("corrupting").  The rates are Table 1 of Sec. 3.4, measured."""
     from synth import ConvShape
     s = ConvShape(32, 14, 14, 64, 64, 3, 3, 1, 1, 1, 1, "3x3_c64_14_n32")
-    L = Int8Layer(s, 7001, Variant.FUSED_OCG)
-    L.run()
-    torch.cuda.synchronize()
-    clean = L.y.clone()
-    rng = np.random.default_rng(args.seed)
     out = {}
-    # accumulators
-    det = 0
-    for _ in range(args.trials):
-        idx, bit = int(rng.integers(0, clean.numel())), int(rng.integers(0, 32))
-        L.run(compute_xchk=False, inject=(1, idx, bit))
-        det += int(L.flags.abs().max().item() != 0)
-    out["accumulator"] = dict(trials=args.trials, detected=det)
-    for name, t in (("filter", L.w), ("input", L.x)):
-        det = corrupting = 0
-        u = t.view(torch.uint8).view(-1)
+
+    def campaign(name, run, flagged, y, w, x):
+        """run(inject, regenerate) enqueues the scheme; regenerate = make the online checksums again."""
+        rng = np.random.default_rng(args.seed)
+        run(None, True)
+        torch.cuda.synchronize()
+        assert not flagged(), name + ": flag on a clean run"
+        clean = y.clone()
+        res = {}
+        det = 0
         for _ in range(args.trials):
-            idx, bit = int(rng.integers(0, u.numel())), int(rng.integers(0, 8))
-            u[idx] ^= (1 << bit)
-            L.run(compute_xchk=False)
-            changed = not torch.equal(L.y, clean)
-            flagged = int(L.flags.abs().max().item()) != 0
-            corrupting += int(changed)
-            det += int(changed and flagged)
-            u[idx] ^= (1 << bit)
-        out[name] = dict(trials=args.trials, corrupting=corrupting, detected_of_corrupting=det)
+            idx, bit = int(rng.integers(0, clean.numel())), int(rng.integers(0, 32))
+            run((1, idx, bit), False)
+            det += int(flagged())
+        res["accumulator"] = dict(trials=args.trials, detected=det)
+        for site, t in (("filter", w), ("input", x)):
+            det = corrupting = 0
+            u = t.view(torch.uint8).view(-1)
+            for _ in range(args.trials):
+                idx, bit = int(rng.integers(0, u.numel())), int(rng.integers(0, 8))
+                u[idx] ^= (1 << bit)
+                run(None, False)
+                changed = not torch.equal(y, clean)
+                corrupting += int(changed)
+                det += int(changed and flagged())
+                u[idx] ^= (1 << bit)
+            res[site] = dict(trials=args.trials, corrupting=corrupting, detected_of_corrupting=det)
+        out[name] = res
+
+    for name, v in (("fc_ic", Variant.FUSED_OCG), ("fc_only", Variant.FUSED_OCG | abed.ONLY_FC), ("ic_only", Variant.FUSED_OCG | abed.ONLY_IC)):
+        L = Int8Layer(s, 7001, v)
+        campaign(name, lambda inject, regen, L=L: L.run(compute_xchk=regen, inject=inject),
+                 lambda L=L: int(L.flags.abs().max().item()) != 0, L.y, L.w, L.x)
+    F = FicLayer(s, 7001, Variant.FUSED_OCG)
+    campaign("fic", lambda inject, regen: abed.fic_conv_int8(F.desc, F.x, F.w, F.wsum, F.xrows, regen, F.y, F.variant, F.result, F.flag,
+                                                             workspace=F.ws, inject=inject),
+             lambda: int(F.flag.item()) != 0, F.y, F.w, F.x)
+    I2 = Ic2Layer(s, 7001, Variant.FUSED_OCG)
+    campaign("ic2", lambda inject, regen: abed.ic2_conv_int8(I2.desc, I2.x, I2.w, I2.xrows, regen, I2.y, I2.variant, I2.result, I2.flags,
+                                                             workspace=I2.ws, inject=inject),
+             lambda: int(I2.flags.abs().max().item()) != 0, I2.y, I2.w, I2.x)
     fp = 0
     for r in range(args.clean):
         L2 = Int8Layer(s, 8000 + r, Variant.FUSED_OCG)
