@@ -116,6 +116,7 @@ void choose_tile(Plan &pl)
     const int nsteps = (pl.crs * pl.esize + 63) / 64;
     int kg = 1;
     if (t < 384 && nsteps >= 16) kg = (t <= 256 && nsteps >= 64) ? 4 : 2;
+    else if (t < 512 && nsteps >= 64) kg = 2;       // long loops still gain with 1.5-2 workgroups per CU (fp16 3x3, 256 channels: 30.8 -> 26.2 us)
     kg = env_int("ABED_TILE_KG", kg);
     while (kg > 1 && !tile_ok(wm, wk, kg)) kg /= 2;
     pl.kg = kg;
