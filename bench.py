@@ -97,6 +97,22 @@ def main():
         abed.fic_filter_prepare_int8(L.desc, L.w, L.wsum)   # offline step, not timed
         return L
 
+    def setup_fic_inloop(s, idx):
+        """Buffers for FIC with the input side formed in the convolution's main loop, same layer and data."""
+        L = Layer()
+        L.s, L.variant = s, abed.FIC_INLOOP
+        L.desc = abed.desc_from_shape(s)
+        lay = abed.fic_inloop_get_layout(L.desc)
+        x, w = int8_tensors(s, seed_for(2, idx))
+        L.x = torch.from_numpy(x).to(dev)
+        L.w = torch.from_numpy(w).to(dev)
+        L.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int32, device=dev)
+        L.wdig = torch.empty((lay.wdig_bytes,), dtype=torch.int8, device=dev)
+        L.ws = torch.zeros((max(256, lay.workspace_bytes),), dtype=torch.uint8, device=dev)
+        abed.workspace_init(L.ws)
+        abed.fic_inloop_filter_prepare_int8(L.desc, L.w, L.wdig)   # offline step, not timed
+        return L
+
     def run_fic(L):
         abed.fic_conv_int8(L.desc, L.x, L.w, L.wsum, L.xrows, True, L.y, L.variant, L.result, L.flag, workspace=L.ws)
 
@@ -206,6 +222,16 @@ def main():
         abed.fic_verify([L.desc for L in Ls], [L.variant for L in Ls], [L.ws for L in Ls], res_all, flag_all)
     t_fic_deferred = time_steps(fic_deferred_step, max(20, args.steps // 2 // 10 * 10), max(10, args.warmup // 2))
     assert int(flag_all.abs().max().item()) == 0 and bool((res_all[:, 0] == res_all[:, 1]).all().item()), "FIC mismatch on a fault-free run"
+    # FIC with the input side formed in the main loop (no second pass over x), comparisons deferred the same way
+    Li = [setup_fic_inloop(s, i) for i, s in enumerate(layers)]
+
+    def fic_inloop_step():
+        for L in Li:
+            abed.fic_inloop_conv_int8(L.desc, L.x, L.w, L.wdig, L.y, None, None, workspace=L.ws)
+        abed.fic_verify([L.desc for L in Li], [L.variant for L in Li], [L.ws for L in Li], res_all, flag_all)
+    t_fic_inloop = time_steps(fic_inloop_step, max(20, args.steps // 2 // 10 * 10), max(10, args.warmup // 2))
+    assert int(flag_all.abs().max().item()) == 0 and bool((res_all[:, 0] == res_all[:, 1]).all().item()), "FIC (in-loop) mismatch on a fault-free run"
+    del Li
     t_checked_eager = time_eager(step_of(Variant.FUSED_OCG), max(20, args.steps // 4), 5)
     t_dup = t_var[Variant.DUPLICATE]
 
@@ -248,11 +274,13 @@ def main():
                speedup_vs_duplicate=t_dup / t_checked,
                variant_overhead_pct={v.name: 100.0 * (t / t_unchecked - 1.0) for v, t in t_var.items() if v != Variant.NONE},
                fic=dict(note="FIC scheme of Sec. 3.3 (input patch checksum . filter checksum == sum of ConvOut, int64): "
-                             "fused option = the input checksum workgroups ride in the convolution's launch, then a one-workgroup kernel adds up the partial sums and compares; fused_deferred = one such launch for the four layers at the end of the step",
+                             "fused option = the input checksum workgroups ride in the convolution's launch, then a one-workgroup kernel adds up the partial sums and compares; fused_deferred = one such launch for the four layers at the end of the step; inloop_deferred = the input side formed in the convolution's main loop from the tiles it loads (no second pass over x; the input fmaps are then not covered), comparisons deferred",
                         fused_tops=total_ops / t_fic[Variant.FUSED_OCG] / 1e12,
                         fused_overhead_pct=100.0 * (t_fic[Variant.FUSED_OCG] / t_unchecked - 1.0),
                         fused_deferred_tops=total_ops / t_fic_deferred / 1e12,
                         fused_deferred_overhead_pct=100.0 * (t_fic_deferred / t_unchecked - 1.0),
+                        inloop_deferred_tops=total_ops / t_fic_inloop / 1e12,
+                        inloop_deferred_overhead_pct=100.0 * (t_fic_inloop / t_unchecked - 1.0),
                         unfused_tops=total_ops / t_fic[Variant.UNFUSED] / 1e12,
                         unfused_overhead_pct=100.0 * (t_fic[Variant.UNFUSED] / t_unchecked - 1.0)),
                single_scheme=dict(note="the headline path carries FC (Sec. 3.1) and the batch-checksum IC (Sec. 3.2 option 1) together; here each alone, FusedOCG",

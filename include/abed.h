@@ -295,6 +295,47 @@ abed_status_t abed_fic_verify(int32_t n_layers, const abed_conv_desc_t *descs, c
                               void *const *workspaces, int64_t *results, uint32_t *flags, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * FIC with the input side formed inside the convolution's main loop (a fusion beyond those of Sec. 4.3).
+ * The dot product of the scheme (Sec. 3.3) is also the sum, over all rows of the input patch matrix, of
+ * row . filter checksum:  dot = sum_{n,p,q} sum_{r,s,c} x[n, p*stride_h - pad_h + r, q*stride_w - pad_w + s, c]
+ * * wsum[r,s,c].  The tiles of the first filter tile hold exactly those rows in their operand fragments, so
+ * they multiply them with the filter checksum as well (vector dot instructions against three base-256 digits
+ * of wsum, exact) while the matrix units do the convolution: there is no second pass over x, no input checksum
+ * tensor, and one launch (plus the one-workgroup comparison).  ocs, dot, the comparison and the flag are those
+ * of abed_fic_conv_int8, bit for bit.
+ * What it protects: the filters (against their offline checksum), the convolution arithmetic and the
+ * accumulators, as FIC does.  A fault in x is seen only where the tiles of the other filter tiles read x
+ * differently from the first; where a layer has a single filter tile the input is not protected (FC alone
+ * has the same coverage, Table 1 of Sec. 3.4).  int8 only.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    int64_t workspace_bytes;
+    int64_t wdig_bytes;    /* 3 * 64 * ceil(R*S*C / 64) int8 */
+} abed_fic_inloop_layout_t;
+
+/* Value for abed_fic_verify's variants[] that names a layer run by abed_fic_inloop_conv_int8. */
+#define ABED_FIC_INLOOP 0x1000
+
+/* Host only.  ABED_ERANGE if the three digits or a lane's 32-bit sums could overflow (K > 32768, or a
+ * reduction axis of several hundred thousand elements); ABED_EUNSUPPORTED if R*S*C > 8192 (the digits must
+ * fit the LDS left beside the tile). */
+abed_status_t abed_fic_inloop_get_layout(const abed_conv_desc_t *desc, abed_fic_inloop_layout_t *out);
+
+/* Offline: the filter checksum wsum[r,s,c] = sum_k w[k,r,s,c] as three balanced base-256 digits,
+ * wdig[d][e] int8, e along (r,s,c), rows of 64 * ceil(R*S*C / 64) bytes, zero from R*S*C on. */
+abed_status_t abed_fic_inloop_filter_prepare_int8(const abed_conv_desc_t *desc, const int8_t *w, int8_t *wdig,
+                                                  void *stream);
+
+/* The checked convolution.  x, w, y, epilogue, result, flag, workspace, inject (site 1 only), errors: as for
+ * abed_fic_conv_int8; result == flag == NULL defers the comparison to abed_fic_verify (variant
+ * ABED_FIC_INLOOP).  All pointers are device pointers except desc, epilogue and inject. */
+abed_status_t abed_fic_inloop_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+                                        const int8_t *wdig, void *y, const abed_epilogue_t *epilogue,
+                                        int64_t *result, uint32_t *flag,
+                                        void *workspace, size_t workspace_bytes,
+                                        const abed_inject_t *inject, void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * IC option 2 (Sec. 3.2): the input fmaps are reduced to a checksum tensor of the size of one filter
  * (the same X[r,s,c] as in the FIC scheme above, in the same row-wise form xrows), that tensor is
  * convolved with the K filters, which gives K values chk[k] = sum_{r,s,c} X[r,s,c] * w[k,r,s,c], and

@@ -55,11 +55,18 @@ class FicLayout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("workspace_bytes", "wsum_bytes", "xrows_bytes")] + [("xrows_parts", ctypes.c_int32), ("xsum_bytes", ctypes.c_int64), ("xsum_next_bytes", ctypes.c_int64)]
 
 
+class FicInloopLayout(ctypes.Structure):
+    _fields_ = [("workspace_bytes", ctypes.c_int64), ("wdig_bytes", ctypes.c_int64)]
+
+
+FIC_INLOOP = 0x1000   # abed_fic_verify's variant value for layers run by abed_fic_inloop_conv_int8
+
+
 class Ic2Layout(ctypes.Structure):
     _fields_ = [("workspace_bytes", ctypes.c_int64), ("xrows_bytes", ctypes.c_int64), ("xrows_parts", ctypes.c_int32), ("n_values", ctypes.c_int32)]
 
 
-EXPORTS = ["abed_fic_verify", "abed_ic2_get_layout", "abed_ic2_conv_int8", "abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
+EXPORTS = ["abed_fic_inloop_get_layout", "abed_fic_inloop_filter_prepare_int8", "abed_fic_inloop_conv_int8", "abed_fic_verify", "abed_ic2_get_layout", "abed_ic2_conv_int8", "abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
            "abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_fp16",
            "abed_input_checksum_int8", "abed_input_checksum_fp16", "abed_workspace_init",
            "abed_conv_int8", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error"]
@@ -76,6 +83,10 @@ def lib():
         path = lib_path()
         if not os.path.exists(path):
             raise FileNotFoundError("%s not built: run python -m paper_2006_04984_amd.build" % path)
+        # torch first: it brings its own copy of the HIP runtime, and the library must resolve its HIP symbols
+        # to that copy.  Loaded the other way round the process holds two runtimes, and the second one to
+        # initialise finds no device.
+        import torch  # noqa: F401
         L = ctypes.CDLL(path)
         for name in EXPORTS:
             getattr(L, name)
@@ -99,6 +110,10 @@ def lib():
         L.abed_fic_input_checksum_int8.argtypes = [ctypes.POINTER(ConvDesc), i32, vp, vp, vp]
         L.abed_fic_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
                                          vp, vp, vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp]
+        L.abed_fic_inloop_get_layout.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(FicInloopLayout)]
+        L.abed_fic_inloop_filter_prepare_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+        L.abed_fic_inloop_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, ctypes.POINTER(_Epilogue), vp, vp,
+                                                vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp]
         L.abed_fic_verify.argtypes = [i32, ctypes.POINTER(ConvDesc), ctypes.POINTER(i32), ctypes.POINTER(vp), vp, vp, vp]
         L.abed_ic2_get_layout.argtypes = [ctypes.POINTER(ConvDesc), i32, ctypes.POINTER(Ic2Layout)]
         L.abed_ic2_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
@@ -213,6 +228,29 @@ def fic_conv_int8(desc, x, w, wsum, xrows, compute_xrows, y, variant, result, fl
     _check(lib().abed_fic_conv_int8(ctypes.byref(desc), _p(x), _p(w), _p(wsum), _p(xrows), int(bool(compute_xrows)),
                                     _p(y), epi, int(variant), _p(result), _p(flag), _p(xsum_in), _p(xsum_next),
                                     _p(workspace), nbytes, inj, _stream(stream)))
+
+
+def fic_inloop_get_layout(desc):
+    out = FicInloopLayout()
+    _check(lib().abed_fic_inloop_get_layout(ctypes.byref(desc), ctypes.byref(out)))
+    return out
+
+
+def fic_inloop_filter_prepare_int8(desc, w, wdig, stream=None):
+    _check(lib().abed_fic_inloop_filter_prepare_int8(ctypes.byref(desc), _p(w), _p(wdig), _stream(stream)))
+
+
+def fic_inloop_conv_int8(desc, x, w, wdig, y, result, flag, epilogue=None, workspace=None, inject=None, stream=None):
+    """abed_fic_inloop_conv_int8.  result: int64[2] tensor, flag: int32[1] tensor (device), or both None."""
+    epi = None
+    if epilogue is not None:
+        epi = ctypes.byref(_Epilogue(epilogue[0].data_ptr(), epilogue[1].data_ptr(), int(bool(epilogue[2]))))
+    inj = None
+    if inject is not None:
+        inj = ctypes.byref(_Inject(int(inject[0]), int(inject[1]), int(inject[2])))
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().abed_fic_inloop_conv_int8(ctypes.byref(desc), _p(x), _p(w), _p(wdig), _p(y), epi, _p(result), _p(flag),
+                                           _p(workspace), nbytes, inj, _stream(stream)))
 
 
 def ic2_get_layout(desc, variant):

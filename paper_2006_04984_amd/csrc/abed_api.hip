@@ -273,6 +273,7 @@ abed_status_t fic_plan(const abed_conv_desc_t *desc, int variant, Plan &pl, bool
     abed_status_t s = make_plan(desc, ABED_INT8, ABED_NONE, int8_out, pl);
     if (s != ABED_OK) return s;
     if (128LL * desc->N * pl.PQ >= (1LL << 31)) return ABED_ERANGE;     // input checksum entries are int32 (Sec. 4.1)
+    if (pl.crs >= 32768) return ABED_ERANGE;                            // four accumulators are added in 32 bits before widening
     if (desc->S > 7) return ABED_EUNSUPPORTED;
     return ABED_OK;
 }
@@ -408,7 +409,7 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
         // and its partial dot products while the tile workgroups convolve, apply the epilog and reduce
         // their accumulators.  Second: a one-workgroup kernel adds up the partial sums and compares.
         const int lead = (rows_blocks + 7) / 8 * 8;      // keeps the tiles' block index aligned to the 8 XCDs
-        cp.y = y; cp.fic_ocs = partial;
+        cp.y = y; cp.fic_ocs = partial; cp.fic_sum32 = !cp.inj_on && (long long)pl.crs * 4 * pl.wm * pl.wk * 16384 < (1LL << 31);
         cp.fic_wsum = wsum; cp.fic_xrows = xrows; cp.fic_dotpart = dotpart;
         cp.fic_parts = lay.xrows_parts; cp.fic_rows_blocks = rows_blocks; cp.fic_rows_lead = lead; cp.fic_from_rows = xsum_in ? 2 : (compute_xrows ? 0 : 1);
         cp.fic_xsum_in = xsum_in; cp.fic_xsum_next = xsum_next;
@@ -449,6 +450,39 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
     return ABED_OK;
 }
 
+// FIC with the input side formed in the convolution's main loop: what a layer's call and the deferred
+// comparison both need
+namespace {
+
+struct InloopPlan {
+    Plan pl;
+    int nstages, gpad;
+    unsigned dyn_lds;
+    long long partial_bytes, dot_bytes;
+};
+
+abed_status_t inloop_plan(const abed_conv_desc_t *desc, bool int8_out, InloopPlan &ip)
+{
+    abed_status_t s = make_plan(desc, ABED_INT8, ABED_NONE, int8_out, ip.pl);
+    if (s != ABED_OK) return s;
+    const Plan &pl = ip.pl;
+    const int nsteps = (pl.crs + 63) / 64;
+    ip.nstages = (nsteps + pl.kg - 1) / pl.kg;
+    ip.gpad = nsteps * 64;
+    // three digits hold |filter checksum| <= 128 K below 2^23; a lane's 32-bit sums take at most
+    // 16 * wm products of magnitude <= 2^14 per step
+    if (desc->K > 32768 || pl.crs >= 32768) return ABED_ERANGE;
+    if ((long long)pl.wm * ip.nstages >= 8192) return ABED_ERANGE;
+    const long long dyn = 3LL * ip.nstages * pl.kg * 64;
+    if (dyn > 24 * 1024) return ABED_EUNSUPPORTED;         // beside the kernel's own LDS (at most 128 KB of 160 KB)
+    ip.dyn_lds = (unsigned)(dyn < 128 ? 128 : dyn);
+    ip.partial_bytes = align256(8LL * pl.grid_m * pl.grid_b * pl.grid_n);
+    ip.dot_bytes = align256(8LL * pl.grid_m * pl.grid_b);
+    return ABED_OK;
+}
+
+}  // namespace
+
 abed_status_t abed_fic_verify(int32_t n_layers, const abed_conv_desc_t *descs, const int32_t *variants,
                               void *const *workspaces, int64_t *results, uint32_t *flags, void *stream)
 {
@@ -456,7 +490,8 @@ abed_status_t abed_fic_verify(int32_t n_layers, const abed_conv_desc_t *descs, c
     // check everything before the first launch
     for (int i = 0; i < n_layers; ++i) {
         Plan pl;
-        abed_status_t s = fic_plan(&descs[i], variants[i], pl, false);
+        InloopPlan ip;
+        abed_status_t s = variants[i] == ABED_FIC_INLOOP ? inloop_plan(&descs[i], false, ip) : fic_plan(&descs[i], variants[i], pl, false);
         if (s != ABED_OK) return s;
         if (!workspaces[i]) return ABED_EINVAL;
     }
@@ -466,13 +501,15 @@ abed_status_t abed_fic_verify(int32_t n_layers, const abed_conv_desc_t *descs, c
         for (int j = 0; j < n; ++j) {
             const int i = base + j;
             Plan pl;
-            fic_plan(&descs[i], variants[i], pl, false);
-            // the same carving as in abed_fic_conv_int8: 256 bytes kept free, partial output checksums, partial dot products
+            const bool inloop = variants[i] == ABED_FIC_INLOOP;
+            if (inloop) make_plan(&descs[i], ABED_INT8, ABED_NONE, false, pl);
+            else fic_plan(&descs[i], variants[i], pl, false);
+            // the same carving as in the call that ran the layer: 256 bytes kept free, partial output checksums, partial dot products
             const int npartial = variants[i] == ABED_UNFUSED ? kFicSumBlocks : pl.grid_m * pl.grid_b * pl.grid_n;
             FicVerifyParams &vp = bp.layer[j];
             vp.partial = (const long long *)((const char *)workspaces[i] + 256);
             vp.dotpart = (const long long *)((const char *)workspaces[i] + 256 + align256(8LL * npartial));
-            vp.ndot = fic_rows_blocks(&descs[i], variants[i]);
+            vp.ndot = inloop ? pl.grid_m * pl.grid_b : fic_rows_blocks(&descs[i], variants[i]);
             vp.npartial = npartial;
             vp.result = (long long *)results + 2 * i;
             vp.flag = flags + i;
@@ -480,6 +517,69 @@ abed_status_t abed_fic_verify(int32_t n_layers, const abed_conv_desc_t *descs, c
         fic_verify_batch_kernel<<<dim3(n), dim3(1024), 0, (hipStream_t)stream>>>(bp);
         LAUNCH_CHECK("fic_verify_batch_kernel");
     }
+    return ABED_OK;
+}
+
+// ---------------------------------------------------------------------------
+// FIC with the input side formed in the convolution's main loop
+// ---------------------------------------------------------------------------
+abed_status_t abed_fic_inloop_get_layout(const abed_conv_desc_t *desc, abed_fic_inloop_layout_t *out)
+{
+    if (!out) return ABED_EINVAL;
+    InloopPlan ip;
+    abed_status_t s = inloop_plan(desc, false, ip);
+    if (s != ABED_OK) return s;
+    out->workspace_bytes = 256 + ip.partial_bytes + ip.dot_bytes;
+    out->wdig_bytes = 3LL * ip.gpad;
+    return ABED_OK;
+}
+
+abed_status_t abed_fic_inloop_filter_prepare_int8(const abed_conv_desc_t *desc, const int8_t *w, int8_t *wdig, void *stream)
+{
+    InloopPlan ip;
+    abed_status_t s = inloop_plan(desc, false, ip);
+    if (s != ABED_OK) return s;
+    if (!w || !wdig) return ABED_EINVAL;
+    fic_filter_digits_i8_kernel<<<dim3(ip.gpad / 64), dim3(1024), 0, (hipStream_t)stream>>>(w, wdig, desc->K, ip.pl.crs, ip.gpad);
+    LAUNCH_CHECK("fic_filter_digits_i8_kernel");
+    return ABED_OK;
+}
+
+abed_status_t abed_fic_inloop_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w, const int8_t *wdig,
+                                        void *y, const abed_epilogue_t *epi, int64_t *result, uint32_t *flag,
+                                        void *workspace, size_t workspace_bytes, const abed_inject_t *inject, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    InloopPlan ip;
+    abed_status_t s = inloop_plan(desc, epi != nullptr, ip);
+    if (s != ABED_OK) return s;
+    const Plan &pl = ip.pl;
+    if (!x || !w || !wdig || !y) return ABED_EINVAL;
+    if ((result == nullptr) != (flag == nullptr)) return ABED_EINVAL;
+    if (epi && (!epi->scale || !epi->bias)) return ABED_EINVAL;
+    if (inject && inject->site != 0) {
+        if (inject->site != 1) return inject->site == 2 ? ABED_EUNSUPPORTED : ABED_EINVAL;
+        if (inject->index < 0 || inject->index >= (long long)desc->N * pl.PQ * desc->K || inject->bit < 0 || inject->bit > 31) return ABED_EINVAL;
+    }
+    if (!workspace || (long long)workspace_bytes < 256 + ip.partial_bytes + ip.dot_bytes) return ABED_EWORKSPACE;
+    long long *partial = (long long *)((char *)workspace + 256);
+    long long *dotpart = (long long *)((char *)workspace + 256 + ip.partial_bytes);
+    const int ntiles = pl.grid_m * pl.grid_b * pl.grid_n;
+    ConvParams cp;
+    fill_params(cp, desc, pl);
+    cp.x = x; cp.w = w; cp.y = y; cp.mode = MODE_PLAIN;
+    set_injection(cp, desc, pl, inject);
+    cp.fic_ocs = partial; cp.fic_sum32 = !cp.inj_on && (long long)pl.crs * 4 * pl.wm * pl.wk * 16384 < (1LL << 31); cp.fic_dotpart = dotpart; cp.fic_wdig = wdig;
+    cp.fic_ndig = 128LL * desc->K < 32768 ? 2 : 3;          // |filter checksum| <= 128 K; two digits reach 32767 + 128
+    if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
+    if (!launch_conv(false, pl.wm, pl.wk, pl.kg, cp, (ntiles + 7) / 8 * 8, st, ip.dyn_lds)) return ABED_EUNSUPPORTED;
+    LAUNCH_CHECK("conv_kernel (FIC, input side in the main loop)");
+    if (!result) return ABED_OK;
+    FicVerifyParams vp;
+    vp.dotpart = dotpart; vp.partial = partial; vp.result = (long long *)result; vp.flag = flag;
+    vp.ndot = pl.grid_m * pl.grid_b; vp.npartial = ntiles;
+    fic_verify_kernel<<<1, 1024, 0, st>>>(vp);
+    LAUNCH_CHECK("fic_verify_kernel");
     return ABED_OK;
 }
 

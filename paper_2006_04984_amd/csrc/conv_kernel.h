@@ -103,6 +103,18 @@ struct ConvParams {
     int fic_parts, fic_rows_blocks, fic_rows_lead, fic_from_rows;
     int32_t *fic_xsum_in;          // batch-summed input image [H][W][C] handed over by the previous layer (fic_from_rows == 2)
     int32_t *fic_xsum_next;        // batch sum of this layer's int8 output [P][Q][K], added to (must start at zero), or null
+    // FIC with the input side formed in the main loop (int8): fic_wdig = three balanced base-256 digits of the
+    // filter checksum, [3][nsteps * 64] int8 along the reduction axis (zero beyond it), or null.  The tiles of
+    // filter tile 0 multiply every activation fragment they feed to the matrix units with the digits as well
+    // (the sum over a tile's rows of row . filter checksum) and leave one 64-bit partial per (pixel group,
+    // batch tile) in fic_dotpart.  The launch then brings 3 * nstages * KG * 64 bytes of dynamic LDS (at
+    // least 128) for the digits.
+    const int8_t *fic_wdig;
+    // a lane's accumulators add up inside 32 bits (R*S*C * 4*WM*WK * 2^14 < 2^31) and no fault is injected: the
+    // lane sums are formed in 32 bits.  A faulty accumulator can then wrap a lane's sum; the reported output
+    // checksum is off by a multiple of 2^32 in that case, and still differs from the dot product.
+    int fic_sum32;
+    int fic_ndig;                  // digits in use: 2 while 128 K < 2^15, else 3 (the third row is zero otherwise)
     // IC option 2 (Sec. 3.2): per-filter sums of a tile's accumulators over its pixels and entries,
     // [grid_m * grid_b][grid_n * WK * 16] int64, or null
     long long *ic2_part;
@@ -158,10 +170,35 @@ __device__ __forceinline__ int next_digit(int &s)
     return d;
 }
 
+#if defined(__HIP_DEVICE_COMPILE__)
+// Sum of a 32-bit value over the 64 lanes of a wave with data-parallel-primitive adds (no LDS round
+// trips): shifts by 1, 2, 4, 8 inside each row of 16 lanes leave a row's sum in its lane 15, two row
+// broadcasts carry it into lane 63.  The values must be small enough that the sum fits 32 bits.
+__device__ __forceinline__ int wave_sum32(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+    return __builtin_amdgcn_readlane(v, 63);
+}
+// The same for a 64-bit value of magnitude below 2^58, as three limbs of 20, 20 and 24 bits.
+__device__ __forceinline__ long long wave_sum64(long long t)
+{
+    const int l0 = (int)(t & 0xfffff), l1 = (int)((t >> 20) & 0xfffff), l2 = (int)(t >> 40);
+    const long long s0 = wave_sum32(l0), s1 = wave_sum32(l1), s2 = wave_sum32(l2);
+    return s0 + (s1 << 20) + (s2 << 40);
+}
+#endif
+
 // F16 = false: int8 data, int32 accumulators, exact checks mod 2^32.
 // F16 = true: fp16 data, fp32 accumulators, threshold checks (Sec. 7); the two checksum tensors
 // per side are the hi/lo pair, recombined by addition.
-template <bool F16, int WM, int WK, int NST, int KG>
+// FICV = true (int8 only): the build of the kernel that also forms the FIC scheme's dot product in the main
+// loop (fic_wdig); kept apart so that the other launches carry none of it.
+template <bool F16, int WM, int WK, int NST, int KG, bool FICV = false>
 __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass needs the signature only (the body uses device-only types)
@@ -350,6 +387,31 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         for (int g = 0; g < KG; ++g) advance(ut);            // this group's next step
     };
 
+    // ---------------- FIC, input side in the main loop: the digits of the filter checksum into LDS ----------------
+    extern __shared__ __attribute__((aligned(16))) int8_t dyn_lds[];
+    bool fic_tile = false;                       // uniform over the workgroup
+    int fic_pad = 0;                             // bytes of one digit row in LDS
+    int fdot0 = 0, fdot1 = 0, fdot2 = 0;         // this lane's sums of fragment . digit
+    if constexpr (FICV) {
+        if (p.fic_wdig && kt == 0) {
+            fic_tile = true;
+            fic_pad = ((p.nsteps + KG - 1) / KG) * KG * 64;
+        }
+    }
+    // 16-byte chunk c of the digits: from global memory (zeros beyond the reduction axis) / to LDS
+    auto dig_load = [&](int c) {
+        const int gpad = p.nsteps * 64, per_row = fic_pad >> 4;
+        const int d = c / per_row, o = (c - d * per_row) << 4;
+        i32x4 v = {0, 0, 0, 0};
+        if (o < gpad) v = *reinterpret_cast<const i32x4 *>(p.fic_wdig + d * gpad + o);
+        return v;
+    };
+    auto dig_store = [&](int c, i32x4 v) {
+        const int per_row = fic_pad >> 4;
+        const int d = c / per_row, o = (c - d * per_row) << 4;
+        *reinterpret_cast<i32x4 *>(dyn_lds + d * fic_pad + o) = v;
+    };
+
     // ---------------- accumulators ----------------
     acc_t acc[WM][WK];
     const acc_t zero4 = {0, 0, 0, 0};
@@ -364,8 +426,22 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     const int rd_lane = lds_off(lj, lg);         // this lane's 16 bytes inside any 1 KB block
     const int nstages = (p.nsteps + KG - 1) / KG;
     auto main_loop = [&](auto ut) {
+    // FIC, input side: a thread's first chunk of the digits is requested before the tile's loads, so that
+    // it does not delay them, and put into LDS behind them; the loop's first barrier publishes it
+    const int dig_chunks = fic_tile ? p.fic_ndig * (fic_pad >> 4) : 0;
+    i32x4 dig_first = {0, 0, 0, 0};
+    if constexpr (FICV) {
+        if (tid < dig_chunks) dig_first = dig_load(tid);
+    }
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s) issue(s, ut);
+    if constexpr (FICV) {
+        if (fic_tile) {
+            if (tid < dig_chunks) dig_store(tid, dig_first);
+            for (int c = tid + 256 * KG; c < dig_chunks; c += 256 * KG) dig_store(c, dig_load(c));
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // the LDS writes (lgkmcnt 0) are done before the barrier
+        }
+    }
     int stage = 0;
 #ifdef ABED_ENABLE_DBG
     const int nloop = (p.dbg & 2) ? 0 : nstages;
@@ -397,12 +473,49 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 else
                     acc[i][kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bfr[i], acc[i][kb], 0, 0, 0);
         }
+        // FIC, input side: the same fragments against the digits of the filter checksum, on the vector ALU
+        // behind the matrix instructions (which are still executing)
+        if constexpr (FICV) {
+            if (fic_tile) {                      // scalar branch
+                const int8_t *dg = dyn_lds + (step * KG + kg) * 64 + lg * 16;
+                const i32x4 d0 = *reinterpret_cast<const i32x4 *>(dg);
+                const i32x4 d1 = *reinterpret_cast<const i32x4 *>(dg + fic_pad);
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        fdot0 = __builtin_amdgcn_sdot4(bfr[i][j], d0[j], fdot0, false);
+                        fdot1 = __builtin_amdgcn_sdot4(bfr[i][j], d1[j], fdot1, false);
+                    }
+                if (p.fic_ndig > 2) {            // scalar branch
+                    const i32x4 d2 = *reinterpret_cast<const i32x4 *>(dg + 2 * fic_pad);
+#pragma unroll
+                    for (int i = 0; i < WM; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) fdot2 = __builtin_amdgcn_sdot4(bfr[i][j], d2[j], fdot2, false);
+                }
+            }
+        }
         if (++stage == NST) stage = 0;
     }
     };
     if (utap) main_loop(std::true_type{}); else main_loop(std::false_type{});
     ABED_WAIT_VMCNT(0);                          // drain the run-ahead loads before LDS is reused
     __builtin_amdgcn_s_barrier();
+
+    // FIC, input side: this lane's share of the dot product, recombined from the digits in 64 bits
+    // (Sec. 4.1).  The waves of the groups that end here leave their sums in LDS (the digits there are no
+    // longer read; the barrier of the group sum publishes them); the others carry theirs into the epilogue.
+    long long fic_dot = 0;
+    if constexpr (FICV) {
+        if (fic_tile) {
+            fic_dot = (long long)fdot0 + 256LL * fdot1 + 65536LL * fdot2;
+            if (KG > 1 && kg > 0) {
+                const long long t = wave_sum64(fic_dot);
+                if (lane == 0) reinterpret_cast<long long *>(dyn_lds)[wave_all] = t;
+            }
+        }
+    }
 
     // ---------------- sum over the groups of the reduction axis ----------------
     if constexpr (KG > 1) {
@@ -635,17 +748,37 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     // (1b) FIC scheme (Sec. 3.3): output fmap checksum = the sum of all accumulators, in 64 bits
     // (Sec. 4.1).  Rows, entries and filters beyond the problem were loaded as zeros and add nothing.
     if (p.fic_ocs) {
+        // a lane's four values of one (entry, filter block) add up inside 32 bits (the host checked R*S*C <
+        // 2^15: each is at most R*S*C * 2^14 in magnitude); so do all of a lane's values when fic_sum32 is set,
+        // else every such group is widened to 64 bits
         long long t = 0;
+        int t32 = 0;
 #pragma unroll
         for (int i = 0; i < WM; ++i)
 #pragma unroll
-            for (int kb = 0; kb < WK; ++kb)
-                t += (long long)acc[i][kb][0] + acc[i][kb][1] + acc[i][kb][2] + acc[i][kb][3];
+            for (int kb = 0; kb < WK; ++kb) {
+                t32 += (acc[i][kb][0] + acc[i][kb][1]) + (acc[i][kb][2] + acc[i][kb][3]);
+                if (!p.fic_sum32) { t += t32; t32 = 0; }         // scalar branch
+            }
+        t += t32;
+        // the workgroup's output sum and, for the in-loop input side, its dot product
+        long long *e64 = reinterpret_cast<long long *>(e_misc + 16);   // [0..3] output sums, [4..7] dot products of the waves
         for (int m = 32; m >= 1; m >>= 1) t += __shfl_xor(t, m, 64);
-        long long *e64 = reinterpret_cast<long long *>(e_misc + 16);
         if (lane == 0) e64[wave] = t;
+        if (fic_tile) {
+            long long d = fic_dot;
+            for (int m = 32; m >= 1; m >>= 1) d += __shfl_xor(d, m, 64);
+            if (lane == 0) e64[4 + wave] = d;
+        }
         __syncthreads();
-        if (tid == 0) p.fic_ocs[tile] = e64[0] + e64[1] + e64[2] + e64[3];
+        if (tid == 0) {
+            p.fic_ocs[tile] = e64[0] + e64[1] + e64[2] + e64[3];
+            if (fic_tile) {
+                long long d = e64[4] + e64[5] + e64[6] + e64[7];
+                for (int w = 4; w < 4 * KG; ++w) d += reinterpret_cast<const long long *>(dyn_lds)[w];
+                p.fic_dotpart[pg * p.grid_b + nt] = d;
+            }
+        }
     }
 
     // (1c) IC option 2 (Sec. 3.2): the output fmaps reduced over batch, height and width, one 64-bit sum

@@ -38,10 +38,11 @@ constexpr bool tile_ok(int wm, int wk, int kg)
     return regs <= 512 / kg && 2 * kg * nb * 1024 <= 160 * 1024 - 1024 && (kg - 1) * 4 * wm * wk * 1024 <= 160 * 1024 - 1024;
 }
 
-// Returns false if (wm, wk, kg) is not a compiled configuration.
-bool launch_conv(bool f16, int wm, int wk, int kg, const ConvParams &p, int grid, hipStream_t st);
+// Returns false if (wm, wk, kg) is not a compiled configuration.  dyn_lds: bytes of dynamic LDS behind the
+// kernel's own (the digits of the FIC scheme's in-loop input side), else 0.
+bool launch_conv(bool f16, int wm, int wk, int kg, const ConvParams &p, int grid, hipStream_t st, unsigned dyn_lds = 0);
 
-#define ABED_DECL_LAUNCH(WK, KG) bool launch_conv_wk##WK##_kg##KG(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st);
+#define ABED_DECL_LAUNCH(WK, KG) bool launch_conv_wk##WK##_kg##KG(bool f16, int wm, const ConvParams &p, int grid, hipStream_t st, unsigned dyn_lds);
 #define ABED_FOR_ALL_WK_KG(X) \
     X(1, 1) X(4, 1) X(5, 1) X(8, 1) X(9, 1) X(1, 2) X(4, 2) X(5, 2) X(8, 2) X(9, 2) X(1, 4) X(4, 4) X(5, 4) X(8, 4) X(9, 4)
 ABED_FOR_ALL_WK_KG(ABED_DECL_LAUNCH)

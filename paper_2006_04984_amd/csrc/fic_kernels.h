@@ -28,6 +28,33 @@ __global__ __launch_bounds__(1024) void fic_filter_checksum_i8_kernel(const int8
     }
 }
 
+// Offline step of the in-loop option: the same filter checksum as three balanced base-256 digits (each in
+// [-128, 127], value = d0 + 256 d1 + 65536 d2, exact while |checksum| < 2^23), int8 [3][gpad] with
+// gpad = 64 * ceil(crs / 64) and zeros from crs on.  Grid gpad / 64 x 1024 threads.
+__global__ __launch_bounds__(1024) void fic_filter_digits_i8_kernel(const int8_t *w, int8_t *wdig, int K, int crs, int gpad)
+{
+    __shared__ int red[16][64];
+    const int slice = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const int e = blockIdx.x * 64 + l;
+    int s = 0;
+    if (e < crs) {
+#pragma unroll 4
+        for (int k = slice; k < K; k += 16) s += w[(long long)k * crs + e];
+    }
+    red[slice][l] = s;
+    __syncthreads();
+    if (slice == 0) {
+        int t = 0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) t += red[q][l];
+        for (int d = 0; d < 3; ++d) {
+            const int dig = ((t + 128) & 255) - 128;
+            t = (t - dig) >> 8;                   // exact: t - dig is a multiple of 256
+            wdig[d * gpad + e] = (int8_t)dig;
+        }
+    }
+}
+
 template <int SMAX>
 __global__ __launch_bounds__(256) void fic_input_rows_i8_kernel(const FicRowsParams p)
 {

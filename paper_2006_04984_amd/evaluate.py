@@ -109,6 +109,34 @@ class FicLayer:
                            self.flag, epilogue=self.epi, workspace=self.ws, xsum_in=self.xsum_in, xsum_next=self.xsum_next)
 
 
+class FicInloopLayer:
+    """Device buffers of one int8 convolution checked by FIC with the input side formed in the main loop."""
+
+    def __init__(self, s, seed, epilogue=False, x=None):
+        from synth import int8_tensors, requant_params
+        self.s, self.variant = s, abed.FIC_INLOOP
+        self.desc = abed.desc_from_shape(s)
+        lay = abed.fic_inloop_get_layout(self.desc)
+        xh, wh = int8_tensors(s, seed)
+        self.x = torch.from_numpy(xh).to(DEV) if x is None else x
+        self.w = torch.from_numpy(wh).to(DEV)
+        self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.int8 if epilogue else torch.int32, device=DEV)
+        self.wdig = torch.empty((lay.wdig_bytes,), dtype=torch.int8, device=DEV)
+        self.result = torch.zeros((2,), dtype=torch.int64, device=DEV)
+        self.flag = torch.zeros((1,), dtype=torch.int32, device=DEV)
+        self.ws = torch.zeros((max(256, lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
+        self.epi = None
+        if epilogue:
+            sc, bi = requant_params(s, seed)
+            self.scale, self.bias = torch.from_numpy(sc).to(DEV), torch.from_numpy(bi).to(DEV)
+            self.epi = (self.scale, self.bias, True)
+        abed.fic_inloop_filter_prepare_int8(self.desc, self.w, self.wdig)
+
+    def run(self, deferred=False, inject=None):
+        abed.fic_inloop_conv_int8(self.desc, self.x, self.w, self.wdig, self.y, None if deferred else self.result,
+                                  None if deferred else self.flag, epilogue=self.epi, workspace=self.ws, inject=inject)
+
+
 class Ic2Layer:
     """Device buffers of one int8 convolution checked by IC option 2 (Sec. 3.2)."""
 
@@ -168,6 +196,11 @@ def cmd_layers(args):
             F.run()
             t_fic = _graph_time(lambda: F.run(), stream)
             assert int(F.flag.item()) == 0
+            FL = FicInloopLayer(s, seed_for(args.config, i), epilogue=epi)
+            FL.run()
+            t_ficl = _graph_time(lambda: FL.run(), stream)
+            t_ficl_def = _graph_time(lambda: FL.run(deferred=True), stream)    # the convolution's launch alone
+            assert int(FL.flag.item()) == 0
             I2 = Ic2Layer(s, seed_for(args.config, i), Variant.FUSED_OCG, epilogue=epi)
             I2.run()
             t_ic2 = _graph_time(lambda: I2.run(), stream)
@@ -175,6 +208,8 @@ def cmd_layers(args):
             nbytes = s.min_bytes(1, 1, 1 if epi else 4)
             row[tag] = dict(unchecked_us=t[Variant.NONE] * 1e6, checked_us=t[Variant.FUSED_OCG] * 1e6,
                             fic_fused_us=t_fic * 1e6, fic_fused_overhead_pct=100.0 * (t_fic / t[Variant.NONE] - 1.0),
+                            fic_inloop_us=t_ficl * 1e6, fic_inloop_overhead_pct=100.0 * (t_ficl / t[Variant.NONE] - 1.0),
+                            fic_inloop_conv_only_us=t_ficl_def * 1e6, fic_inloop_conv_only_overhead_pct=100.0 * (t_ficl_def / t[Variant.NONE] - 1.0),
                             duplicate_us=t[Variant.DUPLICATE] * 1e6,
                             ic2_fused_us=t_ic2 * 1e6, ic2_fused_overhead_pct=100.0 * (t_ic2 / t[Variant.NONE] - 1.0),
                             fc_only_us=t[FC_ONLY] * 1e6, fc_only_overhead_pct=100.0 * (t[FC_ONLY] / t[Variant.NONE] - 1.0),
@@ -189,13 +224,13 @@ def cmd_layers(args):
                            frac_of_hbm_peak=nbytes / (rot["unchecked_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS)
                 row[tag]["rotating_buffers"] = rot
         rows.append(row)
-    print(json.dumps(dict(config=args.config, batch=layers[0].N, note="checked = FC + batch-checksum IC, FusedOCG incl. the ICG kernel; fc_only / ic_only = one of the two alone (FusedOCG; ic_only incl. the ICG kernel); fic_fused = the FIC scheme of Sec. 3.3, fused option; ic2_fused = IC option 2 of Sec. 3.2 (K values), fused option; GB/s = algorithmic minimum bytes / time",
+    print(json.dumps(dict(config=args.config, batch=layers[0].N, note="checked = FC + batch-checksum IC, FusedOCG incl. the ICG kernel; fc_only / ic_only = one of the two alone (FusedOCG; ic_only incl. the ICG kernel); fic_fused = the FIC scheme of Sec. 3.3, fused option; fic_inloop = FIC with the input side formed in the convolution's main loop (conv_only: without the comparison launch); ic2_fused = IC option 2 of Sec. 3.2 (K values), fused option; GB/s = algorithmic minimum bytes / time",
                           layers=rows)))
 
 
 def cmd_detect(args):
     """Single-bit flips in accumulators, filters, inputs of an int8 layer (Sec. 5.4 campaigns), for every
-    scheme: FC + IC, FC alone, IC alone (abed_conv_int8), FIC (abed_fic_conv_int8), IC option 2
+    scheme: FC + IC, FC alone, IC alone (abed_conv_int8), FIC (abed_fic_conv_int8, abed_fic_inloop_conv_int8), IC option 2
     (abed_ic2_conv_int8).  Filter and input flips are made after the checksums were generated; only
     flips that change an output count ("corrupting").  The rates are Table 1 of Sec. 3.4, measured."""
     from synth import ConvShape
@@ -238,6 +273,10 @@ def cmd_detect(args):
     campaign("fic", lambda inject, regen: abed.fic_conv_int8(F.desc, F.x, F.w, F.wsum, F.xrows, regen, F.y, F.variant, F.result, F.flag,
                                                              workspace=F.ws, inject=inject),
              lambda: int(F.flag.item()) != 0, F.y, F.w, F.x)
+    # FIC with the input side formed in the main loop: it has no input checksum made ahead of the convolution,
+    # so a corrupted input is what both sides of the comparison see (expected: none of those flips caught)
+    FL = FicInloopLayer(s, 7001)
+    campaign("fic_inloop", lambda inject, regen: FL.run(inject=inject), lambda: int(FL.flag.item()) != 0, FL.y, FL.w, FL.x)
     I2 = Ic2Layer(s, 7001, Variant.FUSED_OCG)
     campaign("ic2", lambda inject, regen: abed.ic2_conv_int8(I2.desc, I2.x, I2.w, I2.xrows, regen, I2.y, I2.variant, I2.result, I2.flags,
                                                              workspace=I2.ws, inject=inject),
@@ -376,6 +415,36 @@ def cmd_resnet50(args):
     t = _graph_time(fic_deferred_step, stream, reps=2, replays=5)
     result["fic_fused_deferred"] = dict(ms=t * 1e3, tops=total_ops / t / 1e12)
     result["fic_fused_deferred_overhead_pct"] = 100.0 * (result["fic_fused_deferred"]["ms"] / result["unchecked"]["ms"] - 1.0)
+    del objs
+    torch.cuda.empty_cache()
+    # FIC with the input side formed in the main loop: one launch per layer plus the comparison, or deferred
+    objs = []
+    for i, s in enumerate(layers):
+        if s.C % 16:
+            s = ConvShape(s.N, s.H, s.W, 16, s.K, s.R, s.S, s.stride_h, s.stride_w, s.pad_h, s.pad_w, s.name)
+        objs.append(FicInloopLayer(s, 5000 + i, epilogue=True))
+
+    def inloop_step():
+        for L in objs:
+            L.run()
+    inloop_step()
+    torch.cuda.synchronize()
+    bad = [L.s.name for L in objs if int(L.flag.item()) != 0]
+    assert not bad, "FIC (in-loop) flag set on a clean run: %s" % bad
+    t = _graph_time(inloop_step, stream, reps=2, replays=5)
+    result["fic_inloop"] = dict(ms=t * 1e3, tops=total_ops / t / 1e12)
+    result["fic_inloop_overhead_pct"] = 100.0 * (result["fic_inloop"]["ms"] / result["unchecked"]["ms"] - 1.0)
+
+    def inloop_deferred_step():
+        for L in objs:
+            L.run(deferred=True)
+        abed.fic_verify([L.desc for L in objs], [L.variant for L in objs], [L.ws for L in objs], res_all, flag_all)
+    inloop_deferred_step()
+    torch.cuda.synchronize()
+    assert int(flag_all.abs().max().item()) == 0 and bool((res_all[:, 0] == res_all[:, 1]).all().item())
+    t = _graph_time(inloop_deferred_step, stream, reps=2, replays=5)
+    result["fic_inloop_deferred"] = dict(ms=t * 1e3, tops=total_ops / t / 1e12)
+    result["fic_inloop_deferred_overhead_pct"] = 100.0 * (result["fic_inloop_deferred"]["ms"] / result["unchecked"]["ms"] - 1.0)
     del objs
     torch.cuda.empty_cache()
     # FIC with the next layer's input checksum generation fused in (Sec. 4.3): inside a bottleneck the
