@@ -127,3 +127,24 @@ def test_tensor_size_limits_are_in_bytes(L):
     with pytest.raises(AbedError) as e:
         abed.get_layout(d, 1, 0)
     assert e.value.status == 2
+
+
+def test_fic_inloop_layout_and_limits(L):
+    """Host logic of the in-loop FIC option: digit buffer size, workspace carving, range limits."""
+    import dataclasses
+    for s in list(CONFIG2) + [l for l in resnet50_layers(128) if l.C % 16 == 0][:20]:
+        d = abed.desc_from_shape(s)
+        lay = abed.fic_inloop_get_layout(d)
+        crs = s.R * s.S * s.C
+        assert lay.wdig_bytes == 3 * 64 * ((crs + 63) // 64)
+        plain = abed.get_layout(d, 0, 0)
+        tiles, rows = plain.grid_m * plain.grid_b * plain.grid_n, plain.grid_m * plain.grid_b
+        align = lambda v: (v + 255) // 256 * 256
+        assert lay.workspace_bytes == 256 + align(8 * tiles) + align(8 * rows)
+    s = CONFIG2[0]
+    with pytest.raises(AbedError) as e:      # the digits of a reduction axis of 9216 do not fit beside the tile
+        abed.fic_inloop_get_layout(abed.desc_from_shape(dataclasses.replace(s, C=1024)))
+    assert e.value.status == 2
+    with pytest.raises(AbedError) as e:      # three digits hold the filter checksum up to K = 32768
+        abed.fic_inloop_get_layout(abed.desc_from_shape(dataclasses.replace(s, K=32768 + 16)))
+    assert e.value.status in (2, 5)      # the tile plan may refuse such a filter count first
