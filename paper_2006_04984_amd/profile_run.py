@@ -23,9 +23,9 @@ def main():
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--int8-out", action="store_true")
     ap.add_argument("--copy-mb", type=int, default=0)
-    ap.add_argument("--scheme", default="fcic", choices=["fcic", "fc", "ic", "fic", "ic2"],
+    ap.add_argument("--scheme", default="fcic", choices=["fcic", "fc", "ic", "fic", "fic_inloop", "ic2"],
                     help="fcic: filter + batch checksums (abed_conv_int8); fc / ic: one of the two alone; "
-                         "fic: the scalar scheme (abed_fic_conv_int8); ic2: IC option 2, K values (abed_ic2_conv_int8)")
+                         "fic: the scalar scheme (abed_fic_conv_int8); fic_inloop: the same with its input side formed in the main loop (abed_fic_inloop_conv_int8); ic2: IC option 2, K values (abed_ic2_conv_int8)")
     ap.add_argument("--batch", type=int, default=0, help="override the configuration's batch size")
     args = ap.parse_args()
     from synth import CONFIG2, CONFIG3, seed_for
@@ -36,6 +36,9 @@ def main():
     if args.scheme == "fic":
         from .evaluate import FicLayer
         L = FicLayer(s, seed_for(args.config, args.layer), Variant(args.variant), epilogue=args.int8_out)
+    elif args.scheme == "fic_inloop":
+        from .evaluate import FicInloopLayer
+        L = FicInloopLayer(s, seed_for(args.config, args.layer), epilogue=args.int8_out)
     elif args.scheme == "ic2":
         from .evaluate import Ic2Layer
         L = Ic2Layer(s, seed_for(args.config, args.layer), Variant(args.variant), epilogue=args.int8_out)
@@ -54,7 +57,9 @@ def main():
         for _ in range(3):
             b.copy_(a)
         torch.cuda.synchronize()
-    if args.scheme == "fic":
+    if args.scheme == "fic_inloop":
+        print("profiled", s.name, "FIC, input side in the main loop, flag", int(L.flag.item()))
+    elif args.scheme == "fic":
         print("profiled", s.name, "FIC variant", args.variant, "flag", int(L.flag.item()))
     elif args.scheme == "ic2":
         print("profiled", s.name, "IC option 2 variant", args.variant, "flags", int(L.flags.abs().max().item()))
