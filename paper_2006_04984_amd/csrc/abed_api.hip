@@ -309,7 +309,7 @@ abed_status_t fic_input_rows(const abed_conv_desc_t *d, const Plan &pl, int vari
     rp.xsum = nullptr;
     rp.N = d->N; rp.H = d->H; rp.W = d->W; rp.C = d->C; rp.R = wsum ? d->R : 0; rp.S = d->S; rp.P = pl.P; rp.Q = pl.Q;
     rp.sh = d->stride_h; rp.sw = d->stride_w; rp.ph = d->pad_h; rp.pw = d->pad_w;
-    const dim3 grid((unsigned)fic_rows_blocks(d, variant));
+    const dim3 grid((unsigned)((fic_rows_blocks(d, variant) + 7) / 8 * 8));   // whole rounds over the 8 XCDs
     if (d->S <= 1) fic_input_rows_i8_kernel<1><<<grid, dim3(256), 0, st>>>(rp);
     else if (d->S <= 3) fic_input_rows_i8_kernel<3><<<grid, dim3(256), 0, st>>>(rp);
     else fic_input_rows_i8_kernel<7><<<grid, dim3(256), 0, st>>>(rp);

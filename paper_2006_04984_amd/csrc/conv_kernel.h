@@ -236,7 +236,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     if constexpr (!F16) {
         // FIC scheme: the leading workgroups make the input checksum (Sec. 3.3) beside the tiles
         if (blk < p.fic_rows_lead) {
-            if (tid >= 256 || blk >= p.fic_rows_blocks) return;
+            if (tid >= 256) return;               // (indices past the last piece leave inside)
             FicRowsParams rp;
             rp.x = p.x; rp.wsum = p.fic_wsum; rp.xrows = p.fic_xrows; rp.dotpart = p.fic_dotpart;
             rp.N = p.N; rp.H = p.H; rp.W = p.W; rp.C = p.C; rp.R = p.fic_wsum ? p.R : 0; rp.S = p.S; rp.P = p.P; rp.Q = p.Q;

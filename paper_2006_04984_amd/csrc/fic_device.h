@@ -51,14 +51,22 @@ __device__ __forceinline__ long long fic_wsum_meeting_row(const int32_t *wsum, i
 // dot product with the filter checksum:
 //   sum_{r,s,c} X * wsum = sum_{h,s,c} xrows[h,s,c] * (sum of wsum[r,s,c] over the filter rows r that meet h).
 // LDS: cols = 64 x 64 ints (16-byte aligned), meets = SMAX x 64 bytes, dsum = 4 x 8 bytes.  256 threads;
-// `block` is the workgroup's index among the input checksum workgroups.
+// `block` is the workgroup's index among the input checksum workgroups
+// (a multiple of 8 of them are launched).
 constexpr int kFicRowsLdsBytes = 64 * 64 * 4 + 7 * 64 + 64;
 template <int SMAX>
 __device__ __forceinline__ void fic_rows_body(const FicRowsParams &p, const int block, const int tid,
                                               int (*cols)[64], unsigned char (*meets)[64], long long *dsum)
 {
     const int cgroups = (p.C + 63) / 64;
-    int b = block;
+    // Workgroups go to the 8 XCDs round-robin by index and every XCD has its own L2: index i is mapped to
+    // piece (i & 7) * ceil(n / 8) + (i >> 3), so that one XCD takes a contiguous eighth of the pieces and the
+    // channel groups that share 128-byte lines of x (neighbours in the list) meet in one L2.  (The launch
+    // covers a multiple of 8 indices; the ones past the end leave.)
+    const int nblocks = p.parts * p.H * cgroups;
+    const int piece = (block & 7) * ((nblocks + 7) >> 3) + (block >> 3);
+    if (piece >= nblocks) return;
+    int b = piece;
     const int cg = b % cgroups; b /= cgroups;
     const int h = b % p.H;
     const int part = b / p.H;
@@ -179,7 +187,7 @@ __device__ __forceinline__ void fic_rows_body(const FicRowsParams &p, const int 
     for (int m = 32; m >= 1; m >>= 1) dot += __shfl_xor(dot, m, 64);
     if ((tid & 63) == 0) dsum[tid >> 6] = dot;
     __syncthreads();
-    if (tid == 0 && p.dotpart) p.dotpart[block] = dsum[0] + dsum[1] + dsum[2] + dsum[3];
+    if (tid == 0 && p.dotpart) p.dotpart[piece] = dsum[0] + dsum[1] + dsum[2] + dsum[3];
 }
 
 
