@@ -411,7 +411,7 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
         const int lead = (rows_blocks + 7) / 8 * 8;      // keeps the tiles' block index aligned to the 8 XCDs
         cp.y = y; cp.fic_ocs = partial; cp.fic_sum32 = !cp.inj_on && (long long)pl.crs * 4 * pl.wm * pl.wk * 16384 < (1LL << 31);
         cp.fic_wsum = wsum; cp.fic_xrows = xrows; cp.fic_dotpart = dotpart;
-        cp.fic_parts = lay.xrows_parts; cp.fic_rows_blocks = rows_blocks; cp.fic_rows_lead = lead; cp.fic_from_rows = xsum_in ? 2 : (compute_xrows ? 0 : 1);
+        cp.fic_parts = lay.xrows_parts; cp.fic_rows_lead = lead; cp.fic_from_rows = xsum_in ? 2 : (compute_xrows ? 0 : 1);
         cp.fic_xsum_in = xsum_in; cp.fic_xsum_next = xsum_next;
         if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
         // 1024-thread workgroups take a CU each, so every input checksum workgroup in front of them would push
@@ -660,7 +660,7 @@ abed_status_t abed_ic2_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
         // the partial output sums and compares.
         const int lead = compute_xrows ? (rows_blocks + 7) / 8 * 8 : 0;
         cp.y = y; cp.ic2_part = part;
-        cp.fic_xrows = xrows; cp.fic_parts = lay.xrows_parts; cp.fic_rows_blocks = compute_xrows ? rows_blocks : 0; cp.fic_rows_lead = lead;
+        cp.fic_xrows = xrows; cp.fic_parts = lay.xrows_parts; cp.fic_rows_lead = lead;
         if (epi) { cp.scale = epi->scale; cp.bias = epi->bias; cp.relu = epi->relu; cp.out_int8 = 1; }
         const int kg = (pl.kg == 4 && lead > 0) ? 2 : pl.kg;     // as in abed_fic_conv_int8
         if (!launch_conv(false, pl.wm, pl.wk, kg, cp, lead + grid, st)) return ABED_EUNSUPPORTED;

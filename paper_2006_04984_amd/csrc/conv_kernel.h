@@ -92,15 +92,16 @@ struct ConvParams {
     int dbg;          // timing experiments (builds with ABED_ENABLE_DBG only): bit 0 ends the kernel before its stores, bit 1 skips the main loop
     int out_fp32;      // fp16 path: 1 = fp32 output
     float rtol, atol;  // fp16 path: threshold of the checks
-    // FIC scheme (Sec. 3.3).  fic_ocs: per-tile sums of all accumulators [ntiles], or null.  With
-    // fic_rows_blocks > 0 the first fic_rows_lead (= that count rounded up to a multiple of 8)
-    // workgroups of the launch make the input checksum and its partial dot products instead of
-    // a tile; they depend on nothing the tiles produce and nothing waits for them inside the launch.
+    // FIC scheme (Sec. 3.3).  fic_ocs: per-tile sums of all accumulators [ntiles], or null.  The first
+    // fic_rows_lead workgroups of the launch (the number of pieces of the input checksum, fic_parts * H *
+    // ceil(C / 64), rounded up to a multiple of 8; 0 = none) make the input checksum and its partial dot
+    // products instead of a tile; they depend on nothing the tiles produce and nothing waits for them
+    // inside the launch.
     long long *fic_ocs;
     const int32_t *fic_wsum;       // filter checksum [R][S][C]
     int32_t *fic_xrows;            // row-wise input checksum [fic_parts][H][S][C]
-    long long *fic_dotpart;        // [fic_rows_blocks]
-    int fic_parts, fic_rows_blocks, fic_rows_lead, fic_from_rows;
+    long long *fic_dotpart;        // one per piece of the input checksum (in-loop input side: one per (pixel group, batch tile))
+    int fic_parts, fic_rows_lead, fic_from_rows;
     int32_t *fic_xsum_in;          // batch-summed input image [H][W][C] handed over by the previous layer (fic_from_rows == 2)
     int32_t *fic_xsum_next;        // batch sum of this layer's int8 output [P][Q][K], added to (must start at zero), or null
     // FIC with the input side formed in the main loop (int8): fic_wdig = three balanced base-256 digits of the
