@@ -734,7 +734,9 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     const bool want_next = p.mode == MODE_CHECK_NEXT && p.out_int8 && p.xchk_next != nullptr;
     const long long tile = ((long long)pg * p.grid_b + nt) * p.grid_n + kt;
 
-    // (1) accumulator fault injection (tests)
+    // (1) accumulator fault injection (tests).  inj_fix: what the 32-bit sum of the faulty accumulator's group
+    // of four loses when it wraps (a multiple of 2^32), so that the FIC output sum below stays exact for any bit.
+    long long inj_fix = 0;
     if (p.inj_on && pg == p.inj_pg && nt == p.inj_nt && kt == p.inj_kt) {
 #pragma unroll
         for (int i = 0; i < WM; ++i)
@@ -742,8 +744,11 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             for (int kb = 0; kb < WK; ++kb)
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
-                    if (wave * WM + i == p.inj_mb && kb == p.inj_kb && v == p.inj_v && lane == p.inj_lane)
+                    if (wave * WM + i == p.inj_mb && kb == p.inj_kb && v == p.inj_v && lane == p.inj_lane) {
                         acc[i][kb][v] ^= (int)p.inj_mask;
+                        const long long g = (long long)acc[i][kb][0] + acc[i][kb][1] + acc[i][kb][2] + acc[i][kb][3];
+                        inj_fix = g - (long long)(int)(unsigned)g;
+                    }
     }
 
     // (1b) FIC scheme (Sec. 3.3): output fmap checksum = the sum of all accumulators, in 64 bits
@@ -761,7 +766,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 t32 += (acc[i][kb][0] + acc[i][kb][1]) + (acc[i][kb][2] + acc[i][kb][3]);
                 if (!p.fic_sum32) { t += t32; t32 = 0; }         // scalar branch
             }
-        t += t32;
+        t += t32 + inj_fix;
         // the workgroup's output sum and, for the in-loop input side, its dot product
         long long *e64 = reinterpret_cast<long long *>(e_misc + 16);   // [0..3] output sums, [4..7] dot products of the waves
         for (int m = 32; m >= 1; m >>= 1) t += __shfl_xor(t, m, 64);

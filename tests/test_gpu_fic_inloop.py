@@ -185,3 +185,42 @@ def test_errors():
     big = dataclasses.replace(s, C=1024)     # 9216 elements along the reduction axis: the digits do not fit beside the tile
     with pytest.raises(abed.AbedError):
         abed.fic_inloop_get_layout(abed.desc_from_shape(big))
+
+
+def _random_shape(seed):
+    rng = np.random.default_rng(seed)
+    while True:
+        R, S = int(rng.choice([1, 2, 3, 5])), int(rng.choice([1, 2, 3, 5]))
+        sh, sw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        ph, pw = int(rng.integers(0, min(R, 3))), int(rng.integers(0, min(S, 3)))
+        H, W = int(rng.integers(1, 13)), int(rng.integers(1, 13))
+        if H + 2 * ph < R or W + 2 * pw < S:
+            continue
+        N = int(rng.choice([1, 2, 3, 5, 8, 13, 24, 33, 40]))
+        C = int(rng.choice([16, 32, 48, 64, 80, 128, 272]))
+        K = int(rng.choice([1, 7, 13, 16, 30, 32, 47, 48, 64, 77, 96, 130, 144, 272]))
+        return ConvShape(N, H, W, C, K, R, S, sh, sw, ph, pw, "rnd%d" % seed), bool(rng.integers(0, 2))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shape(oracle, seed):
+    """Seeded random shapes (extents that fit no tile size, both digit counts, both loader paths), int32 or int8
+    output: outputs and both scalars against the oracle, clean and with one accumulator flip."""
+    s, int8_out = _random_shape(seed)
+    print("case", seed, s, "int8_out", int8_out, flush=True)
+    x, w = int8_tensors(s, 9500 + seed)
+    epi = None
+    if int8_out:
+        scale, bias = requant_params(s, 9500 + seed)
+        epi = (scale, bias, bool(seed & 1))
+    ref = oracle.abed_fic_int8(x, w, s, epilog=epi)
+    g = GpuFicInloop(s, int8_out=int8_out)
+    g.prepare(w)
+    y, ocs, dot, flag = g.run(x, epilogue=epi)
+    assert np.array_equal(y, ref["out8"] if int8_out else ref["y"])
+    assert (ocs, dot, flag) == (ref["ocs"], ref["dot"], 0)
+    idx, bit = (s.N * s.P * s.Q * s.K) // 2, seed % 32
+    ref2 = oracle.abed_fic_int8(x, w, s, acc_flip=(idx, bit), epilog=epi)
+    y2, ocs2, dot2, flag2 = g.run(x, epilogue=epi, inject=(1, idx, bit))
+    assert np.array_equal(y2, ref2["out8"] if int8_out else ref2["y"])
+    assert (ocs2, dot2, flag2) == (ref2["ocs"], ref2["dot"], 1)
