@@ -273,7 +273,7 @@ abed_status_t abed_fic_input_checksum_int8(const abed_conv_desc_t *desc, int32_t
  * partial sums and compares.
  *   inject        site 1 (accumulator) for both variants; site 2 (stored ConvOut) for ABED_UNFUSED.
  * Errors as for abed_conv_int8; ABED_ERANGE if an input checksum entry could exceed int32
- * (128 * N*P*Q >= 2^31). */
+ * (128 * N*P*Q >= 2^31) or if R*S*C >= 32768 (the kernel adds four accumulators in 32 bits before it widens). */
 abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
                                  const int32_t *wsum, int32_t *xrows, int32_t compute_xrows,
                                  void *y, const abed_epilogue_t *epilogue, int32_t variant,
@@ -316,9 +316,9 @@ typedef struct {
 /* Value for abed_fic_verify's variants[] that names a layer run by abed_fic_inloop_conv_int8. */
 #define ABED_FIC_INLOOP 0x1000
 
-/* Host only.  ABED_ERANGE if the three digits or a lane's 32-bit sums could overflow (K > 32768, or a
- * reduction axis of several hundred thousand elements); ABED_EUNSUPPORTED if R*S*C > 8192 (the digits must
- * fit the LDS left beside the tile). */
+/* Host only.  ABED_ERANGE if the three digits or a lane's 32-bit sums could overflow (K > 32768, R*S*C >=
+ * 32768); ABED_EUNSUPPORTED if R*S*C exceeds about 8000 (the digits must fit the LDS left beside the tile:
+ * 3 * 64 * ceil(R*S*C / 64) bytes, rounded up to the tile's wave groups, at most 24 KB). */
 abed_status_t abed_fic_inloop_get_layout(const abed_conv_desc_t *desc, abed_fic_inloop_layout_t *out);
 
 /* Offline: the filter checksum wsum[r,s,c] = sum_k w[k,r,s,c] as three balanced base-256 digits,
