@@ -172,25 +172,19 @@ __device__ __forceinline__ int next_digit(int &s)
 }
 
 #if defined(__HIP_DEVICE_COMPILE__)
-// Sum of a 32-bit value over the 64 lanes of a wave with data-parallel-primitive adds (no LDS round
-// trips): shifts by 1, 2, 4, 8 inside each row of 16 lanes leave a row's sum in its lane 15, two row
-// broadcasts carry it into lane 63.  The values must be small enough that the sum fits 32 bits.
-__device__ __forceinline__ int wave_sum32(int v)
-{
-    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
-    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
-    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
-    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
-    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
-    return __builtin_amdgcn_readlane(v, 63);
-}
-// The same for a 64-bit value of magnitude below 2^58, as three limbs of 20, 20 and 24 bits.
+// Sum of a 64-bit integer (magnitude below 2^46) over the 64 lanes of a wave on the matrix unit, which is idle
+// in the epilogue: as doubles, exactly.  A 16x16x4 product of the lanes' values (A[i][k] = lane i + 16 k)
+// with a matrix of ones leaves the sum over k of row i in every column; a lane adds the four rows it holds,
+// and the same product once more adds the four groups of rows.  Every lane gets the total.  All lanes of the
+// wave must be active (matrix instructions ignore the execution mask).
 __device__ __forceinline__ long long wave_sum64(long long t)
 {
-    const int l0 = (int)(t & 0xfffff), l1 = (int)((t >> 20) & 0xfffff), l2 = (int)(t >> 40);
-    const long long s0 = wave_sum32(l0), s1 = wave_sum32(l1), s2 = wave_sum32(l2);
-    return s0 + (s1 << 20) + (s2 << 40);
+    typedef double f64x4 __attribute__((ext_vector_type(4)));
+    const f64x4 zero = {0.0, 0.0, 0.0, 0.0};
+    f64x4 d = __builtin_amdgcn_mfma_f64_16x16x4f64((double)t, 1.0, zero, 0, 0, 0);
+    const double rows = (d[0] + d[1]) + (d[2] + d[3]);
+    d = __builtin_amdgcn_mfma_f64_16x16x4f64(rows, 1.0, zero, 0, 0, 0);
+    return (long long)d[0];
 }
 #endif
 
@@ -769,11 +763,10 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         t += t32 + inj_fix;
         // the workgroup's output sum and, for the in-loop input side, its dot product
         long long *e64 = reinterpret_cast<long long *>(e_misc + 16);   // [0..3] output sums, [4..7] dot products of the waves
-        for (int m = 32; m >= 1; m >>= 1) t += __shfl_xor(t, m, 64);
+        t = wave_sum64(t);
         if (lane == 0) e64[wave] = t;
         if (fic_tile) {
-            long long d = fic_dot;
-            for (int m = 32; m >= 1; m >>= 1) d += __shfl_xor(d, m, 64);
+            const long long d = wave_sum64(fic_dot);
             if (lane == 0) e64[4 + wave] = d;
         }
         __syncthreads();
