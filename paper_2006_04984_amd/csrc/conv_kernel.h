@@ -203,7 +203,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     constexpr int L = (NB + 3) / 4;            // direct-to-LDS loads per wave and step
     constexpr int SUB = NB * 1024;              // one 64-byte step of the tile
     constexpr int STAGE = KG * SUB;
-    constexpr int EPI_BYTES = (F16 ? 8 : 4) * WK * 1024 + 128;
+    constexpr int EPI_BYTES = (F16 ? 8 : 4) * WK * 1024 + 128 + (F16 ? 0 : WK * 128);   // + misc words, + the tile's scale and bias
     constexpr int RED_BYTES = (KG - 1) * 4 * WM * WK * 1024;   // accumulators of groups 1..KG-1
     constexpr int FIC_BYTES = F16 ? 0 : kFicRowsLdsBytes;      // the input checksum workgroups of the FIC scheme
     constexpr int LDS_MIN0 = EPI_BYTES > RED_BYTES ? EPI_BYTES : RED_BYTES;
@@ -720,6 +720,17 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     int *e_ic = reinterpret_cast<int *>(lds);                 // [4 waves][WK][64 lanes][4]
     int *e_misc = e_ic + 4 * WK * 256;                        // [0] flag bits, [1] last for FC, [2] last for IC
     if (tid < 16) e_misc[tid] = 0;
+    // the epilog's per-filter scale and bias of this tile's filters, fetched once (zeros beyond K); the first
+    // barrier before their use publishes them
+    float *e_scale = reinterpret_cast<float *>(e_misc + 32), *e_bias = e_scale + WK * 16;
+    if (p.out_int8) {
+        for (int t = tid; t < 2 * WK * 16; t += 256) {
+            const int f = t < WK * 16 ? t : t - WK * 16;
+            const int k = kt * WK * 16 + f;
+            const float *src = t < WK * 16 ? p.scale : p.bias;
+            e_scale[t] = k < p.K ? src[k] : 0.f;
+        }
+    }
     uint32_t my_flag = 0;
     // a scheme that is not selected (d_f or d_i zero) has nothing to exchange
     const bool fc_local = p.grid_n == 1 || p.d_f == 0, ic_local = p.grid_b == 1 || p.d_i == 0;
@@ -901,10 +912,11 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 // loop (16 more live registers there cost more than these few operations)
                 const int k = (kt * WK + kb) * 16 + lg * 4;
                 float sc[4], bi[4];
+                {
+                    const f32x4 s4 = *reinterpret_cast<const f32x4 *>(e_scale + kb * 16 + lg * 4);
+                    const f32x4 b4 = *reinterpret_cast<const f32x4 *>(e_bias + kb * 16 + lg * 4);
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    sc[v] = (k + v < p.K) ? p.scale[k + v] : 0.f;
-                    bi[v] = (k + v < p.K) ? p.bias[k + v] : 0.f;
+                    for (int v = 0; v < 4; ++v) { sc[v] = s4[v]; bi[v] = b4[v]; }
                 }
 #pragma unroll
                 for (int i = 0; i < WM; ++i)
@@ -1032,10 +1044,11 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                 const int fb = kt * WK + kb;
                 const int k = fb * 16 + lg * 4;
                 float sc[4], bi[4];
+                {
+                    const f32x4 s4 = *reinterpret_cast<const f32x4 *>(e_scale + kb * 16 + lg * 4);
+                    const f32x4 b4 = *reinterpret_cast<const f32x4 *>(e_bias + kb * 16 + lg * 4);
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    sc[v] = (k + v < p.K) ? p.scale[k + v] : 0.f;
-                    bi[v] = (k + v < p.K) ? p.bias[k + v] : 0.f;
+                    for (int v = 0; v < 4; ++v) { sc[v] = s4[v]; bi[v] = b4[v]; }
                 }
 #pragma unroll
                 for (int il = 0; il < 4; ++il) {
