@@ -224,3 +224,32 @@ def test_random_shape(oracle, seed):
     y2, ocs2, dot2, flag2 = g.run(x, epilogue=epi, inject=(1, idx, bit))
     assert np.array_equal(y2, ref2["out8"] if int8_out else ref2["y"])
     assert (ocs2, dot2, flag2) == (ref2["ocs"], ref2["dot"], 1)
+
+
+def test_lane_sums_in_groups_of_four(oracle, monkeypatch):
+    """A tile shape and reduction axis for which a lane's accumulators no longer add up inside 32 bits
+    (R*S*C * 4*WM*WK * 2^14 >= 2^31): the output sum is then formed in groups of four.  Both FIC forms."""
+    import paper_2006_04984_amd as abed
+    from test_gpu_fic import GpuFic
+    monkeypatch.setenv("ABED_TILE_WM", "2")
+    monkeypatch.setenv("ABED_TILE_WK", "8")
+    monkeypatch.setenv("ABED_TILE_KG", "1")
+    s = ConvShape(16, 7, 7, 512, 256, 3, 3, 1, 1, 1, 1, "c512_k256_2x8_tiles")
+    x, w = int8_tensors(s, 7600)
+    ref = oracle.abed_fic_int8(x, w, s)
+    g = GpuFicInloop(s)
+    assert (abed.get_layout(g.desc, 0, 0).tile_batch, abed.get_layout(g.desc, 0, 0).tile_n) == (8, 128)
+    g.prepare(w)
+    y, ocs, dot, flag = g.run(x)
+    assert np.array_equal(y, ref["y"]) and (ocs, dot, flag) == (ref["ocs"], ref["dot"], 0)
+    r = GpuFic(s, 4)
+    r.prepare(w)
+    y, ocs, dot, flag = r.run(x)
+    assert np.array_equal(y, ref["y"]) and (ocs, dot, flag) == (ref["ocs"], ref["dot"], 0)
+    # the largest magnitudes: every product 16384
+    x[:] = -128
+    w[:] = -128
+    ref = oracle.abed_fic_int8(x, w, s)
+    g.prepare(w)
+    y, ocs, dot, flag = g.run(x)
+    assert np.array_equal(y, ref["y"]) and (ocs, dot, flag) == (ref["ocs"], ref["dot"], 0)
