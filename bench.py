@@ -299,7 +299,7 @@ def main():
             for s, (x, w) in zip(layers, ins):
                 abed_oracle.abed_int8(x, w, s)
             reps += 1
-            if time.perf_counter() - t0 > 10.0 or reps >= 50:
+            if time.perf_counter() - t0 > 10.0 or reps >= 200:
                 break
         dt = (time.perf_counter() - t0) / reps
         out["cpu_baseline"] = dict(value=total_ops / dt / 1e12, unit="TOPS", cores=abed_oracle.num_threads(),
