@@ -175,3 +175,24 @@ def test_packed_needs_one_buffer():
     with pytest.raises(abed.AbedError) as e:
         g.run(torch.zeros((s.N, s.H, s.W, s.C), dtype=torch.int8, device="cuda:0"))
     assert e.value.status == 1
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+def test_nine_wide_tiles_for_the_filter_checksum_alone(oracle, variant):
+    """256 filters + the block of checksum filters = 17 filter blocks: with a long reduction axis and a grid of
+    200 tiles or more the plan takes tiles 9 blocks wide (two filter tiles instead of five)."""
+    from gpu_helpers import GpuConv, flags_match
+    s = ConvShape(64, 14, 14, 128, 256, 3, 3, 1, 1, 1, 1, "n64_c128_k256_14x14")
+    x, w = int8_tensors(s, 6464)
+    ref = oracle.abed_int8(x, w, s)
+    g = GpuConv(s, variant | abed.ONLY_FC)
+    assert (g.lay.tile_batch, g.lay.tile_n, g.lay.grid_n) == (8, 144, 2)
+    g.prepare(w)
+    y, flags = g.run(x)
+    assert np.array_equal(y, ref["y"]) and not flags.any()
+    idx, bit = (s.N * s.P * s.Q * s.K) // 3 + 200, 30
+    ref = oracle.abed_int8(x, w, s, acc_flip=(idx, bit))
+    y, flags = g.run(x, inject=(1, idx, bit))
+    assert np.array_equal(y, ref["y"]) and flags_match(flags, ref, s, g.lay) and flags.any()
+    # the same shape with both schemes keeps its 4-wide tiles
+    assert abed.get_layout(g.desc, 0, variant).tile_n in (64, 80)
