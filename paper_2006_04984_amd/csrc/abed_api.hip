@@ -86,9 +86,14 @@ void choose_tile(Plan &pl)
     }
     // tiles 8 blocks wide and 8 entries deep read the activations half as often; they pay when the filter
     // blocks fill them exactly and the grid stays large (measured: 64->256 1x1 at 56x56, 256->256 3x3 at
-    // 14x14 with 128 images), and lose on small grids
+    // 14x14 with 128 images), and lose on small grids; with a long reduction axis one workgroup per CU is
+    // enough (512 -> 512 3x3 at 7x7 with 128 images: 39 -> 31 us)
     bool wide = false;
-    if (pl.n_fblk % 8 == 0 && (long long)((pl.PQ + 15) / 16) * ((pl.n_entries + 7) / 8) * (pl.n_fblk / 8) >= 384) { wk = 8; wide = true; }
+    {
+        const long long tiles8 = (long long)((pl.PQ + 15) / 16) * ((pl.n_entries + 7) / 8) * (pl.n_fblk / 8);
+        const int steps = (pl.crs * pl.esize + 63) / 64;
+        if (pl.n_fblk % 8 == 0 && (tiles8 >= 384 || (tiles8 >= 256 && steps >= 64))) { wk = 8; wide = true; }
+    }
     // Tiles 9 blocks wide, for the filter checksum alone on 256 or 512 filters: its one extra block makes 17 or
     // 33 filter blocks, which 4-wide tiles split 5 or 9 ways and 9-wide tiles 2 or 4 ways, so the activations
     // are read that much less often.  Measured on the ResNet-50 layers at N = 64 and 128: -10 ... -27 % where the
