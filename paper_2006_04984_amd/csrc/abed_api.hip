@@ -112,6 +112,12 @@ void choose_tile(Plan &pl)
     // most CUs a workgroup; failing that, the smallest
     for (int c : cand)
         if (tiles(c) >= 384 && 5 * waste(c) <= pl.n_entries && (!wm || waste(c) < waste(wm))) wm = c;
+    // (the plain problem, with no exchange between tiles, rather fills every CU with a smaller tile than three
+    // quarters of them with a larger one: 2048 -> 512 1x1 at 7x7 with 64 images, 14.2 -> 12.5 us)
+    const bool plain = pl.variant == ABED_NONE || pl.variant == ABED_DUPLICATE;
+    if (!wm && plain)
+        for (int c : cand)
+            if (!wm && tiles(c) >= 256 && 5 * waste(c) <= pl.n_entries) wm = c;
     if (!wm)
         for (int c : cand)
             if (!wm && tiles(c) >= 160 && 5 * waste(c) <= pl.n_entries) wm = c;
