@@ -98,14 +98,24 @@ void choose_tile(Plan &pl)
         const int steps = (pl.crs * pl.esize + 63) / 64;
         if (pl.n_fblk % 8 == 0 && (tiles8 >= 384 || (tiles8 >= 256 && steps >= 64))) { wk = 8; wide = true; }
     }
-    // Tiles 9 blocks wide, for the filter checksum alone on 256 or 512 filters: its one extra block makes 17 or
-    // 33 filter blocks, which 4-wide tiles split 5 or 9 ways and 9-wide tiles 2 or 4 ways, so the activations
-    // are read that much less often.  Measured on the ResNet-50 layers at N = 64 and 128: -10 ... -27 % where the
-    // reduction axis is long and at least 200 tiles remain (3x3 layers at 28x28 to 7x7, 1x1 layers with 1024
-    // or more channels), slower on short reduction axes and on smaller grids (all of N = 32).
+    // Tiles 9 blocks wide (and 8 entries deep) for the filter checksum alone, whose digit block makes the
+    // filter blocks 8 m + 1:
+    //  - 128 filters + digit block = 9: one filter tile, so the FC residual stays inside the tile and the
+    //    activations are read once (128 -> 128 3x3 at 28x28: -20 / -13 / -8 % at N = 64 / 128 / 256, 512 -> 128 1x1 at
+    //    28x28 and N = 64: +26 % -> +4 % over the unchecked layer; slower at N = 32, and no gain with both schemes
+    //    on the ResNet-50 layers);
+    //  - 256 or 512 filters (17 or 33 blocks, which 4- and 5-wide tiles split 5 or 7 ways and 9-wide tiles 2 or
+    //    4 ways): -10 ... -27 % on the ResNet-50 layers at N = 64 and 128 where the reduction axis is long and at
+    //    least 200 tiles remain, slower on short axes and smaller grids.
     const int pad9 = (pl.n_fblk + 8) / 9 * 9;
-    if (!wide && pl.esize == 1 && pl.d_f > 0 && pl.d_i == 0 && !pl.packed && pl.n_fblk >= 17 && pad9 - pl.n_fblk <= 3 &&
-        pl.crs >= 1024 && (long long)((pl.PQ + 15) / 16) * ((pl.n_entries + 7) / 8) * (pad9 / 9) >= 200) { wk = 9; wide = true; }
+    if (!wide && pl.esize == 1 && pl.n_fblk > pl.kblk && !pl.packed) {
+        const long long tiles9 = (long long)((pl.PQ + 15) / 16) * ((pl.n_entries + 7) / 8) * (pad9 / 9);
+        const bool fc_alone = pl.d_i == 0;
+        bool nine = false;
+        if (fc_alone && pl.n_fblk == 9) nine = tiles9 >= 384;
+        else if (fc_alone && pl.n_fblk >= 17 && pad9 - pl.n_fblk <= 3 && pl.crs >= 1024) nine = tiles9 >= 200;
+        if (nine) { wk = 9; wide = true; }
+    }
     const int grid_m = (pl.PQ + 15) / 16, grid_n = (pl.n_fblk + wk - 1) / wk;
     auto tiles = [&](int wm) { return (long long)grid_m * ((pl.n_entries + 4 * wm - 1) / (4 * wm)) * grid_n; };
     auto waste = [&](int wm) { const int mb = 4 * wm; return (pl.n_entries + mb - 1) / mb * mb - pl.n_entries; };
