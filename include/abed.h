@@ -50,7 +50,8 @@ typedef enum {
     ABED_EUNSUPPORTED = 2,  /* valid convolution outside the implemented shape set    */
     ABED_EWORKSPACE = 3,    /* workspace smaller than abed_get_layout() reports        */
     ABED_EHIP = 4,          /* a HIP call failed (see abed_last_hip_error)             */
-    ABED_ERANGE = 5         /* a checksum would need more than four digits (Sec. 4.1)  */
+    ABED_ERANGE = 5         /* a checksum would need more than four digits (Sec. 4.1), or a
+                               scheme's exact-arithmetic bound is exceeded (see its entry point) */
 } abed_status_t;
 
 /* Implementation options (Sec. 4.3).  All checked variants give the same
