@@ -96,7 +96,8 @@ void choose_tile(Plan &pl)
     {
         const long long tiles8 = (long long)((pl.PQ + 15) / 16) * ((pl.n_entries + 7) / 8) * (pl.n_fblk / 8);
         const int steps = (pl.crs * pl.esize + 63) / 64;
-        if (pl.n_fblk % 8 == 0 && (tiles8 >= 384 || (tiles8 >= 256 && steps >= 64))) { wk = 8; wide = true; }
+        const bool plain_problem = pl.variant == ABED_NONE || pl.variant == ABED_DUPLICATE;   // (measured there only)
+        if (pl.n_fblk % 8 == 0 && (tiles8 >= 384 || (plain_problem && tiles8 >= 256 && steps >= 64))) { wk = 8; wide = true; }
     }
     // Tiles 9 blocks wide (and 8 entries deep) for the filter checksum alone, whose digit block makes the
     // filter blocks 8 m + 1:
