@@ -148,3 +148,33 @@ def test_fic_inloop_layout_and_limits(L):
     with pytest.raises(AbedError) as e:      # three digits hold the filter checksum up to K = 32768
         abed.fic_inloop_get_layout(abed.desc_from_shape(dataclasses.replace(s, K=32768 + 16)))
     assert e.value.status in (2, 5)      # the tile plan may refuse such a filter count first
+
+
+def test_tile_plan_rules(L):
+    """The tile plan for shapes the rules were measured on (entries per tile, filters per tile)."""
+    from synth import ConvShape
+
+    def tile(shape, variant):
+        lay = abed.get_layout(abed.desc_from_shape(ConvShape(*shape, "plan")), 0, variant)
+        return lay.tile_batch, lay.tile_n
+
+    FC, IC = abed.ONLY_FC, abed.ONLY_IC
+    # the benchmark's layers at N = 32: checked and unchecked
+    assert [tile(tuple(getattr(s, f) for f in ("N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w")), 4)
+            for s in CONFIG2] == [(12, 80), (8, 80), (12, 64), (8, 64)]
+    assert [tile(tuple(getattr(s, f) for f in ("N", "H", "W", "C", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w")), 0)
+            for s in CONFIG2] == [(8, 64), (8, 64), (8, 64), (4, 64)]
+    # 256 filters + the digit block: 9-wide tiles for the filter checksum alone on a long reduction axis, not with both schemes
+    s = (128, 14, 14, 256, 256, 3, 3, 1, 1, 1, 1)
+    assert tile(s, 4 | FC) == (8, 144) and tile(s, 4) == (12, 64) and tile(s, 0) == (8, 128)
+    # ... and not at N = 32 (too few tiles)
+    assert tile((32, 14, 14, 256, 256, 3, 3, 1, 1, 1, 1), 4 | FC)[1] == 64
+    # 128 filters + the digit block = 9 blocks: one filter tile for the filter checksum alone from 384 tiles on
+    assert tile((64, 28, 28, 512, 128, 1, 1, 1, 1, 0, 0), 4 | FC) == (8, 144)
+    assert tile((32, 28, 28, 128, 128, 3, 3, 1, 1, 1, 1), 4 | FC) == (8, 80)
+    # 512 filters at 7x7 with 128 images: 8-wide tiles for the plain problem from 256 tiles on (long reduction axis),
+    # 5-wide tiles (33 blocks in 7 tiles) with both schemes, 4-wide for the batch checksum alone
+    s = (128, 7, 7, 512, 512, 3, 3, 1, 1, 1, 1)
+    assert tile(s, 0) == (8, 128) and tile(s, 4) == (8, 80) and tile(s, 4 | IC) == (8, 64)
+    # a plain problem on a small grid takes the largest tile that still gives every CU a workgroup
+    assert tile((64, 7, 7, 2048, 512, 1, 1, 1, 1, 0, 0), 0) == (8, 64)
