@@ -163,6 +163,15 @@ __device__ __forceinline__ i32x4 ld_dev4(const __amdgpu_buffer_rsrc_t rs, int by
 }
 #endif
 
+#if defined(__HIP_DEVICE_COMPILE__)
+// OR of the three flag bits over the lanes of a wave
+__device__ __forceinline__ uint32_t wave_or3(uint32_t f)
+{
+    return (__builtin_amdgcn_ballot_w64((f & 1u) != 0) ? 1u : 0u) | (__builtin_amdgcn_ballot_w64((f & 2u) != 0) ? 2u : 0u) |
+           (__builtin_amdgcn_ballot_w64((f & 4u) != 0) ? 4u : 0u);
+}
+#endif
+
 // balanced base-256 digit (same rule as the ICG kernel)
 __device__ __forceinline__ int next_digit(int &s)
 {
@@ -540,7 +549,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         const bool pvalid = pix < PQ;
         float *e_ic = reinterpret_cast<float *>(lds);            // [2][4 waves][WK][64 lanes][4]: sums, checksum values
         int *e_misc = reinterpret_cast<int *>(e_ic + 8 * WK * 256);
-        if (tid < 16) e_misc[tid] = 0;
+        if (tid < 4) e_misc[tid] = 0;     // [1], [2]: "last arriver" marks, read after later barriers
         uint32_t my_flag = 0;
         // a scheme that is not selected (d_f or d_i zero) has nothing to exchange
         const bool fc_local = p.grid_n == 1 || p.d_f == 0, ic_local = p.grid_b == 1 || p.d_i == 0;
@@ -632,9 +641,13 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             if (checking) {
                 // (4) flags of this tile; when sums span several tiles, count this tile's arrival (the
                 // answer is picked up after the output stores have been issued)
-                if (my_flag) atomicOr(reinterpret_cast<unsigned *>(&e_misc[0]), my_flag);
+                // every wave leaves its bits in a word of its own (nothing to initialise, so no wave can wipe another's)
+                {
+                    const uint32_t wf = wave_or3(my_flag);
+                    if (lane == 0) e_misc[4 + wave] = (int)wf;
+                }
                 __syncthreads();
-                if (tid == 0) __hip_atomic_store(&p.flags[word], (uint32_t)e_misc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (tid == 0) __hip_atomic_store(&p.flags[word], (uint32_t)(e_misc[4] | e_misc[5] | e_misc[6] | e_misc[7]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (exchange) {
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                     __syncthreads();
@@ -719,7 +732,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     const bool pvalid = pix < PQ;
     int *e_ic = reinterpret_cast<int *>(lds);                 // [4 waves][WK][64 lanes][4]
     int *e_misc = e_ic + 4 * WK * 256;                        // [0] flag bits, [1] last for FC, [2] last for IC
-    if (tid < 16) e_misc[tid] = 0;
+    if (tid < 4) e_misc[tid] = 0;     // [1], [2]: "last arriver" marks, read after later barriers
     // the epilog's per-filter scale and bias of this tile's filters, fetched once (zeros beyond K); the first
     // barrier before their use publishes them
     float *e_scale = reinterpret_cast<float *>(e_misc + 32), *e_bias = e_scale + WK * 16;
@@ -984,9 +997,13 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     // after the output stores have been issued, which hides the round trip of the counter.
     const bool exchange = checking && !(fc_local && ic_local);
     auto arrive = [&]() {
-        if (my_flag) atomicOr(reinterpret_cast<unsigned *>(&e_misc[0]), my_flag);
+        // every wave leaves its bits in a word of its own (nothing to initialise, so no wave can wipe another's)
+        {
+            const uint32_t wf = wave_or3(my_flag);
+            if (lane == 0) e_misc[4 + wave] = (int)wf;
+        }
         __syncthreads();
-        if (tid == 0) __hip_atomic_store(&p.flags[tile], (uint32_t)e_misc[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_store(&p.flags[tile], (uint32_t)(e_misc[4] | e_misc[5] | e_misc[6] | e_misc[7]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (!exchange) return;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
