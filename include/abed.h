@@ -201,6 +201,22 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
                              void *workspace, size_t workspace_bytes,
                              const abed_inject_t *inject, void *y2, void *stream);
 
+/* abed_conv_int8 for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results, flags
+ * and errors as abed_conv_int8, without `workspace`: the scratch memory is an array of
+ * ABED_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends.  The call
+ * allocates and frees nothing.  A convolution whose layout reports workspace_bytes above
+ * ABED_STATIC_SCRATCH_BYTES (the variants that keep ConvOut in the workspace, very large grids) is
+ * refused with ABED_EWORKSPACE and nothing is enqueued.  All calls on one GPU share that GPU's array: the
+ * call clears what must start at zero itself (no abed_workspace_init), and calls that may overlap on
+ * one GPU (different streams, different threads) race - serialise them. */
+#define ABED_STATIC_SCRATCH_BYTES (16u << 20)
+abed_status_t abed_conv_int8_static(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+                                    const int8_t *wchk, int8_t *xchk, int32_t compute_xchk,
+                                    void *y, const abed_epilogue_t *epilogue, int32_t variant,
+                                    uint32_t *flags, int8_t *xchk_next,
+                                    const abed_inject_t *inject, void *y2, void *stream);
+
 /* Checked fp16 convolution (fp32 accumulation; Sec. 7).  As above with fp16
  * data; y is fp16 (out_fp32 == 0) or fp32.  A check fails when
  * |s - c| > rtol * max(|s|, |c|) + atol, s the reduction of the real

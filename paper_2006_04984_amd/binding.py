@@ -69,7 +69,7 @@ class Ic2Layout(ctypes.Structure):
 EXPORTS = ["abed_fic_inloop_get_layout", "abed_fic_inloop_filter_prepare_int8", "abed_fic_inloop_conv_int8", "abed_fic_verify", "abed_ic2_get_layout", "abed_ic2_conv_int8", "abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
            "abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_fp16",
            "abed_input_checksum_int8", "abed_input_checksum_fp16", "abed_workspace_init",
-           "abed_conv_int8", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error"]
+           "abed_conv_int8", "abed_conv_int8_static", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error"]
 
 
 def lib_path():
@@ -100,6 +100,8 @@ def lib():
         L.abed_workspace_init.argtypes = [vp, ctypes.c_size_t, vp]
         L.abed_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
                                      vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp, vp]
+        L.abed_conv_int8_static.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
+                                            vp, vp, ctypes.POINTER(_Inject), vp, vp]
         f32 = ctypes.c_float
         L.abed_filter_prepare_fp16.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
         L.abed_input_checksum_fp16.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
@@ -179,6 +181,19 @@ def conv_int8(desc, x, w, wchk, xchk, compute_xchk, y, variant, flags=None, epil
     _check(lib().abed_conv_int8(ctypes.byref(desc), _p(x), _p(w), _p(wchk), _p(xchk), int(bool(compute_xchk)),
                                 _p(y), epi, int(variant), _p(flags), _p(xchk_next), _p(workspace), nbytes,
                                 inj, _p(y2), _stream(stream)))
+
+
+def conv_int8_static(desc, x, w, wchk, xchk, compute_xchk, y, variant, flags=None, epilogue=None, xchk_next=None,
+                     inject=None, y2=None, stream=None):
+    """abed_conv_int8_static: abed_conv_int8 on the library's own per-GPU scratch array (no workspace)."""
+    epi = None
+    if epilogue is not None:
+        epi = ctypes.byref(_Epilogue(epilogue[0].data_ptr(), epilogue[1].data_ptr(), int(bool(epilogue[2]))))
+    inj = None
+    if inject is not None:
+        inj = ctypes.byref(_Inject(int(inject[0]), int(inject[1]), int(inject[2])))
+    _check(lib().abed_conv_int8_static(ctypes.byref(desc), _p(x), _p(w), _p(wchk), _p(xchk), int(bool(compute_xchk)),
+                                       _p(y), epi, int(variant), _p(flags), _p(xchk_next), inj, _p(y2), _stream(stream)))
 
 
 def filter_prepare_fp16(desc, w, wchk, stream=None):

@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <mutex>
 
 #include "../../include/abed.h"
 #include "aux_kernels.h"
@@ -14,7 +15,16 @@
 
 using namespace abed;
 
+// Scratch of the entry point that allocates nothing (abed_conv_int8_static): one array per GPU, held
+// until the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the device
+// address it yields (kept per device in g_scratch_ptr) is what kernels and fills get.
+static __device__ __align__(256) unsigned char scratch[ABED_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+const int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];       // device address of `scratch` on each GPU, or null until first use there
+std::mutex g_scratch_mutex;
 
 thread_local char g_hip_error[256] = "";
 
@@ -812,12 +822,17 @@ abed_status_t abed_input_checksum_fp16(const abed_conv_desc_t *desc, const void 
     return ABED_OK;
 }
 
-abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+}  // extern "C"
+
+namespace {
+
+// abed_conv_int8; with validate_only every check is made and nothing is enqueued
+abed_status_t conv_int8_impl(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
                              const int8_t *wchk, int8_t *xchk, int32_t compute_xchk,
                              void *y, const abed_epilogue_t *epi, int32_t variant,
                              uint32_t *flags, int8_t *xchk_next,
                              void *workspace, size_t workspace_bytes,
-                             const abed_inject_t *inject, void *y2, void *stream)
+                             const abed_inject_t *inject, void *y2, void *stream, bool validate_only)
 {
     hipStream_t st = (hipStream_t)stream;
     const bool int8_out = epi != nullptr;
@@ -846,6 +861,8 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
 
     if ((variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE) && ((size_t)desc->N + desc->K + 2) * 4 > 64 * 1024)
         return ABED_EUNSUPPORTED;                                     // the verify kernel keeps N + K sums in LDS
+    if (!tile_compiled(pl.wm, pl.wk, pl.kg)) return ABED_EUNSUPPORTED;   // before anything is enqueued
+    if (validate_only) return ABED_OK;
     if (checked && compute_xchk && pl.d_i) {
         s = abed_input_checksum_int8(desc, x, xchk, stream);
         if (s != ABED_OK) return s;
@@ -929,6 +946,61 @@ abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, cons
         LAUNCH_CHECK("finish_i8_kernel");
     }
     return ABED_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+abed_status_t abed_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+                             const int8_t *wchk, int8_t *xchk, int32_t compute_xchk,
+                             void *y, const abed_epilogue_t *epi, int32_t variant,
+                             uint32_t *flags, int8_t *xchk_next,
+                             void *workspace, size_t workspace_bytes,
+                             const abed_inject_t *inject, void *y2, void *stream)
+{
+    return conv_int8_impl(desc, x, w, wchk, xchk, compute_xchk, y, epi, variant, flags, xchk_next,
+                          workspace, workspace_bytes, inject, y2, stream, false);
+}
+
+abed_status_t abed_conv_int8_static(const abed_conv_desc_t *desc, const int8_t *x, const int8_t *w,
+                                    const int8_t *wchk, int8_t *xchk, int32_t compute_xchk,
+                                    void *y, const abed_epilogue_t *epi, int32_t variant,
+                                    uint32_t *flags, int8_t *xchk_next,
+                                    const abed_inject_t *inject, void *y2, void *stream)
+{
+    // sized as abed_get_layout reports it (the int8-output case, which needs the most)
+    Plan pl;
+    abed_status_t s = make_plan(desc, ABED_INT8, variant, true, pl);
+    if (s != ABED_OK) return s;
+    if (pl.ws_bytes > (long long)ABED_STATIC_SCRATCH_BYTES) return ABED_EWORKSPACE;
+    // this GPU's copy of the scratch array: looked up once per device, with that device current
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ABED_EUNSUPPORTED;
+    void *ptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void *sym = nullptr;
+            HIP_TRY(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+            if (!sym) return hip_fail(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+            g_scratch_ptr[dev] = sym;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    // every argument check before the first launch
+    s = conv_int8_impl(desc, x, w, wchk, xchk, compute_xchk, y, epi, variant, flags, xchk_next,
+                       ptr, (size_t)ABED_STATIC_SCRATCH_BYTES, inject, y2, stream, true);
+    if (s != ABED_OK) return s;
+    // The array keeps the previous call's contents; only the arrival counters at its start must be
+    // zero.  A fill kernel clears them (a memset node would not survive graph replays).
+    const long long cnt_bytes = pl.off_cnt_ic + align256((long long)pl.grid_m * pl.grid_n * 4);
+    const long long words = cnt_bytes / 4;
+    fill_u32_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>((uint32_t *)ptr, words, 0u);
+    LAUNCH_CHECK("fill_u32_kernel (static scratch)");
+    return abed_conv_int8(desc, x, w, wchk, xchk, compute_xchk, y, epi, variant, flags, xchk_next,
+                          ptr, (size_t)ABED_STATIC_SCRATCH_BYTES, inject, y2, stream);
 }
 
 abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const void *w,

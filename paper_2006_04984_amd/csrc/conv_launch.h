@@ -38,6 +38,16 @@ constexpr bool tile_ok(int wm, int wk, int kg)
     return regs <= 512 / kg && 2 * kg * nb * 1024 <= 160 * 1024 - 1024 && (kg - 1) * 4 * wm * wk * 1024 <= 160 * 1024 - 1024;
 }
 
+// Whether launch_conv has an instantiation for (wm, wk, kg)
+inline bool tile_compiled(int wm, int wk, int kg)
+{
+    bool a = false, b = false, c = false;
+    for (int v : kWmList) a |= v == wm;
+    for (int v : kWkList) b |= v == wk;
+    for (int v : kKgList) c |= v == kg;
+    return a && b && c && tile_ok(wm, wk, kg);
+}
+
 // Returns false if (wm, wk, kg) is not a compiled configuration.  dyn_lds: bytes of dynamic LDS behind the
 // kernel's own (the digits of the FIC scheme's in-loop input side), else 0.
 bool launch_conv(bool f16, int wm, int wk, int kg, const ConvParams &p, int grid, hipStream_t st, unsigned dyn_lds = 0);

@@ -178,3 +178,17 @@ def test_tile_plan_rules(L):
     assert tile(s, 0) == (8, 128) and tile(s, 4) == (8, 80) and tile(s, 4 | IC) == (8, 64)
     # a plain problem on a small grid takes the largest tile that still gives every CU a workgroup
     assert tile((64, 7, 7, 2048, 512, 1, 1, 1, 1, 0, 0), 0) == (8, 64)
+
+
+def test_static_scratch_entry_point_rejects_large_workspace(L):
+    """abed_conv_int8_static refuses, before anything touches a GPU, a convolution whose layout needs more
+    scratch than the library's array holds (the pointers are never used: the call must return first)."""
+    from synth.shapes import ConvShape
+    s = ConvShape(64, 56, 56, 64, 256, 1, 1, 1, 1, 0, 0, "too_big")
+    desc = abed.desc_from_shape(s)
+    lay = abed.get_layout(desc, 0, Variant.UNFUSED)
+    assert lay.workspace_bytes > 16 << 20
+    import ctypes
+    st = L.abed_conv_int8_static(ctypes.byref(desc), None, None, None, None, 1, None, None, int(Variant.UNFUSED),
+                                 None, None, None, None, None)
+    assert st == 3
