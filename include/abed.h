@@ -89,6 +89,21 @@ typedef enum {
  * w + K*R*S*C (else ABED_EINVAL).  Outputs and flags are those of the plain layout. */
 #define ABED_PACKED_FC 0x400
 
+/* Checksums local to a workgroup.  OR into ABED_FUSED_OCG (int8; with or without ABED_ONLY_FC / ABED_ONLY_IC):
+ * the schemes of Sec. 3.1 and Sec. 3.2 option 1 are applied per tile instead of per layer, so that no tile
+ * waits for another and no checksum tensor is made at run time:
+ *   - FC per filter tile: every tile of tile_n filters carries the d_f = 2 digit filters of ITS OWN filters'
+ *     sum; wchk is [grid_n][d_f][R][S][C], made offline by abed_filter_prepare_local_int8;
+ *   - IC per batch tile: every range of tile_batch images carries the d_i = 2 digit images of ITS OWN images'
+ *     sum, formed inside the convolution kernel from the inputs it stages (no input checksum kernel,
+ *     xchk and compute_xchk are ignored, no workspace).
+ * A tile is a box of 8x8 output pixels x tile_batch images x tile_n filters; flag word (box, batch tile,
+ * filter tile) = flags[(box * grid_b + tb) * grid_n + tn] with box = (p / 8) * ceil(Q / 8) + q / 8, and every
+ * bit is reported on the tile it was found in.  What is protected is what Table 1 (Sec. 3.4) lists for the
+ * schemes; outputs are those of every other variant.  Shapes: 3x3 filters, stride 1, C and K multiples of 64,
+ * C/64 in {1, 2, 4, 8} with the batch checksum; else ABED_EUNSUPPORTED. */
+#define ABED_LOCAL 0x800
+
 typedef enum { ABED_INT8 = 0, ABED_FP16 = 1 } abed_dtype_t;
 
 typedef struct {
@@ -138,6 +153,8 @@ typedef struct {
     int64_t wchk_bytes;    /* d_f * R*S*C elements                                           */
     int64_t xchk_bytes;    /* d_i * H*W*C elements                                           */
     int64_t xchk_next_bytes; /* d_i * P*Q*K elements (variant 5)                             */
+    int32_t tile_box;      /* 0: a tile's pixels are consecutive in p*Q + q; 8: a box of 8x8 pixels (ABED_LOCAL) */
+    int32_t local_checksums; /* 1: FC per filter tile, IC per batch tile, wchk is [grid_n][d_f][R][S][C]   */
 } abed_layout_t;
 
 /* Flag word of tile (tm, tb, tn) is flags[(tm * grid_b + tb) * grid_n + tn].
@@ -165,6 +182,11 @@ abed_status_t abed_filter_prepare_int8(const abed_conv_desc_t *desc, const int8_
                                        void *stream);
 abed_status_t abed_filter_prepare_fp16(const abed_conv_desc_t *desc, const void *w, void *wchk,
                                        void *stream);
+/* The offline step for a given variant: with ABED_LOCAL the checksum filters of every filter tile
+ * (wchk[grid_n][d_f][R][S][C], tile g = sum of filters g*tile_n .. (g+1)*tile_n - 1, split into digits as
+ * above; Sec. 3.1, 4.1, 4.2), else exactly abed_filter_prepare_int8. */
+abed_status_t abed_filter_prepare_local_int8(const abed_conv_desc_t *desc, int32_t variant, const int8_t *w,
+                                             int8_t *wchk, void *stream);
 
 /* Online input checksum generation, ICG (Sec. 3.2 option 1, Sec. 4.3): xsum =
  * sum_n x[n] in int32 (fp32), split into d_i digit images xchk[d_i][H][W][C]. */

@@ -29,6 +29,7 @@ class Variant(enum.IntEnum):
 ONLY_FC = 0x100
 ONLY_IC = 0x200
 PACKED_FC = 0x400   # checksum filters in the free rows of the last block of 16 filters (wchk must follow w)
+LOCAL = 0x800       # checksums local to a workgroup: FC per filter tile, IC per batch tile, formed inside the kernel
 
 
 class ConvDesc(ctypes.Structure):
@@ -48,7 +49,8 @@ class Layout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("tile_pixels", "tile_batch", "tile_n", "grid_m", "grid_b", "grid_n", "d_f", "d_i")] + \
                [(n, ctypes.c_int64) for n in
-                ("n_flag_words", "workspace_bytes", "wchk_bytes", "xchk_bytes", "xchk_next_bytes")]
+                ("n_flag_words", "workspace_bytes", "wchk_bytes", "xchk_bytes", "xchk_next_bytes")] + \
+               [("tile_box", ctypes.c_int32), ("local_checksums", ctypes.c_int32)]
 
 
 class FicLayout(ctypes.Structure):
@@ -67,7 +69,7 @@ class Ic2Layout(ctypes.Structure):
 
 
 EXPORTS = ["abed_fic_inloop_get_layout", "abed_fic_inloop_filter_prepare_int8", "abed_fic_inloop_conv_int8", "abed_fic_verify", "abed_ic2_get_layout", "abed_ic2_conv_int8", "abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
-           "abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_fp16",
+           "abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_local_int8", "abed_filter_prepare_fp16",
            "abed_input_checksum_int8", "abed_input_checksum_fp16", "abed_workspace_init",
            "abed_conv_int8", "abed_conv_int8_static", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error"]
 
@@ -97,6 +99,7 @@ def lib():
         L.abed_get_layout.argtypes = [ctypes.POINTER(ConvDesc), i32, i32, ctypes.POINTER(Layout)]
         L.abed_filter_prepare_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
         L.abed_input_checksum_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
+        L.abed_filter_prepare_local_int8.argtypes = [ctypes.POINTER(ConvDesc), i32, vp, vp, vp]
         L.abed_workspace_init.argtypes = [vp, ctypes.c_size_t, vp]
         L.abed_conv_int8.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
                                      vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp, vp]
@@ -156,6 +159,10 @@ def get_layout(desc, dtype=0, variant=Variant.FUSED_OCG):
 
 def filter_prepare_int8(desc, w, wchk, stream=None):
     _check(lib().abed_filter_prepare_int8(ctypes.byref(desc), _p(w), _p(wchk), _stream(stream)))
+
+
+def filter_prepare_local_int8(desc, variant, w, wchk, stream=None):
+    _check(lib().abed_filter_prepare_local_int8(ctypes.byref(desc), int(variant), _p(w), _p(wchk), _stream(stream)))
 
 
 def input_checksum_int8(desc, x, xchk, stream=None):

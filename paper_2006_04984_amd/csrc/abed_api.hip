@@ -12,6 +12,7 @@
 #include "fic_kernels.h"
 #include "ic2_kernels.h"
 #include "conv_launch.h"
+#include "conv_box_launch.h"
 
 using namespace abed;
 
@@ -271,6 +272,111 @@ void set_injection(ConvParams &cp, const abed_conv_desc_t *d, const Plan &pl, co
     cp.inj_mask = 1u << inject->bit;
 }
 
+// ---------------------------------------------------------------------------
+// The box kernel (conv_box_kernel.h): 3x3 stride-1 layers, checksums local to a workgroup
+// ---------------------------------------------------------------------------
+struct BoxPlan {
+    int P, Q, crs;
+    int fb, fbr, xch;          // filter blocks per tile incl. the digit block, real ones, chunks of the batch checksum (0 = none)
+    bool fc, ic;
+    int boxes_x, boxes_y, grid_n, nranges, range_len;
+};
+
+// Shapes the box kernel takes: 3x3, stride 1, padding below 3, channels in chunks of 64, filters in tiles of 64.
+bool box_shape_ok(const abed_conv_desc_t *d)
+{
+    if (d->R != 3 || d->S != 3 || d->stride_h != 1 || d->stride_w != 1 || d->pad_h > 2 || d->pad_w > 2) return false;
+    if (d->C % 64 != 0 || d->K % 64 != 0) return false;
+    const long long P = d->H + 2 * d->pad_h - 2, Q = d->W + 2 * d->pad_w - 2;
+    if (P < 1 || Q < 1) return false;
+    // 32-bit byte offsets, with room for a batch that runs up to 7 entries past N
+    if ((long long)(d->N + 8) * d->H * d->W * d->C >= 0x7ffffff0LL) return false;
+    if ((long long)d->N * P * Q * d->K * 4 >= 0x7ffffff0LL) return false;
+    if ((long long)d->K * 9 * d->C >= 0x7ffffff0LL) return false;
+    return true;
+}
+
+// want_fc / want_ic: which checksums ride along (both false: the unchecked kernel)
+abed_status_t make_box_plan(const abed_conv_desc_t *d, bool want_fc, bool want_ic, BoxPlan &bp)
+{
+    if (!box_shape_ok(d)) return ABED_EUNSUPPORTED;
+    bp.P = d->H + 2 * d->pad_h - 2; bp.Q = d->W + 2 * d->pad_w - 2; bp.crs = 9 * d->C;
+    bp.fc = want_fc; bp.ic = want_ic;
+    const int nch = d->C / 64;
+    bp.xch = want_ic ? nch : 0;
+    bp.boxes_x = (bp.Q + 7) / 8; bp.boxes_y = (bp.P + 7) / 8;
+    const int nboxes = bp.boxes_x * bp.boxes_y;
+    bp.fbr = 4;
+    // the unchecked kernel takes 128 filters per tile where that still leaves a workgroup for every CU
+    if (!want_fc && !want_ic && d->K % 128 == 0 && (long long)nboxes * (d->K / 128) * ((d->N + 7) / 8) >= 256) bp.fbr = 8;
+    bp.fbr = env_int("ABED_BOX_FBR", bp.fbr);
+    if (bp.fbr != 4 && bp.fbr != 8) return ABED_EUNSUPPORTED;
+    if (d->K % (16 * bp.fbr) != 0) return ABED_EUNSUPPORTED;
+    bp.fb = bp.fbr + (want_fc ? 1 : 0);
+    bp.grid_n = d->K / (16 * bp.fbr);
+    if (!box_compiled(bp.fb, want_fc, bp.xch)) return ABED_EUNSUPPORTED;
+    // Entry ranges: a range is a whole number of batches of 8 (at most 256 entries: the checksum's 16-bit
+    // fields and two digits).  Longer ranges make the digit batch cheaper (it costs about half a batch),
+    // shorter ones fill the chip; pick the best product of the two.
+    const long long base = (long long)nboxes * bp.grid_n;
+    int best_len = 8; double best = -1.0;
+    for (int len = 8; len <= 256; len += 8) {
+        const int nr = (d->N + len - 1) / len;
+        const long long tiles = base * nr;
+        const double fill = (double)tiles / (256.0 * (double)((tiles + 255) / 256));
+        const double nb = len / 8.0;
+        const double score = fill * (want_ic ? nb / (nb + 0.5) : 1.0) * (1.0 - 0.02 / nb);
+        if (score > best + 1e-9) { best = score; best_len = len; }
+        if (len >= d->N) break;
+    }
+    bp.range_len = env_int("ABED_BOX_RANGE", best_len);
+    if (bp.range_len < 8 || bp.range_len > 256 || bp.range_len % 8 != 0) return ABED_EUNSUPPORTED;
+    bp.nranges = (d->N + bp.range_len - 1) / bp.range_len;
+    return ABED_OK;
+}
+
+abed_status_t launch_box_conv(const abed_conv_desc_t *d, const BoxPlan &bp, const int8_t *x, const int8_t *w, const int8_t *wchk,
+                              void *y, const abed_epilogue_t *epi, uint32_t *flags, const abed_inject_t *inject, hipStream_t st)
+{
+    BoxParams p;
+    memset(&p, 0, sizeof(p));
+    p.x = x; p.w = w; p.wchk = wchk; p.y = y; p.flags = flags;
+    if (epi) { p.scale = epi->scale; p.bias = epi->bias; p.relu = epi->relu; p.out_int8 = 1; }
+    p.N = d->N; p.H = d->H; p.W = d->W; p.C = d->C; p.K = d->K; p.P = bp.P; p.Q = bp.Q; p.ph = d->pad_h; p.pw = d->pad_w;
+    p.crsb = bp.crs; p.nch = d->C / 64;
+    p.boxes_x = bp.boxes_x; p.boxes_y = bp.boxes_y; p.grid_n = bp.grid_n; p.nranges = bp.nranges; p.range_len = bp.range_len;
+    if (inject && inject->site == 1) {
+        const long long k = inject->index % d->K, row = inject->index / d->K;
+        const int n = (int)(row / (bp.P * bp.Q)), pix = (int)(row % (bp.P * bp.Q));
+        const int oy = pix / bp.Q, ox = pix % bp.Q;
+        const int tile_n = 16 * bp.fbr, rel = n % bp.range_len;
+        p.inj_on = 1;
+        p.inj_box = (oy / 8) * bp.boxes_x + ox / 8; p.inj_range = n / bp.range_len; p.inj_kt = (int)(k / tile_n);
+        p.inj_batch = rel / 8;
+        const int pgrp = ((oy % 8) / 4) * 2 + (ox % 8) / 4, eh = (rel % 8) / 4;
+        p.inj_wave = pgrp * 2 + eh; p.inj_i = rel % 4;
+        p.inj_fb = (int)((k % tile_n) / 16);
+        p.inj_lane = (int)((k % 16) / 4) * 16 + (oy % 4) * 4 + ox % 4; p.inj_v = (int)(k % 4);
+        p.inj_mask = 1u << inject->bit;
+    }
+    const int tiles = bp.boxes_x * bp.boxes_y * bp.nranges * bp.grid_n;
+    if (!launch_box(bp.fb, bp.fc, bp.xch, p, (tiles + 7) / 8 * 8, st)) return ABED_EUNSUPPORTED;
+    LAUNCH_CHECK("box_conv_kernel");
+    return ABED_OK;
+}
+
+// Whether the unchecked convolution should take the box kernel: shapes it covers, with enough boxes to
+// give most CUs a workgroup (ABED_BOX=0/1 overrides, for tests and sweeps).
+bool box_preferred_plain(const abed_conv_desc_t *d)
+{
+    const int forced = env_int("ABED_BOX", -1);
+    if (forced == 0 || !box_shape_ok(d)) return false;
+    if (forced == 1) return true;
+    const long long P = d->H + 2 * d->pad_h - 2, Q = d->W + 2 * d->pad_w - 2;
+    const long long tiles = ((P + 7) / 8) * ((Q + 7) / 8) * (d->K / 64) * ((d->N + 7) / 8);
+    return tiles >= 128;
+}
+
 // An unchecked convolution with its own tile plan (the baseline, and the checksum
 // convolutions of the unfused variant).
 abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_t *w, void *y,
@@ -279,6 +385,10 @@ abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_
     Plan pl;
     abed_status_t s = make_plan(d, ABED_INT8, ABED_NONE, false, pl);
     if (s != ABED_OK) return s;
+    if (box_preferred_plain(d)) {
+        BoxPlan bp;
+        if (make_box_plan(d, false, false, bp) == ABED_OK) return launch_box_conv(d, bp, x, w, nullptr, y, epi, nullptr, inject, st);
+    }
     ConvParams cp;
     fill_params(cp, d, pl);
     cp.x = x; cp.w = w; cp.y = y; cp.mode = MODE_PLAIN;
@@ -745,9 +855,24 @@ abed_status_t abed_get_layout(const abed_conv_desc_t *desc, int32_t dtype, int32
     if (!out) return ABED_EINVAL;
     Plan pl;
     // the workspace is sized for the int8-output case, which needs the most
-    abed_status_t s = make_plan(desc, dtype, variant, true, pl);
+    abed_status_t s = make_plan(desc, dtype, variant & ~ABED_LOCAL, true, pl);
     if (s != ABED_OK) return s;
     memset(out, 0, sizeof(*out));
+    if (variant & ABED_LOCAL) {
+        if (dtype != ABED_INT8 || pl.variant != ABED_FUSED_OCG) return ABED_EUNSUPPORTED;
+        BoxPlan bp;
+        if ((s = make_box_plan(desc, pl.d_f > 0, pl.d_i > 0, bp)) != ABED_OK) return s;
+        out->tile_pixels = 64; out->tile_box = 8;
+        out->tile_batch = bp.range_len; out->tile_n = 16 * bp.fbr;
+        out->grid_m = bp.boxes_x * bp.boxes_y; out->grid_b = bp.nranges; out->grid_n = bp.grid_n;
+        out->d_f = bp.fc ? 2 : 0; out->d_i = bp.ic ? 2 : 0;
+        out->n_flag_words = (long long)out->grid_m * out->grid_b * out->grid_n;
+        out->workspace_bytes = 0;
+        out->wchk_bytes = (long long)out->d_f * bp.grid_n * bp.crs;
+        out->xchk_bytes = 0; out->xchk_next_bytes = 0;
+        out->local_checksums = 1;
+        return ABED_OK;
+    }
     out->tile_pixels = 16;
     out->tile_batch = pl.mb;
     out->tile_n = 16 * pl.wk;
@@ -782,6 +907,23 @@ abed_status_t abed_filter_prepare_int8(const abed_conv_desc_t *desc, const int8_
     if (!w || !wchk) return ABED_EINVAL;
     filter_checksum_i8_kernel<<<dim3((pl.crs + 63) / 64), dim3(1024), 0, (hipStream_t)stream>>>(w, wchk, desc->K, pl.crs, pl.d_f);
     LAUNCH_CHECK("filter_checksum_i8_kernel");
+    return ABED_OK;
+}
+
+abed_status_t abed_filter_prepare_local_int8(const abed_conv_desc_t *desc, int32_t variant, const int8_t *w, int8_t *wchk, void *stream)
+{
+    abed_layout_t lay;
+    abed_status_t s = abed_get_layout(desc, ABED_INT8, variant, &lay);
+    if (s != ABED_OK) return s;
+    if (!lay.local_checksums) return abed_filter_prepare_int8(desc, w, wchk, stream);
+    if (lay.d_f == 0) return ABED_OK;
+    if (!w || !wchk) return ABED_EINVAL;
+    const int crs = 9 * desc->C;
+    for (int g = 0; g < lay.grid_n; ++g) {
+        filter_checksum_i8_kernel<<<dim3((crs + 63) / 64), dim3(1024), 0, (hipStream_t)stream>>>(
+            w + (long long)g * lay.tile_n * crs, wchk + (long long)g * lay.d_f * crs, lay.tile_n, crs, lay.d_f);
+        LAUNCH_CHECK("filter_checksum_i8_kernel (per filter tile)");
+    }
     return ABED_OK;
 }
 
@@ -836,12 +978,26 @@ abed_status_t conv_int8_impl(const abed_conv_desc_t *desc, const int8_t *x, cons
 {
     hipStream_t st = (hipStream_t)stream;
     const bool int8_out = epi != nullptr;
+    const bool local = (variant & ABED_LOCAL) != 0;
     Plan pl;
-    abed_status_t s = make_plan(desc, ABED_INT8, variant, int8_out, pl);
+    abed_status_t s = make_plan(desc, ABED_INT8, variant & ~ABED_LOCAL, int8_out, pl);
     if (s != ABED_OK) return s;
     variant = pl.variant;                       // scheme selection is in pl.d_f / pl.d_i from here on
     if (!x || !w || !y) return ABED_EINVAL;
     if (int8_out && (!epi->scale || !epi->bias)) return ABED_EINVAL;
+    if (local) {
+        // checksums local to a workgroup: one launch, no workspace, no checksum images in memory
+        if (variant != ABED_FUSED_OCG) return ABED_EUNSUPPORTED;
+        BoxPlan bp;
+        if ((s = make_box_plan(desc, pl.d_f > 0, pl.d_i > 0, bp)) != ABED_OK) return s;
+        if ((bp.fc && !wchk) || !flags) return ABED_EINVAL;
+        if (inject && inject->site != 0) {
+            if (inject->site != 1) return inject->site == 2 ? ABED_EUNSUPPORTED : ABED_EINVAL;
+            if (inject->index < 0 || inject->index >= (long long)desc->N * bp.P * bp.Q * desc->K || inject->bit < 0 || inject->bit > 31) return ABED_EINVAL;
+        }
+        if (validate_only) return ABED_OK;
+        return launch_box_conv(desc, bp, x, w, wchk, y, epi, flags, inject, st);
+    }
     const bool checked = variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG;
     if (checked && ((pl.d_f && !wchk) || (pl.d_i && !xchk) || !flags)) return ABED_EINVAL;
     if (pl.packed && wchk != w + (long long)desc->K * pl.crs) return ABED_EINVAL;   // the digit filters must follow w in memory
@@ -969,6 +1125,9 @@ abed_status_t abed_conv_int8_static(const abed_conv_desc_t *desc, const int8_t *
                                     uint32_t *flags, int8_t *xchk_next,
                                     const abed_inject_t *inject, void *y2, void *stream)
 {
+    // the variants with checksums local to a workgroup use no scratch memory at all
+    if (variant & ABED_LOCAL)
+        return conv_int8_impl(desc, x, w, wchk, xchk, compute_xchk, y, epi, variant, flags, xchk_next, nullptr, 0, inject, y2, stream, false);
     // sized as abed_get_layout reports it (the int8-output case, which needs the most)
     Plan pl;
     abed_status_t s = make_plan(desc, ABED_INT8, variant, true, pl);

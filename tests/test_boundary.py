@@ -94,7 +94,7 @@ def test_layout_of_one_scheme_alone(L, s):
 
 def test_scheme_selection_errors(L):
     d = abed.desc_from_shape(CONFIG1[0])
-    for v in (0 | abed.ONLY_FC, 6 | abed.ONLY_IC, 4 | abed.ONLY_FC | abed.ONLY_IC, 5 | abed.ONLY_FC, 4 | 0x800,
+    for v in (0 | abed.ONLY_FC, 6 | abed.ONLY_IC, 4 | abed.ONLY_FC | abed.ONLY_IC, 5 | abed.ONLY_FC, 4 | 0x2000,
               4 | abed.PACKED_FC | abed.ONLY_IC, 3 | abed.PACKED_FC):
         with pytest.raises(AbedError) as e:
             abed.get_layout(d, 0, v)
