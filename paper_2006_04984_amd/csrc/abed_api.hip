@@ -290,7 +290,7 @@ bool box_shape_ok(const abed_conv_desc_t *d)
     const long long P = d->H + 2 * d->pad_h - 2, Q = d->W + 2 * d->pad_w - 2;
     if (P < 1 || Q < 1) return false;
     // 32-bit byte offsets, with room for a batch that runs up to 7 entries past N
-    if ((long long)(d->N + 8) * d->H * d->W * d->C >= 0x7ffffff0LL) return false;
+    if ((long long)(d->N + 8) * d->H * d->W * d->C >= 0x40000000LL) return false;    // (the kernel's mask offset is 2^30)
     if ((long long)d->N * P * Q * d->K * 4 >= 0x7ffffff0LL) return false;
     if ((long long)d->K * 9 * d->C >= 0x7ffffff0LL) return false;
     return true;
@@ -306,10 +306,8 @@ abed_status_t make_box_plan(const abed_conv_desc_t *d, bool want_fc, bool want_i
     bp.xch = want_ic ? nch : 0;
     bp.boxes_x = (bp.Q + 7) / 8; bp.boxes_y = (bp.P + 7) / 8;
     const int nboxes = bp.boxes_x * bp.boxes_y;
-    bp.fbr = 4;
-    // the unchecked kernel takes 128 filters per tile where that still leaves a workgroup for every CU
-    if (!want_fc && !want_ic && d->K % 128 == 0 && (long long)nboxes * (d->K / 128) * ((d->N + 7) / 8) >= 256) bp.fbr = 8;
-    bp.fbr = env_int("ABED_BOX_FBR", bp.fbr);
+    // 64 filters per tile; 128 (unchecked only, ABED_BOX_FBR=8) measured the same or slower on every configured layer
+    bp.fbr = env_int("ABED_BOX_FBR", 4);
     if (bp.fbr != 4 && bp.fbr != 8) return ABED_EUNSUPPORTED;
     if (d->K % (16 * bp.fbr) != 0) return ABED_EUNSUPPORTED;
     bp.fb = bp.fbr + (want_fc ? 1 : 0);
@@ -359,6 +357,10 @@ abed_status_t launch_box_conv(const abed_conv_desc_t *d, const BoxPlan &bp, cons
         p.inj_lane = (int)((k % 16) / 4) * 16 + (oy % 4) * 4 + ox % 4; p.inj_v = (int)(k % 4);
         p.inj_mask = 1u << inject->bit;
     }
+#ifdef ABED_ENABLE_DBG
+    p.dbg = env_int("ABED_DBG", 0);
+    { const char *v = getenv("ABED_DBG_PTR"); p.dbg_ts = (v && *v) ? (long long *)strtoull(v, nullptr, 0) : nullptr; }
+#endif
     const int tiles = bp.boxes_x * bp.boxes_y * bp.nranges * bp.grid_n;
     if (!launch_box(bp.fb, bp.fc, bp.xch, p, (tiles + 7) / 8 * 8, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("box_conv_kernel");
@@ -373,8 +375,10 @@ bool box_preferred_plain(const abed_conv_desc_t *d)
     if (forced == 0 || !box_shape_ok(d)) return false;
     if (forced == 1) return true;
     const long long P = d->H + 2 * d->pad_h - 2, Q = d->W + 2 * d->pad_w - 2;
+    // measured on the configured 3x3 layers at 32 and 256 images: faster than the pixel-group kernel from about
+    // three quarters of a workgroup per CU on, slower below (few, long-running workgroups)
     const long long tiles = ((P + 7) / 8) * ((Q + 7) / 8) * (d->K / 64) * ((d->N + 7) / 8);
-    return tiles >= 128;
+    return tiles >= 192;
 }
 
 // An unchecked convolution with its own tile plan (the baseline, and the checksum

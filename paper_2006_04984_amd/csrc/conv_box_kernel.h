@@ -51,6 +51,8 @@ struct BoxParams {
     int out_int8, relu;
     int inj_on, inj_box, inj_range, inj_kt, inj_batch, inj_wave, inj_i, inj_fb, inj_lane, inj_v;
     uint32_t inj_mask;
+    long long *dbg_ts;   // builds with ABED_ENABLE_DBG only: time stamps of two waves of one workgroup
+    int dbg;   // timing experiments (builds with ABED_ENABLE_DBG only): bit 0 no loads in the loop, 1 no matrix instructions, 2 no stores, 3 no barriers
 };
 
 constexpr int kBox = 8;                       // output pixels per box side
@@ -62,15 +64,23 @@ constexpr int kAStage = kEB * kAEntry;        // 51200
 constexpr int kAInstr = kAStage / 1024;       // 50 one-KB loads per stage
 
 // s_waitcnt vmcnt(n) for a wave-uniform run-time n (the instruction takes an immediate): the largest
-// compiled limit that does not exceed n.  Waiting for a smaller count than allowed is always safe.
+// compiled limit that does not exceed n, found by a short tree of scalar branches.  Waiting for a smaller
+// count than allowed is always safe.
 __device__ __forceinline__ void wait_vmcnt_upto(int n)
 {
-#define ABED_W(k) if (n >= k) { ABED_WAIT_VMCNT(k); return; }
-    ABED_W(48) ABED_W(40) ABED_W(36) ABED_W(32) ABED_W(28) ABED_W(24) ABED_W(22) ABED_W(20) ABED_W(18) ABED_W(16)
-    ABED_W(14) ABED_W(12) ABED_W(11) ABED_W(10) ABED_W(9) ABED_W(8) ABED_W(7) ABED_W(6) ABED_W(5) ABED_W(4)
-    ABED_W(3) ABED_W(2) ABED_W(1)
-#undef ABED_W
-    ABED_WAIT_VMCNT(0);
+    if (n >= 6) {
+        if (n >= 16) {
+            if (n >= 24) ABED_WAIT_VMCNT(24); else if (n >= 20) ABED_WAIT_VMCNT(20); else ABED_WAIT_VMCNT(16);
+        } else {
+            if (n >= 12) ABED_WAIT_VMCNT(12); else if (n >= 8) ABED_WAIT_VMCNT(8); else ABED_WAIT_VMCNT(6);
+        }
+    } else {
+        if (n >= 3) {
+            if (n >= 5) ABED_WAIT_VMCNT(5); else if (n >= 4) ABED_WAIT_VMCNT(4); else ABED_WAIT_VMCNT(3);
+        } else {
+            if (n >= 2) ABED_WAIT_VMCNT(2); else if (n >= 1) ABED_WAIT_VMCNT(1); else ABED_WAIT_VMCNT(0);
+        }
+    }
 }
 
 template <int I, int N, class F>
@@ -124,6 +134,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     const int PQ = p.P * p.Q;
 
     constexpr int OOB = 0x7ffffff0;
+    constexpr int kMasked = 0x40000000;     // + any offset inside x (below 2^30 bytes) stays beyond x's descriptor and below 2^31
     const __amdgpu_buffer_rsrc_t rs_x = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, n_end * HWC, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, p.K * p.crsb, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_wc = __builtin_amdgcn_make_buffer_rsrc((void *)p.wchk, 0, (FC && p.wchk) ? p.grid_n * 2 * p.crsb : 0, 0x00020000);
@@ -136,7 +147,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
 #pragma unroll
     for (int j = 0; j < LA; ++j) {
         const int instr = j * 8 + wave;
-        a_off[j] = OOB;
+        a_off[j] = kMasked;
         if (instr < kAInstr) {
             ++a_cnt;
             const int q = instr * 64 + lane;
@@ -150,12 +161,11 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     }
     // B sub-stage: piece q -> (filter row f of the tile, tap t of the filter row, part'); fetched part = part' ^ ((f >> 2) & 3)
     int b_off[LB];
-    bool b_chk[LB];           // wave-uniform: the instruction's rows belong to the digit block
     int b_cnt = 0;
 #pragma unroll
     for (int j = 0; j < LB; ++j) {
         const int instr = j * 8 + wave;
-        b_off[j] = OOB; b_chk[j] = false;
+        b_off[j] = OOB;
         if (instr < B_INSTR) {
             ++b_cnt;
             const int q = instr * 64 + lane;
@@ -165,50 +175,51 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
             if (f < FBR * 16) {
                 b_off[j] = (kt * FBR * 16 + f) * p.crsb + inrow;
             } else {
-                b_chk[j] = true;
                 const int df = f - FBR * 16;
                 if (df < 2) b_off[j] = (kt * 2 + df) * p.crsb + inrow;
             }
         }
     }
 
-    // ---- in-order model of the vector-memory counter (loads, LDS DMA and stores complete in issue order):
-    // `issued` counts this wave's vector-memory instructions; a wait for "everything up to mark m" allows
-    // issued - m younger ones to be outstanding.
-    int issued = 0;
-    int b_mark[NBR];          // value of `issued` right after the loads of the sub-stage in ring slot i
-    int a_mark[2];
+    // ---- which of the 3*FB load slots of a sub-step this wave uses (loop-invariant, wave-uniform bit masks):
+    // filters at slots 1 + 4 J, inputs at the even slots 2 + 2 J' (r == 0: instructions J = J', r == 1: J = J' + 4)
+    unsigned msk_b = 0, msk_a0 = 0, msk_a1 = 0;
 #pragma unroll
-    for (int i = 0; i < NBR; ++i) b_mark[i] = 0;
-    a_mark[0] = a_mark[1] = 0;
+    for (int j = 0; j < LB; ++j)
+        if (j * 8 + wave < B_INSTR) msk_b |= 1u << (1 + 4 * j);
+#pragma unroll
+    for (int j = 0; j < LA; ++j)
+        if (j * 8 + wave < kAInstr) { if (j < 4) msk_a0 |= 1u << (2 + 2 * j); else msk_a1 |= 1u << (2 + 2 * (j - 4)); }
+    static_assert(1 + 4 * (LB - 1) < 3 * FB && 2 + 2 * 3 < 3 * FB && LA <= 8, "load slots");
+    // the digit block's rows can only be in this wave's last filter instruction
+    const bool last_chk = FC && (LB - 1) * 8 + wave >= FBR * 3;
+    const __amdgpu_buffer_rsrc_t rs_blast = last_chk ? rs_wc : rs_w;
+
+    // Vector-memory instructions (loads, LDS DMA, stores) complete in issue order, so "everything issued
+    // before the previous sub-step's are done" is a wait that allows as many outstanding ones as that
+    // sub-step issued: vm_prev.  Filters are requested two sub-steps ahead (NBR == 3; with NBR == 2 one
+    // ahead: then only the stores behind them may stay outstanding) and inputs a step ahead.
+    int vm_prev = 0, st_prev = 0;   // loads / stores issued by this wave in the previous sub-step
 
     auto issue_b = [&](int slot, int chunk, int r) {
-        const int soff = r * 3 * p.C + chunk * 64;
-        int8_t *dst0 = lds + B_OFF + slot * B_SUB;
-#pragma unroll
-        for (int j = 0; j < LB; ++j) {
-            const int instr = j * 8 + wave;
-            if (instr < B_INSTR) {   // wave-uniform
-                __attribute__((address_space(3))) void *dst = (__attribute__((address_space(3))) void *)(dst0 + instr * 1024);
-                if (b_chk[j]) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_wc, dst, 16, b_off[j], soff, 0, 0);
-                else __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, dst, 16, b_off[j], soff, 0, 0);
+        static_for<0, LB>([&](auto j_tag) {
+            constexpr int J = decltype(j_tag)::value;
+            const int instr = J * 8 + wave;
+            if (instr < B_INSTR) {
+                __attribute__((address_space(3))) void *dst = (__attribute__((address_space(3))) void *)(lds + B_OFF + slot * B_SUB + instr * 1024);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(J == LB - 1 ? rs_blast : rs_w, dst, 16, b_off[J], r * 3 * p.C + chunk * 64, 0, 0);
             }
-        }
-        issued += b_cnt;
+        });
     };
     auto issue_a = [&](int buf, int batch, int chunk) {
-        const int base = (n0 + batch * kEB) * HWC;
-        int8_t *dst0 = lds + A_OFF + buf * kAStage;
-#pragma unroll
-        for (int j = 0; j < LA; ++j) {
-            const int instr = j * 8 + wave;
-            if (instr < kAInstr) {   // wave-uniform
-                __attribute__((address_space(3))) void *dst = (__attribute__((address_space(3))) void *)(dst0 + instr * 1024);
-                const int voff = a_off[j] == OOB ? OOB : a_off[j] + base;   // entries at or past n_end fall outside the descriptor
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, dst, 16, voff, chunk * 64, 0, 0);
+        static_for<0, LA>([&](auto j_tag) {
+            constexpr int J = decltype(j_tag)::value;
+            const int instr = J * 8 + wave;
+            if (instr < kAInstr) {
+                __attribute__((address_space(3))) void *dst = (__attribute__((address_space(3))) void *)(lds + A_OFF + buf * kAStage + instr * 1024);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, dst, 16, a_off[J] + (n0 + batch * kEB) * HWC, chunk * 64, 0, 0);
             }
-        }
-        issued += a_cnt;
+        });
     };
 
     // ---- fragment addresses
@@ -231,6 +242,9 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
 #pragma unroll
         for (int d = 0; d < 4; ++d) xs_lo[c][d] = xs_hi[c][d] = 0u;
 
+    unsigned xt_lo[4] = {0u, 0u, 0u, 0u}, xt_hi[4] = {0u, 0u, 0u, 0u};
+    i32x4 x_next = {0, 0, 0, 0};
+
     // the epilog's scale and bias of this tile's filters, once (the loop's first barrier publishes them)
     float *e_scale = reinterpret_cast<float *>(lds + MISC_OFF + 256), *e_bias = e_scale + FBR * 16;
     if (p.out_int8 && tid < 2 * FBR * 16) {
@@ -247,24 +261,35 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
 
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.N * PQ * p.K * (p.out_int8 ? 1 : 4), 0x00020000);
 
-    // ---- the multiply phase of one sub-step (filter row r) for NI of this wave's entries
-    auto mfma_row = [&](auto ni_tag, int abuf, int bslot, int r) {
+    // ---- the multiply phase of one sub-step (filter row r) for NI of this wave's entries.  The fragments of
+    // tap s+1 are requested before the matrix instructions of tap s are issued (two register sets), so the
+    // LDS latency of a tap hides behind the previous tap's 4*FB matrix instructions.
+    auto mfma_row = [&](auto ni_tag, int abuf, int bslot, int r, int ebase, auto &&mid) {
         constexpr int NI = decltype(ni_tag)::value;
         const int hy = oy_l + r;
-        const int8_t *pa = lds + A_OFF + abuf * kAStage + (eh * 4) * kAEntry + (sig0 + r * kHalo) * 64 + (((lg ^ hy) & 3) << 4);
+        const int8_t *pa = lds + A_OFF + abuf * kAStage + ebase * kAEntry + (sig0 + r * kHalo) * 64 + (((lg ^ hy) & 3) << 4);
         const int8_t *pb = lds + B_OFF + bslot * B_SUB + b_lane;
-#pragma unroll 1
-        for (int s = 0; s < 3; ++s) {
-            i32x4 bfr[NI];
+        i32x4 bfr[2][NI], afr[2][FB];
+        auto fetch = [&](int set, int s) {
 #pragma unroll
-            for (int i = 0; i < NI; ++i) bfr[i] = *reinterpret_cast<const i32x4 *>(pa + i * kAEntry + s * 64);
+            for (int i = 0; i < NI; ++i) bfr[set][i] = *reinterpret_cast<const i32x4 *>(pa + i * kAEntry + s * 64);
 #pragma unroll
-            for (int fb = 0; fb < FB; ++fb) {
-                const i32x4 afr = *reinterpret_cast<const i32x4 *>(pb + fb * 3072 + s * 64);
+            for (int fb = 0; fb < FB; ++fb) afr[set][fb] = *reinterpret_cast<const i32x4 *>(pb + fb * 3072 + s * 64);
+        };
+        fetch(0, 0);
+        static_for<0, 3>([&](auto s_tag) {
+            constexpr int S = decltype(s_tag)::value;
+            if (S < 2) fetch((S + 1) & 1, S + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<0, FB>([&](auto fb_tag) {
+                constexpr int F = decltype(fb_tag)::value;
 #pragma unroll
-                for (int i = 0; i < NI; ++i) acc[i][fb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr, bfr[i], acc[i][fb], 0, 0, 0);
-            }
-        }
+                for (int i = 0; i < NI; ++i) acc[i][F] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[S & 1][F], bfr[S & 1][i], acc[i][F], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                mid(std::integral_constant<int, S * FB + F>{});      // at most one refill load (see the sub-step)
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
     };
 
     // ---- FC residual of one accumulator row set (Sec. 3.1 with the digit shifts of Sec. 4.1)
@@ -279,112 +304,186 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
         return r;
     };
 
-    // ---- main loop over steps = (batch, chunk); batch == nbatch is the digit batch (IC only)
+    // ---- main loop over sub-steps; a step = (batch, chunk) = three sub-steps (filter rows); batch == nbatch is
+    // the digit batch (IC only)
     const int nsteps_real = nbatch * p.nch;
     const int nsteps = (nbatch + (IC ? 1 : 0)) * p.nch;
     const int nsub = nsteps * 3;
-    // prologue: the first NBR-1 filter sub-stages and the first A stage
-    {
+    // prologue: the first filter sub-stage and the first A stage, then (NBR == 3) the second filter sub-stage
+    issue_b(0, 0, 0);
+    issue_a(0, 0, 0);
+    if (NBR == 3) { issue_b(1, 0, 1); vm_prev = b_cnt; }
 #pragma unroll
-        for (int u = 0; u < NBR - 1; ++u) {
-            if (u < nsub) {
-                const int st = u / 3, r = u - st * 3;
-                issue_b(u % NBR, st % p.nch, r);
-                b_mark[u % NBR] = issued;
-            }
-            if (u == 0) { issue_a(0, 0, 0); a_mark[0] = issued; }
-        }
-    }
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb) acc[i][fb] = zero4;
 
-    int usub = 0;             // running sub-step index
     int bslot = 0;            // usub % NBR
-    for (int batch = 0; batch < nbatch + (IC ? 1 : 0); ++batch) {
-        const bool digit = IC && batch == nbatch;
+    int r = 0, chunk = 0, batch = 0, stepi = 0;
+    int pf_r = (NBR - 1) % 3, pf_chunk = ((NBR - 1) / 3) % p.nch;    // (filter row, chunk) of sub-step usub + NBR - 1
+#ifdef ABED_ENABLE_DBG
+    int nts = 0;
+    const bool ts_on = p.dbg_ts && (int)blockIdx.x == 16 && (tid == 0 || tid == 448);
+    long long *ts_buf = p.dbg_ts + (tid == 0 ? 0 : 2048);
+#define ABED_TS() do { if (ts_on && nts < 2048) ts_buf[nts++] = (long long)__builtin_amdgcn_s_memtime(); } while (0)
+#else
+#define ABED_TS() do { } while (0)
+#endif
+    int usub = 0;
+    // one sub-step; dig_tag: compile-time "this is the digit batch" (its own copy of the code, so that no
+    // branch inside the loop decides which matrix instructions touch the accumulators)
+    auto substep = [&](auto dig_tag) {
+        constexpr bool digit = decltype(dig_tag)::value;
+        const int abuf = stepi & 1;
+        ABED_TS();
+        // (1) this sub-step's filters, and at r == 0 this step's inputs, have landed.  With one chunk the filter
+        // ring holds the whole tile from the second step on: then only the change of the A buffer (r == 0)
+        // needs the workgroup to meet.
+        const bool resident = NBR == 3 && p.nch == 1 && usub >= 3;
+        if (!resident || r == 0) {
+            wait_vmcnt_upto((NBR == 3 ? vm_prev : 0) + st_prev);
+            ABED_TS();
+            __builtin_amdgcn_s_waitcnt(0xc07f);          // this wave's LDS writes (digit images) are done: lgkmcnt(0)
+#ifdef ABED_ENABLE_DBG
+            if (!(p.dbg & 8))
+#endif
+            __builtin_amdgcn_s_barrier();
+        } else {
+            ABED_TS();
+        }
+        ABED_TS();
+        // (2) refill, issued inside (4), at most one load behind every group of matrix instructions: the
+        // address unit the loads go through is shared by the eight waves, and a burst from all of them stalls
+        // every wave at once.  Filters of sub-step usub + NBR - 1 go into the ring slot that sub-step usub-1
+        // used; inputs of step + 1 (at r == 0 and r == 1) into the A buffer that step-1 used.  With one chunk the
+        // ring holds the whole filter tile after the first three sub-steps, and nothing is reloaded.
+        const bool more_a = stepi + 1 < nsteps_real && r < 2;
+        const bool more_b = usub + NBR - 1 < nsub && !(NBR == 3 && p.nch == 1 && usub >= 1);
+        unsigned m = (more_b ? msk_b : 0u) | (more_a ? (r == 0 ? msk_a0 : msk_a1) : 0u);
+#ifdef ABED_ENABLE_DBG
+        if (p.dbg & 1) m = 0;
+#endif
+        int bsl = bslot + NBR - 1; if (bsl >= NBR) bsl -= NBR;
+        const int8_t *b_dst = lds + B_OFF + bsl * B_SUB + wave * 1024;
+        const int b_soff = pf_r * 3 * p.C + pf_chunk * 64;
+        const int8_t *a_dst = lds + A_OFF + (abuf ^ 1) * kAStage + wave * 1024 + (r == 1 ? 4 * 8192 : 0);
+        const int a_soff = ((chunk + 1 == p.nch) ? 0 : chunk + 1) * 64;
+        int a_voff[4];
+        if (more_a) {
+            const int abase = (n0 + ((chunk + 1 == p.nch) ? batch + 1 : batch) * kEB) * HWC;   // masked lanes stay beyond the descriptor, as do entries at or past n_end
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int fb = 0; fb < FB; ++fb) acc[i][fb] = zero4;
-
-        auto step = [&](auto c_tag, int chunk) {
-            constexpr int CT = decltype(c_tag)::value;       // compile-time chunk for the checksum registers (0 when XCH == 0)
-            const int stepi = batch * p.nch + chunk;
-            const int abuf = stepi & 1;
-#pragma unroll
-            for (int r = 0; r < 3; ++r) {
-                // (1) this sub-step's filters, and at r == 0 this step's inputs, have landed
-                {
-                    int need = b_mark[bslot];
-                    if (r == 0 && !digit && a_mark[abuf] > need) need = a_mark[abuf];
-                    wait_vmcnt_upto(issued - need);
-                }
-                __builtin_amdgcn_s_waitcnt(0xc07f);          // this wave's LDS writes (digit images) are done: lgkmcnt(0)
-                __builtin_amdgcn_s_barrier();
-                // (2) refill: the ring slot that sub-step usub-1 used, and at r == 0 the A buffer that step-1 used
-                {
-                    const int un = usub + NBR - 1;
-                    if (un < nsub) {
-                        const int st = un / 3, rr = un - st * 3;
-                        int sl = bslot + NBR - 1; if (sl >= NBR) sl -= NBR;
-                        issue_b(sl, st % p.nch, rr);
-                        b_mark[sl] = issued;
-                    }
-                    if (r == 0 && stepi + 1 < nsteps_real) {
-                        const int nb = (chunk + 1 == p.nch) ? batch + 1 : batch;
-                        const int nc = (chunk + 1 == p.nch) ? 0 : chunk + 1;
-                        issue_a(abuf ^ 1, nb, nc);
-                        a_mark[abuf ^ 1] = issued;
-                    }
-                }
-                // (3) batch checksum: add this step's staged inputs; hand the finished sums of the next
-                // digit step's chunk to LDS as two digit images (Sec. 4.1)
-                if constexpr (IC) {
-                    if (r == 0) {
-                        if (!digit && x_on) {
-                            const int8_t *src = lds + A_OFF + abuf * kAStage + x_piece;
-#pragma unroll
-                            for (int e = 0; e < kEB; ++e) {
-                                const i32x4 v = *reinterpret_cast<const i32x4 *>(src + e * kAEntry);
-#pragma unroll
-                                for (int d = 0; d < 4; ++d) {
-                                    const unsigned u = (unsigned)v[d] ^ 0x80808080u;
-                                    xs_lo[CT][d] += u & 0x00ff00ffu;
-                                    xs_hi[CT][d] += (u >> 8) & 0x00ff00ffu;
-                                }
-                            }
-                        }
-                        if (stepi + 1 >= nsteps_real && stepi + 1 < nsteps && x_on) {
-                            constexpr int CN = (CT + 1) % XR;        // chunk of step stepi + 1
-                            const int bias = 128 * nbatch * kEB;     // every staged entry added 128 per byte (zero-filled ones too)
-                            i32x4 d0, d1;
-#pragma unroll
-                            for (int d = 0; d < 4; ++d) {
-                                int s0 = (int)(xs_lo[CN][d] & 0xffffu) - bias, s1 = (int)(xs_hi[CN][d] & 0xffffu) - bias;
-                                int s2 = (int)(xs_lo[CN][d] >> 16) - bias, s3 = (int)(xs_hi[CN][d] >> 16) - bias;
-                                const unsigned lo = ((unsigned)next_digit(s0) & 0xffu) | (((unsigned)next_digit(s1) & 0xffu) << 8) |
-                                                    (((unsigned)next_digit(s2) & 0xffu) << 16) | (((unsigned)next_digit(s3) & 0xffu) << 24);
-                                const unsigned hi = ((unsigned)s0 & 0xffu) | (((unsigned)s1 & 0xffu) << 8) | (((unsigned)s2 & 0xffu) << 16) | (((unsigned)s3 & 0xffu) << 24);
-                                d0[d] = (int)lo; d1[d] = (int)hi;
-                            }
-                            int8_t *dst = lds + A_OFF + (abuf ^ 1) * kAStage + x_piece;
-                            *reinterpret_cast<i32x4 *>(dst) = d0;
-                            *reinterpret_cast<i32x4 *>(dst + kAEntry) = d1;
-                        }
-                    }
-                }
-                // (4) multiply
-                if (!digit) mfma_row(std::integral_constant<int, 4>{}, abuf, bslot, r);
-                else if (eh == 0) mfma_row(std::integral_constant<int, 2>{}, abuf, bslot, r);
-                ++usub;
-                if (++bslot == NBR) bslot = 0;
+            for (int j = 0; j < 4; ++j) a_voff[j] = (r == 1 ? (j + 4 < LA ? a_off[j + 4 < LA ? j + 4 : 0] : kMasked) : a_off[j]) + abase;
+        }
+        auto mid = [&](auto k_tag) {
+            constexpr int K = decltype(k_tag)::value;
+            if constexpr (K % 4 == 1 && (K - 1) / 4 < LB) {
+                constexpr int J = (K - 1) / 4;
+                if (m & (1u << K))
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(J == LB - 1 ? rs_blast : rs_w, (__attribute__((address_space(3))) void *)(b_dst + J * 8192), 16, b_off[J], b_soff, 0, 0);
+            } else if constexpr (K % 2 == 0 && K >= 2 && K <= 8) {
+                constexpr int J = (K - 2) / 2;
+                if (m & (1u << K))
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (__attribute__((address_space(3))) void *)(a_dst + J * 8192), 16, a_voff[J], a_soff, 0, 0);
             }
         };
-        if constexpr (IC) {
-            // chunk loop unrolled: the checksum registers of a chunk are selected at compile time
-            static_for<0, XR>([&](auto c_tag) { step(c_tag, decltype(c_tag)::value); });
-        } else {
-            for (int chunk = 0; chunk < p.nch; ++chunk) step(std::integral_constant<int, 0>{}, chunk);
+        ABED_TS();
+        // (3) batch checksum (Sec. 3.2 option 1): this thread's 16 bytes of every staged entry are added up in the
+        // load slots that sub-steps r == 1 and r == 2 leave free (one entry per slot, requested one slot ahead), so
+        // the additions hide behind the matrix instructions.  xt_*: the step's sums, folded into the chunk's
+        // registers at the end of r == 2.
+        const int8_t *x_src = lds + A_OFF + abuf * kAStage + x_piece;
+        auto x_add = [&](const i32x4 v) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const unsigned u = (unsigned)v[d] ^ 0x80808080u;
+                xt_lo[d] += u & 0x00ff00ffu;
+                xt_hi[d] += (u >> 8) & 0x00ff00ffu;
+            }
+        };
+        auto mid_all = [&](auto k_tag) {
+            constexpr int K = decltype(k_tag)::value;
+            mid(k_tag);
+            if constexpr (IC && !digit) {
+                // slots 0, 3, 7, 10 of r == 1 take entries 0..3, the same slots of r == 2 entries 4..7
+                constexpr int Q = K == 0 ? 0 : K == 3 ? 1 : K == 7 ? 2 : K == 10 ? 3 : -1;
+                if constexpr (Q >= 0) {
+                    if (r >= 1 && x_on) {
+                        const int e = (r - 1) * 4 + Q;
+                        x_add(x_next);                          // entry e, requested one slot earlier
+                        if (e + 1 < kEB) x_next = *reinterpret_cast<const i32x4 *>(x_src + (e + 1) * kAEntry);
+                    }
+                }
+            }
+        };
+        if constexpr (IC && !digit) {
+            if (r == 1 && x_on) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) xt_lo[d] = xt_hi[d] = 0u;
+                x_next = *reinterpret_cast<const i32x4 *>(x_src);
+            }
         }
+        // (4) multiply; in the digit batch entries 0 and 1 of the stage are the two digit images: the even waves
+        // take digit 0, the odd waves digit 1 of their pixel group
+        ABED_TS();
+#ifdef ABED_ENABLE_DBG
+        if (!(p.dbg & 2)) {
+#endif
+        if constexpr (digit) mfma_row(std::integral_constant<int, 1>{}, abuf, bslot, r, eh, mid_all);
+        else mfma_row(std::integral_constant<int, 4>{}, abuf, bslot, r, eh * 4, mid_all);
+#ifdef ABED_ENABLE_DBG
+        }
+#endif
+        ABED_TS();
+        vm_prev = __builtin_popcount(m); st_prev = 0;   // (sub-steps that skip the wait issue their loads before r == 2, whose own count is then 0)
+        if (++pf_r == 3) { pf_r = 0; if (++pf_chunk == p.nch) pf_chunk = 0; }
+        if (++bslot == NBR) bslot = 0;
+        ++usub;
 
+        if constexpr (IC) {
+            if (r == 2 && x_on) {
+                if constexpr (!digit) {
+                    static_for<0, XR>([&](auto c_tag) {
+                        constexpr int CT = decltype(c_tag)::value;
+                        if (chunk == CT) {
+#pragma unroll
+                            for (int d = 0; d < 4; ++d) { xs_lo[CT][d] += xt_lo[d]; xs_hi[CT][d] += xt_hi[d]; }
+                        }
+                    });
+                }
+                // the next step is a digit step: its chunk's sums are complete; split them into two int8 digit
+                // images (Sec. 4.1) and put them into the free A buffer as entries 0 and 1
+                if (stepi + 1 >= nsteps_real && stepi + 1 < nsteps) {
+                    const int cn = (chunk + 1 == p.nch) ? 0 : chunk + 1;     // chunk of step stepi + 1
+                    unsigned lo[4], hi[4];
+                    static_for<0, XR>([&](auto c_tag) {
+                        constexpr int CT = decltype(c_tag)::value;
+                        if (cn == CT) {
+#pragma unroll
+                            for (int d = 0; d < 4; ++d) { lo[d] = xs_lo[CT][d]; hi[d] = xs_hi[CT][d]; }
+                        }
+                    });
+                    const int bias = 128 * nbatch * kEB;     // every staged entry added 128 per byte (zero-filled ones too)
+                    i32x4 d0, d1;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        int s0 = (int)(lo[d] & 0xffffu) - bias, s1 = (int)(hi[d] & 0xffffu) - bias;
+                        int s2 = (int)(lo[d] >> 16) - bias, s3 = (int)(hi[d] >> 16) - bias;
+                        const unsigned dl = ((unsigned)next_digit(s0) & 0xffu) | (((unsigned)next_digit(s1) & 0xffu) << 8) |
+                                            (((unsigned)next_digit(s2) & 0xffu) << 16) | (((unsigned)next_digit(s3) & 0xffu) << 24);
+                        const unsigned dh = ((unsigned)s0 & 0xffu) | (((unsigned)s1 & 0xffu) << 8) | (((unsigned)s2 & 0xffu) << 16) | (((unsigned)s3 & 0xffu) << 24);
+                        d0[d] = (int)dl; d1[d] = (int)dh;
+                    }
+                    int8_t *dst = lds + A_OFF + (abuf ^ 1) * kAStage + x_piece;
+                    *reinterpret_cast<i32x4 *>(dst) = d0;
+                    *reinterpret_cast<i32x4 *>(dst + kAEntry) = d1;
+                }
+            }
+        }
+        // (5) end of a step / of a batch
+        if (++r < 3) return;
+        r = 0; ++stepi;
+        if (++chunk < p.nch) return;
+        chunk = 0;
         // ---- epilogue of the batch (registers only; the next batch's loads are already in flight)
         if (!digit) {
             if (p.inj_on && box == p.inj_box && range == p.inj_range && kt == p.inj_kt && batch == p.inj_batch && wave == p.inj_wave) {
@@ -400,21 +499,24 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
             for (int i = 0; i < 4; ++i) {
                 const int e = n0 + batch * kEB + eh * 4 + i;
                 if (FC) {
-                    const unsigned r = fc_residual(i);
-                    if (r != 0 && e < n_end) my_flag |= 1u;
+                    const unsigned res = fc_residual(i);
+                    if (res != 0 && e < n_end) my_flag |= 1u;
                 }
                 if (IC) {
 #pragma unroll
                     for (int fb = 0; fb < FB; ++fb) icsum[fb] += acc[i][fb];   // entries past the range are all zero
                 }
                 // stores: checksum columns are trimmed (end of Sec. 4.3); masked lanes go out of the descriptor's range
+#ifdef ABED_ENABLE_DBG
+                const bool live = pvalid && e < n_end && !(p.dbg & 4);
+#else
                 const bool live = pvalid && e < n_end;
+#endif
                 if (!p.out_int8) {
                     const int o = live ? ((e * PQ + pix) * p.K + kt * FBR * 16 + lg * 4) * 4 : OOB;
 #pragma unroll
                     for (int fb = 0; fb < FBR; ++fb)
                         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[i][fb]), rs_y, o, fb * 64, 0);
-                    issued += FBR;
                 } else {
                     const int o = live ? (e * PQ + pix) * p.K + kt * FBR * 16 + lg * 4 : OOB;
 #pragma unroll
@@ -425,10 +527,24 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
                         for (int v = 0; v < 4; ++v) pk |= ((unsigned)requant(acc[i][fb][v], e_scale[k + v], e_bias[k + v], p.relu) & 0xffu) << (8 * v);
                         __builtin_amdgcn_raw_buffer_store_b32(pk, rs_y, o, fb * 16, 0);
                     }
-                    issued += FBR;
                 }
             }
+            st_prev = 4 * FBR;
         }
+        ++batch;
+        if (usub < nsub) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb) acc[i][fb] = zero4;
+        }
+    };
+    const int nsub_real = nsteps_real * 3;
+#pragma unroll 1
+    while (usub < nsub_real) substep(std::false_type{});
+    if constexpr (IC) {
+#pragma unroll 1
+        while (usub < nsub) substep(std::true_type{});
     }
 
     // ---- final comparisons
@@ -437,20 +553,24 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
         int *red = reinterpret_cast<int *>(lds);              // [4 pixel groups][FB][64 lanes][4]: the odd waves' sums
         ABED_WAIT_VMCNT(0);
         __syncthreads();                                      // all fragment reads are done; LDS is free
+        // the digit batch left, in acc[0], the fmaps of digit image 0 (even waves) / digit image 1 (odd waves)
+        if (FC) {
+            if (fc_residual(0) != 0) my_flag |= 4u;           // corner: a digit image's row under FC
+        }
         if (eh == 1) {
 #pragma unroll
-            for (int fb = 0; fb < FB; ++fb) *reinterpret_cast<i32x4 *>(red + ((pg * FB + fb) * 64 + lane) * 4) = icsum[fb];
+            for (int fb = 0; fb < FB; ++fb) {
+                i32x4 c = icsum[fb];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) c[v] -= (int)((unsigned)acc[0][fb][v] << 8);
+                *reinterpret_cast<i32x4 *>(red + ((pg * FB + fb) * 64 + lane) * 4) = c;
+            }
         }
         __syncthreads();
         if (eh == 0) {
-            if (FC) {
-                if (fc_residual(0) != 0 || fc_residual(1) != 0) my_flag |= 4u;
-            }
 #pragma unroll
             for (int fb = 0; fb < FB; ++fb) {
-                i32x4 c = icsum[fb] + *reinterpret_cast<const i32x4 *>(red + ((pg * FB + fb) * 64 + lane) * 4);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) c[v] -= (int)((unsigned)acc[0][fb][v] + ((unsigned)acc[1][fb][v] << 8));
+                const i32x4 c = icsum[fb] + *reinterpret_cast<const i32x4 *>(red + ((pg * FB + fb) * 64 + lane) * 4) - acc[0][fb];
                 if ((c[0] | c[1] | c[2] | c[3]) != 0) my_flag |= (FC && fb == FB - 1) ? 4u : 2u;
             }
         }

@@ -57,8 +57,9 @@ class Int8Layer:
         self.y2 = torch.empty_like(self.y) if self.variant == int(Variant.DUPLICATE) else None
         self.flags = torch.zeros((max(1, self.lay.n_flag_words),), dtype=torch.int32, device=DEV)
         self.ws = torch.zeros((max(256, self.lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
-        self.wchk = torch.empty((self.lay.d_f, s.R, s.S, s.C), dtype=torch.int8, device=DEV)
-        self.xchk = torch.empty((self.lay.d_i, s.H, s.W, s.C), dtype=torch.int8, device=DEV)
+        local = bool(self.lay.local_checksums)                # checksum filters per filter tile, no checksum images
+        self.wchk = torch.empty((self.lay.d_f * (self.lay.grid_n if local else 1), s.R, s.S, s.C), dtype=torch.int8, device=DEV)
+        self.xchk = torch.empty((0 if local else self.lay.d_i, s.H, s.W, s.C), dtype=torch.int8, device=DEV)
         self.xchk_next = torch.empty((self.lay.d_i, s.P, s.Q, s.K), dtype=torch.int8, device=DEV) if epilogue else None
         self.epi = None
         if epilogue:
@@ -71,7 +72,7 @@ class Int8Layer:
             both[: s.K].copy_(self.w)
             self.w, self.wchk = both[: s.K], both[s.K:]
         if self.lay.d_f:
-            abed.filter_prepare_int8(self.desc, self.w, self.wchk)
+            abed.filter_prepare_local_int8(self.desc, self.variant, self.w, self.wchk)
 
     def run(self, compute_xchk=True, inject=None):
         abed.conv_int8(self.desc, self.x, self.w, self.wchk, self.xchk, compute_xchk, self.y, self.variant,
