@@ -155,6 +155,9 @@ typedef struct {
     int64_t xchk_next_bytes; /* d_i * P*Q*K elements (variant 5)                             */
     int32_t tile_box;      /* 0: a tile's pixels are consecutive in p*Q + q; 8: a box of 8x8 pixels (ABED_LOCAL) */
     int32_t local_checksums; /* 1: FC per filter tile, IC per batch tile, wchk is [grid_n][d_f][R][S][C]   */
+    int32_t local_preferred; /* ABED_LOCAL layouts: 1 where the library's timing rule expects this form to be
+                                faster than the layer-wide checksums for this shape, else 0                   */
+    int32_t reserved_;
 } abed_layout_t;
 
 /* Flag word of tile (tm, tb, tn) is flags[(tm * grid_b + tb) * grid_n + tn].
@@ -320,6 +323,15 @@ abed_status_t abed_fic_conv_int8(const abed_conv_desc_t *desc, const int8_t *x, 
                                  int32_t *xsum_in, int32_t *xsum_next,
                                  void *workspace, size_t workspace_bytes,
                                  const abed_inject_t *inject, void *stream);
+
+/* Probes of the machine's own ceilings, for roofline reports (no part of the method; for benchmark
+ * programs that may not allocate or launch kernels of their own).  Enqueues on `stream`:
+ *   kind 0: a register-resident loop of `iters` x 16 int8 matrix instructions (16x16x64) per wave on 256
+ *           workgroups of 8 waves = 256 * 8 * iters * 16 * 32768 operations; a: device scratch, bytes >= 512 KiB;
+ *   kind 1: `iters` fills of the `bytes` at a (16 bytes per lane);
+ *   kind 2: `iters` copies of `bytes` from a to b.
+ * ABED_EINVAL for other kinds, null pointers or too small a buffer. */
+abed_status_t abed_probe(int32_t kind, void *a, void *b, size_t bytes, int32_t iters, void *stream);
 
 const char *abed_status_string(abed_status_t status);
 /* Text of the last HIP error seen by this thread's most recent failing call. */

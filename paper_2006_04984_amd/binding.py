@@ -50,7 +50,8 @@ class Layout(ctypes.Structure):
                 ("tile_pixels", "tile_batch", "tile_n", "grid_m", "grid_b", "grid_n", "d_f", "d_i")] + \
                [(n, ctypes.c_int64) for n in
                 ("n_flag_words", "workspace_bytes", "wchk_bytes", "xchk_bytes", "xchk_next_bytes")] + \
-               [("tile_box", ctypes.c_int32), ("local_checksums", ctypes.c_int32)]
+               [("tile_box", ctypes.c_int32), ("local_checksums", ctypes.c_int32), ("local_preferred", ctypes.c_int32),
+                ("reserved_", ctypes.c_int32)]
 
 
 class FicLayout(ctypes.Structure):
@@ -71,7 +72,7 @@ class Ic2Layout(ctypes.Structure):
 EXPORTS = ["abed_fic_inloop_get_layout", "abed_fic_inloop_filter_prepare_int8", "abed_fic_inloop_conv_int8", "abed_fic_verify", "abed_ic2_get_layout", "abed_ic2_conv_int8", "abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
            "abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_local_int8", "abed_filter_prepare_fp16",
            "abed_input_checksum_int8", "abed_input_checksum_fp16", "abed_workspace_init",
-           "abed_conv_int8", "abed_conv_int8_static", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error"]
+           "abed_conv_int8", "abed_conv_int8_static", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error", "abed_probe"]
 
 
 def lib_path():
@@ -105,6 +106,7 @@ def lib():
                                      vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(_Inject), vp, vp]
         L.abed_conv_int8_static.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp, vp, i32, vp, ctypes.POINTER(_Epilogue), i32,
                                             vp, vp, ctypes.POINTER(_Inject), vp, vp]
+        L.abed_probe.argtypes = [i32, vp, vp, ctypes.c_size_t, i32, vp]
         f32 = ctypes.c_float
         L.abed_filter_prepare_fp16.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
         L.abed_input_checksum_fp16.argtypes = [ctypes.POINTER(ConvDesc), vp, vp, vp]
@@ -201,6 +203,11 @@ def conv_int8_static(desc, x, w, wchk, xchk, compute_xchk, y, variant, flags=Non
         inj = ctypes.byref(_Inject(int(inject[0]), int(inject[1]), int(inject[2])))
     _check(lib().abed_conv_int8_static(ctypes.byref(desc), _p(x), _p(w), _p(wchk), _p(xchk), int(bool(compute_xchk)),
                                        _p(y), epi, int(variant), _p(flags), _p(xchk_next), inj, _p(y2), _stream(stream)))
+
+
+def probe(kind, a, b=None, iters=1, stream=None):
+    """abed_probe: machine ceilings for roofline reports (0: int8 matrix instruction loop, 1: fill a, 2: copy a -> b)."""
+    _check(lib().abed_probe(int(kind), _p(a), _p(b), a.numel() * a.element_size(), int(iters), _stream(stream)))
 
 
 def filter_prepare_fp16(desc, w, wchk, stream=None):

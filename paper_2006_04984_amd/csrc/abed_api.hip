@@ -875,6 +875,11 @@ abed_status_t abed_get_layout(const abed_conv_desc_t *desc, int32_t dtype, int32
         out->wchk_bytes = (long long)out->d_f * bp.grid_n * bp.crs;
         out->xchk_bytes = 0; out->xchk_next_bytes = 0;
         out->local_checksums = 1;
+        // Measured on the configured 3x3 layers at 32 and 256 images: this form beats the layer-wide checksums
+        // (input checksum kernel + augmented convolution with its exchange between tiles) where the tiles give
+        // at least three quarters of the CUs a workgroup and the digit batch is a small part of a workgroup's
+        // life: one chunk of channels (the filters then stay in LDS), or batch tiles of at least 32 images.
+        out->local_preferred = (out->n_flag_words >= 192 && (desc->C == 64 || bp.range_len >= 32)) ? 1 : 0;
         return ABED_OK;
     }
     out->tile_pixels = 16;
@@ -890,6 +895,24 @@ abed_status_t abed_get_layout(const abed_conv_desc_t *desc, int32_t dtype, int32
     out->wchk_bytes = (long long)pl.d_f * pl.crs * pl.esize;
     out->xchk_bytes = (long long)pl.d_i * desc->H * desc->W * desc->C * pl.esize;
     out->xchk_next_bytes = (long long)pl.d_i * pl.PQ * desc->K;
+    return ABED_OK;
+}
+
+abed_status_t abed_probe(int32_t kind, void *a, void *b, size_t bytes, int32_t iters, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    if (!a || iters < 1) return ABED_EINVAL;
+    if (kind == 0) {
+        if (bytes < 256u * 512u * 4u) return ABED_EINVAL;
+        probe_mfma_i8_kernel<<<dim3(256), dim3(512), 0, st>>>((int *)a, iters);
+    } else if (kind == 1 || kind == 2) {
+        if (bytes < 16 || (kind == 2 && !b)) return ABED_EINVAL;
+        for (int i = 0; i < iters; ++i)
+            probe_stream_kernel<<<dim3(256 * 8), dim3(256), 0, st>>>(kind == 2 ? (const i32x4p *)a : nullptr, (i32x4p *)(kind == 2 ? b : a), (long long)(bytes / 16));
+    } else {
+        return ABED_EINVAL;
+    }
+    LAUNCH_CHECK("probe kernel");
     return ABED_OK;
 }
 

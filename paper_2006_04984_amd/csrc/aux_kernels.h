@@ -312,4 +312,34 @@ __global__ void flip_bit_u32_kernel(uint32_t *p, long long index, uint32_t mask)
     if (blockIdx.x == 0 && threadIdx.x == 0) p[index] ^= mask;
 }
 
+// ---- probes of the machine's own ceilings, for the benchmark's roofline lines (no part of the method)
+typedef int i32x4p __attribute__((ext_vector_type(4)));
+
+// register-resident v_mfma_i32_16x16x64_i8 loop: 16 independent accumulators per wave, 8 waves per workgroup
+__global__ __launch_bounds__(512) void probe_mfma_i8_kernel(int *out, int iters)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    i32x4p acc[16];
+    const i32x4p a = {(int)threadIdx.x, 1, 2, 3}, b = {3, 2, 1, (int)blockIdx.x};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = i32x4p{0, 0, 0, 0};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[i], 0, 0, 0);
+    }
+    i32x4p t = {0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += acc[i];
+    out[blockIdx.x * 512 + threadIdx.x] = t[0] + t[1] + t[2] + t[3];
+#endif
+}
+
+// 16 bytes per lane, grid-stride: fill (src == nullptr) or copy
+__global__ __launch_bounds__(256) void probe_stream_kernel(const i32x4p *src, i32x4p *dst, long long n16)
+{
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        dst[i] = src ? src[i] : i32x4p{1, 2, 3, 4};
+}
+
 }  // namespace abed
