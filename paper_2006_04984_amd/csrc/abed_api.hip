@@ -306,8 +306,12 @@ abed_status_t make_box_plan(const abed_conv_desc_t *d, bool want_fc, bool want_i
     bp.xch = want_ic ? nch : 0;
     bp.boxes_x = (bp.Q + 7) / 8; bp.boxes_y = (bp.P + 7) / 8;
     const int nboxes = bp.boxes_x * bp.boxes_y;
-    // 64 filters per tile; 128 (unchecked only, ABED_BOX_FBR=8) measured the same or slower on every configured layer
-    bp.fbr = env_int("ABED_BOX_FBR", 4);
+    // 64 filters per tile, or 128 (without the batch checksum, whose registers it would take) where that still
+    // leaves every CU a workgroup: twice the matrix instructions per barrier and a quarter less LDS traffic per
+    // matrix instruction (measured -9 ... -17 % on the 128- and 256-filter layers at 256 images, slower below)
+    bp.fbr = 4;
+    if (!want_ic && d->K % 128 == 0 && (long long)nboxes * (d->K / 128) * ((d->N + 7) / 8) >= 256) bp.fbr = 8;
+    bp.fbr = env_int("ABED_BOX_FBR", bp.fbr);
     if (bp.fbr != 4 && bp.fbr != 8) return ABED_EUNSUPPORTED;
     if (d->K % (16 * bp.fbr) != 0) return ABED_EUNSUPPORTED;
     bp.fb = bp.fbr + (want_fc ? 1 : 0);

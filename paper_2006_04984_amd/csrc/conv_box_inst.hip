@@ -15,6 +15,7 @@ bool CAT2(launch_box_x, BOX_XCH)(int fb, bool fc, const BoxParams &p, int grid, 
     if (!fc && fb == 4) { box_conv_kernel<4, false, BOX_XCH, 3><<<dim3(grid), dim3(512), 0, st>>>(p); return true; }
 #if BOX_XCH == 0
     if (!fc && fb == 8) { box_conv_kernel<8, false, 0, 2><<<dim3(grid), dim3(512), 0, st>>>(p); return true; }
+    if (fc && fb == 9) { box_conv_kernel<9, true, 0, 2><<<dim3(grid), dim3(512), 0, st>>>(p); return true; }
 #endif
     return false;
 }

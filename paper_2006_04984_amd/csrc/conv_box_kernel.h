@@ -261,34 +261,40 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
 
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.N * PQ * p.K * (p.out_int8 ? 1 : 4), 0x00020000);
 
-    // ---- the multiply phase of one sub-step (filter row r) for NI of this wave's entries.  The fragments of
-    // tap s+1 are requested before the matrix instructions of tap s are issued (two register sets), so the
-    // LDS latency of a tap hides behind the previous tap's 4*FB matrix instructions.
+    // ---- the multiply phase of one sub-step (filter row r) for NI of this wave's entries: 3 FB groups of NI matrix
+    // instructions, group g = (tap g / FB, filter block g % FB).  Fragments are requested ahead of their use: the
+    // pixel fragments of tap s+1 at the start of tap s (two register sets), the filter fragment of group g + 3
+    // before group g's matrix instructions (a ring of four), so the LDS latency hides behind matrix work.
     auto mfma_row = [&](auto ni_tag, int abuf, int bslot, int r, int ebase, auto &&mid) {
         constexpr int NI = decltype(ni_tag)::value;
+        constexpr int RB = 4, G = 3 * FB;
         const int hy = oy_l + r;
         const int8_t *pa = lds + A_OFF + abuf * kAStage + ebase * kAEntry + (sig0 + r * kHalo) * 64 + (((lg ^ hy) & 3) << 4);
         const int8_t *pb = lds + B_OFF + bslot * B_SUB + b_lane;
-        i32x4 bfr[2][NI], afr[2][FB];
-        auto fetch = [&](int set, int s) {
+        i32x4 bfr[2][NI], afr[RB];
+        auto fetch_a = [&](int set, int s) {
 #pragma unroll
             for (int i = 0; i < NI; ++i) bfr[set][i] = *reinterpret_cast<const i32x4 *>(pa + i * kAEntry + s * 64);
-#pragma unroll
-            for (int fb = 0; fb < FB; ++fb) afr[set][fb] = *reinterpret_cast<const i32x4 *>(pb + fb * 3072 + s * 64);
         };
-        fetch(0, 0);
-        static_for<0, 3>([&](auto s_tag) {
-            constexpr int S = decltype(s_tag)::value;
-            if (S < 2) fetch((S + 1) & 1, S + 1);
+        fetch_a(0, 0);
+        static_for<0, RB - 1>([&](auto g_tag) {
+            constexpr int GG = decltype(g_tag)::value;
+            afr[GG % RB] = *reinterpret_cast<const i32x4 *>(pb + (GG % FB) * 3072 + (GG / FB) * 64);
+        });
+        static_for<0, G>([&](auto g_tag) {
+            constexpr int GG = decltype(g_tag)::value;
+            constexpr int S = GG / FB, F = GG % FB;
+            if constexpr (F == 0 && S < 2) fetch_a((S + 1) & 1, S + 1);
+            if constexpr (GG + RB - 1 < G) {
+                constexpr int GN = GG + RB - 1;
+                afr[GN % RB] = *reinterpret_cast<const i32x4 *>(pb + (GN % FB) * 3072 + (GN / FB) * 64);
+            }
             __builtin_amdgcn_sched_barrier(0);
-            static_for<0, FB>([&](auto fb_tag) {
-                constexpr int F = decltype(fb_tag)::value;
 #pragma unroll
-                for (int i = 0; i < NI; ++i) acc[i][F] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[S & 1][F], bfr[S & 1][i], acc[i][F], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                mid(std::integral_constant<int, S * FB + F>{});      // at most one refill load (see the sub-step)
-                __builtin_amdgcn_sched_barrier(0);
-            });
+            for (int i = 0; i < NI; ++i) acc[i][F] = __builtin_amdgcn_mfma_i32_16x16x64_i8(afr[GG % RB], bfr[S & 1][i], acc[i][F], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mid(g_tag);      // at most one refill load (see the sub-step)
+            __builtin_amdgcn_sched_barrier(0);
         });
     };
 

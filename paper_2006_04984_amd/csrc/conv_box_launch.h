@@ -13,7 +13,7 @@ bool launch_box(int fb, bool fc, int xch, const BoxParams &p, int grid, hipStrea
 inline bool box_compiled(int fb, bool fc, int xch)
 {
     if (!(xch == 0 || xch == 1 || xch == 2 || xch == 4 || xch == 8)) return false;
-    if (fc) return fb == 5;
+    if (fc) return fb == 5 || (fb == 9 && xch == 0);
     return fb == 4 || (fb == 8 && xch == 0);
 }
 
