@@ -83,6 +83,13 @@ __device__ __forceinline__ void wait_vmcnt_upto(int n)
     }
 }
 
+// Where the 16-byte parts of a staged input pixel sit inside its 64-byte slot.  A 16-byte-per-lane LDS read serves
+// 8 consecutive lanes per cycle out of a 128-byte bank window; the 8 lanes of a fragment read are 4 neighbouring
+// pixels of two neighbouring halo rows, i.e. slots sigma..sigma+3 and sigma+10..sigma+13.  Slots of equal parity
+// share a half of the window, so the part index is XOR-ed with (bit 1 of the slot, bit 0 of the halo row): the four
+// lanes of a parity class then read four different parts.
+__device__ __forceinline__ int a_swz(int slot, int hy) { return ((slot >> 1) & 1) | ((hy & 1) << 1); }
+
 template <int I, int N, class F>
 __device__ __forceinline__ void static_for(F &&f)
 {
@@ -156,10 +163,11 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
             const int hy = slot / kHalo, hx = slot - hy * kHalo;
             const int iy = by * kBox - p.ph + hy, ix = bx * kBox - p.pw + hx;
             if ((unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W)
-                a_off[j] = ((e * p.H + iy) * p.W + ix) * p.C + ((part ^ (hy & 3)) << 4);
+                a_off[j] = ((e * p.H + iy) * p.W + ix) * p.C + ((part ^ a_swz(slot, hy)) << 4);
         }
     }
-    // B sub-stage: piece q -> (filter row f of the tile, tap t of the filter row, part'); fetched part = part' ^ ((f >> 2) & 3)
+    // B sub-stage: piece q -> (filter row f of the tile, tap t of the filter row, part'); fetched part = part' ^ ((f >> 1) & 3)
+    // (rows are 192 bytes: rows of equal parity share a half of the 128-byte bank window, and the 8 lanes of a read are 8 consecutive rows)
     int b_off[LB];
     int b_cnt = 0;
 #pragma unroll
@@ -171,7 +179,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
             const int q = instr * 64 + lane;
             const int f = q / 12, rem = q - f * 12;
             const int t = rem >> 2, part = rem & 3;
-            const int inrow = t * p.C + ((part ^ ((f >> 2) & 3)) << 4);
+            const int inrow = t * p.C + ((part ^ ((f >> 1) & 3)) << 4);
             if (f < FBR * 16) {
                 b_off[j] = (kt * FBR * 16 + f) * p.crsb + inrow;
             } else {
@@ -224,7 +232,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
 
     // ---- fragment addresses
     // B: lane (lg, lj) wants part lg of row fb*16 + lj, tap s: const + fb * 3072 + s * 64
-    const int b_lane = lj * 192 + (((lg ^ (lj >> 2)) & 3) << 4);
+    const int b_lane = lj * 192 + (((lg ^ (lj >> 1)) & 3) << 4);
     // A: lane's pixel inside the box and its slot for tap (0,0)
     const int oy_l = (pg >> 1) * 4 + (lj >> 2), ox_l = (pg & 1) * 4 + (lj & 3);
     const int sig0 = oy_l * kHalo + ox_l;
@@ -269,12 +277,18 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
         constexpr int NI = decltype(ni_tag)::value;
         constexpr int RB = 4, G = 3 * FB;
         const int hy = oy_l + r;
-        const int8_t *pa = lds + A_OFF + abuf * kAStage + ebase * kAEntry + (sig0 + r * kHalo) * 64 + (((lg ^ hy) & 3) << 4);
+        // this lane's pixel fragment of tap s: slot sig0 + 10 r + s, part lg at its swizzled place
+        const int8_t *pa3[3];
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            const int slot = sig0 + r * kHalo + t;
+            pa3[t] = lds + A_OFF + abuf * kAStage + ebase * kAEntry + slot * 64 + ((lg ^ a_swz(slot, hy)) << 4);
+        }
         const int8_t *pb = lds + B_OFF + bslot * B_SUB + b_lane;
         i32x4 bfr[2][NI], afr[RB];
         auto fetch_a = [&](int set, int s) {
 #pragma unroll
-            for (int i = 0; i < NI; ++i) bfr[set][i] = *reinterpret_cast<const i32x4 *>(pa + i * kAEntry + s * 64);
+            for (int i = 0; i < NI; ++i) bfr[set][i] = *reinterpret_cast<const i32x4 *>(pa3[s] + i * kAEntry);
         };
         fetch_a(0, 0);
         static_for<0, RB - 1>([&](auto g_tag) {

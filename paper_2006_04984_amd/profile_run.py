@@ -27,6 +27,7 @@ def main():
                     help="fcic: filter + batch checksums (abed_conv_int8); fc / ic: one of the two alone; "
                          "fic: the scalar scheme (abed_fic_conv_int8); fic_inloop: the same with its input side formed in the main loop (abed_fic_inloop_conv_int8); ic2: IC option 2, K values (abed_ic2_conv_int8)")
     ap.add_argument("--batch", type=int, default=0, help="override the configuration's batch size")
+    ap.add_argument("--local", action="store_true", help="checksums local to a workgroup (ABED_LOCAL, with --variant 4)")
     args = ap.parse_args()
     from synth import CONFIG2, CONFIG3, seed_for
     s = {2: CONFIG2, 3: CONFIG3}[args.config][args.layer]
@@ -45,7 +46,7 @@ def main():
     else:
         from . import binding as abed
         only = {"fcic": 0, "fc": abed.ONLY_FC, "ic": abed.ONLY_IC}[args.scheme] if args.variant in (1, 2, 3, 4, 5) else 0
-        L = Int8Layer(s, seed_for(args.config, args.layer), args.variant | only, epilogue=args.int8_out)
+        L = Int8Layer(s, seed_for(args.config, args.layer), args.variant | only | (abed.LOCAL if args.local else 0), epilogue=args.int8_out)
     for _ in range(args.reps):
         L.run()
     torch.cuda.synchronize()
