@@ -37,6 +37,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("3x3_c512_7", 32, "layer", (16, 8, 64, 4, 5, 9)): 16.2e6 + 7.9e6,
     ("3x3_c256_14", 32, "layer", (16, 12, 64, 13, 3, 5)): 12.7e6 + 9.9e6,
     ("3x3_c128_28", 32, "layer", (16, 8, 80, 49, 5, 2)): 12.8e6 + 20.9e6,
+    ("3x3_c64_56", 32, "local", (64, 8, 64, 49, 4, 1)): 9.7e6 + 34.3e6,
 }
 
 

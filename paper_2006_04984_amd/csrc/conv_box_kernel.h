@@ -119,6 +119,9 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
     __shared__ __attribute__((aligned(1024))) int8_t lds[LDS_BYTES];
 
+#ifdef ABED_ENABLE_DBG
+    if (p.dbg & 16) return;      // launch floor
+#endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lg = lane >> 4, lj = lane & 15;
@@ -329,6 +332,9 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     const int nsteps_real = nbatch * p.nch;
     const int nsteps = (nbatch + (IC ? 1 : 0)) * p.nch;
     const int nsub = nsteps * 3;
+#ifdef ABED_ENABLE_DBG
+    if (p.dbg & 32) { if (p.flags && tid == 0) p.flags[(box * p.nranges + range) * p.grid_n + kt] = (uint32_t)(a_off[0] + b_off[0] + msk_b) & 0u; return; }   // set-up only
+#endif
     // prologue: the first filter sub-stage and the first A stage, then (NBR == 3) the second filter sub-stage
     issue_b(0, 0, 0);
     issue_a(0, 0, 0);
