@@ -371,20 +371,44 @@ def split_hi_lo(s):
     return np.stack([hi, lo])
 
 
-def threshold_bad(s, c, rtol, atol):
-    """Mismatch test for floating point: |s - c| > rtol * max(|s|, |c|) + atol."""
+def threshold_bad(s, c, rtol, atol, mag=None):
+    """Mismatch test for floating point (Sec. 7: the two reduced values are "close enough" when they
+    differ by no more than a threshold).  Two readings of the threshold's magnitude:
+
+    mag is None: relative to the compared values, tol = rtol * max(|s|, |c|) + atol;
+    mag given  : relative to the L1 norm of what was reduced, tol = rtol * mag + atol with
+                 mag = sum of |y| over the elements that s sums (rounding error of a sum grows with
+                 that norm, not with the sum, which may cancel to zero).
+
+    A mismatch is  not (|s - c| <= tol); a NaN or an infinity on either side is a mismatch."""
     s = np.asarray(s, dtype=np.float64)
     c = np.asarray(c, dtype=np.float64)
-    return np.abs(s - c) > rtol * np.maximum(np.abs(s), np.abs(c)) + atol
+    with np.errstate(invalid="ignore"):
+        scale = np.maximum(np.abs(s), np.abs(c)) if mag is None else np.asarray(mag, dtype=np.float64)
+        tol = rtol * scale + atol
+        ok = (np.abs(s - c) <= tol) & np.isfinite(s) & np.isfinite(c) & np.isfinite(tol)
+    return ~ok
 
 
-def abed_fp16(x, w, shape, rtol, atol, wchk=None, xchk=None, acc_flip=None, out_dtype=np.float16):
+def threshold_margin(s, c, rtol, atol, mag=None):
+    """|s - c| - tol of threshold_bad (positive = mismatch), for guard bands around the decision."""
+    s = np.asarray(s, dtype=np.float64)
+    c = np.asarray(c, dtype=np.float64)
+    with np.errstate(invalid="ignore"):
+        scale = np.maximum(np.abs(s), np.abs(c)) if mag is None else np.asarray(mag, dtype=np.float64)
+        return np.abs(s - c) - (rtol * scale + atol)
+
+
+def abed_fp16(x, w, shape, rtol, atol, wchk=None, xchk=None, acc_flip=None, out_dtype=np.float16, l1=False):
     """Checked fp16 convolution, double-precision reference.
 
     The reductions are taken over the (double) accumulators before the output
     is rounded, as the fused kernels reduce their fp32 accumulators.  acc_flip =
     (flat index, bit 0..15) flips a bit of the value rounded to fp16, and the
     corrupted value replaces the accumulator in the reductions and in the store.
+    l1 selects the threshold's magnitude (threshold_bad): the compared values, or the sum of |y| over
+    the reduced elements (rs_abs over the filters for FC, cs_abs over the batch for IC; for the corner
+    the same norms of the checksum fmaps).
     Returns y (out_dtype), yf, yi, yfi, rs, cs (float64), fc_bad, ic_bad,
     corner_bad, and the signed margins  |s-c| - tol  of both checks."""
     x = np.asarray(x, dtype=np.float16)
@@ -403,14 +427,14 @@ def abed_fp16(x, w, shape, rtol, atol, wchk=None, xchk=None, acc_flip=None, out_
     yi = conv_f64(xchk, w, shape).sum(axis=0)
     yfi = conv_f64(xchk, wchk, shape).sum(axis=(0, 3))
     rs, cs = y.sum(axis=3), y.sum(axis=0)
+    rs_abs, cs_abs = np.abs(y).sum(axis=3), np.abs(y).sum(axis=0)
 
-    def margin(s, c):
-        return np.abs(s - c) - (rtol * np.maximum(np.abs(s), np.abs(c)) + atol)
-
-    res = dict(y=y.astype(out_dtype), y_exact=y, yf=yf, yi=yi, yfi=yfi, rs=rs, cs=cs, wchk=wchk, xchk=xchk)
-    res["fc_margin"], res["ic_margin"] = margin(rs, yf), margin(cs, yi)
-    with np.errstate(invalid="ignore"):
-        res["fc_bad"] = ~(res["fc_margin"] <= 0)               # NaN/Inf count as mismatches
-        res["ic_bad"] = ~(res["ic_margin"] <= 0)
-        res["corner_bad"] = (~(margin(yf.sum(axis=0), yfi) <= 0)) | (~(margin(yi.sum(axis=2), yfi) <= 0))
+    res = dict(y=y.astype(out_dtype), y_exact=y, yf=yf, yi=yi, yfi=yfi, rs=rs, cs=cs, rs_abs=rs_abs, cs_abs=cs_abs,
+               wchk=wchk, xchk=xchk)
+    res["fc_margin"] = threshold_margin(rs, yf, rtol, atol, rs_abs if l1 else None)
+    res["ic_margin"] = threshold_margin(cs, yi, rtol, atol, cs_abs if l1 else None)
+    res["fc_bad"] = threshold_bad(rs, yf, rtol, atol, rs_abs if l1 else None)
+    res["ic_bad"] = threshold_bad(cs, yi, rtol, atol, cs_abs if l1 else None)
+    res["corner_bad"] = (threshold_bad(yf.sum(axis=0), yfi, rtol, atol, np.abs(yf).sum(axis=0) if l1 else None)
+                         | threshold_bad(yi.sum(axis=2), yfi, rtol, atol, np.abs(yi).sum(axis=2) if l1 else None))
     return res

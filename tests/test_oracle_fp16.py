@@ -65,6 +65,82 @@ def test_threshold_rule_hand_cases(oracle):
     c = np.array([100.05, 100.2, 0.0005, 0.002, 50.0, 1.0, 1.0])
     bad = oracle.threshold_bad(s, c, 1e-3, 1e-3)
     assert list(bad[:5]) == [False, True, False, True, True]
+    # an infinity or a NaN on either side is a mismatch, whatever the tolerance works out to
+    assert list(bad[5:]) == [True, True]
+    assert list(oracle.threshold_bad(np.array([1.0, 1.0, np.inf]), np.array([np.inf, np.nan, np.inf]), 1e-3, 1e-3)) == [True] * 3
+    assert list(oracle.threshold_bad(np.array([np.nan]), np.array([1.0]), 0.0, np.inf)) == [True]
+
+
+def test_l1_threshold_hand_cases(oracle):
+    """Threshold relative to the L1 norm of the reduced elements: tol = rtol * sum|y| + atol."""
+    # two elements that cancel: s = 1e-4 against a checksum of 0.  Relative to the values the tolerance is
+    # 1e-3 * 1e-4 and the check fails; relative to sum|y| = 1.9999 it is 2e-3 and the check passes
+    y = np.array([1.0, -0.9999])
+    assert oracle.threshold_bad(y.sum(), 0.0, 1e-3, 0.0)
+    assert not oracle.threshold_bad(y.sum(), 0.0, 1e-3, 0.0, mag=np.abs(y).sum())
+    # no cancellation: both readings agree (2 against 2.01: tolerance 2.01e-3 and 2e-3)
+    y = np.array([1.0, 1.0])
+    assert oracle.threshold_bad(y.sum(), 2.01, 1e-3, 0.0) and oracle.threshold_bad(y.sum(), 2.01, 1e-3, 0.0, mag=2.0)
+    assert not oracle.threshold_bad(y.sum(), 2.001, 1e-3, 0.0, mag=2.0)
+    # the boundary itself passes (<=), one ulp beyond fails; atol adds
+    assert not oracle.threshold_bad(0.5, 0.0, 0.25, 0.0, mag=2.0)
+    assert oracle.threshold_bad(np.nextafter(0.5, 1.0), 0.0, 0.25, 0.0, mag=2.0)
+    assert not oracle.threshold_bad(0.75, 0.0, 0.25, 0.25, mag=2.0)
+    # margins have the sign of the decision
+    assert oracle.threshold_margin(0.75, 0.0, 0.25, 0.0, mag=2.0) == 0.25
+    assert oracle.threshold_margin(3.0, 1.0, 0.5, 0.0) == 0.5
+    # non-finite sums or norms are mismatches
+    assert oracle.threshold_bad(np.inf, 1.0, 1e-3, 0.0, mag=np.inf) and oracle.threshold_bad(1.0, 1.0, 1e-3, 0.0, mag=np.nan)
+
+
+@pytest.mark.parametrize("s", SHAPES, ids=lambda s: s.name)
+def test_l1_threshold_on_convolutions(oracle, s):
+    x, w = fp16_tensors(s, 24)
+    r = oracle.abed_fp16(x, w, s, rtol=1e-5, atol=0.0, l1=True)
+    # the norms are what they say: recomputed from the library convolution
+    y = torch_conv_f64(x, w, s)
+    np.testing.assert_allclose(r["rs_abs"], np.abs(y).sum(3), rtol=1e-12)
+    np.testing.assert_allclose(r["cs_abs"], np.abs(y).sum(0), rtol=1e-12)
+    assert np.all(r["rs_abs"] >= np.abs(r["rs"])) and np.all(r["cs_abs"] >= np.abs(r["cs"]))
+    # clean data: the only error is the hi/lo rounding of the checksums (2^-22 relative), far below 1e-5 of the norm
+    assert not (r["fc_bad"].any() or r["ic_bad"].any() or r["corner_bad"].any())
+    # same data, same tolerance relative to the values: never fewer mismatches on clean data (sum|y| >= |sum y|, and
+    # the checksum side equals the sum to rounding)
+    lit = oracle.abed_fp16(x, w, s, rtol=1e-5, atol=0.0)
+    assert np.all(lit["fc_margin"] >= r["fc_margin"] - 1e-9) and np.all(lit["ic_margin"] >= r["ic_margin"] - 1e-9)
+    # an exponent-bit flip is found and localised under both readings; the lowest mantissa bit under neither at 1e-3
+    idx = ((1 * s.P + 1) * s.Q + 2) * s.K + 3
+    for l1 in (False, True):
+        f = oracle.abed_fp16(x, w, s, 1e-3, 1e-3, acc_flip=(idx, 14), l1=l1)
+        assert f["fc_bad"][1, 1, 2] and f["fc_bad"].sum() == 1 and f["ic_bad"][1, 2, 3] and f["ic_bad"].sum() == 1
+        f = oracle.abed_fp16(x, w, s, 1e-3, 1e-3, acc_flip=(idx, 0), l1=l1)
+        assert not (f["fc_bad"].any() or f["ic_bad"].any())
+
+
+@pytest.mark.parametrize("l1", [False, True])
+def test_corner_mismatch(oracle, l1):
+    """A corrupted checksum tensor shows in the corner (Sec. 2.1: the checksum row and column are checked against
+    each other): the checksum image enters yi and yfi, so the IC comparison fails where the element is used while
+    sum_k yi still agrees with yfi; but sum_n yf, made from the real images, no longer agrees with yfi."""
+    s = SHAPES[2]
+    x, w = fp16_tensors(s, 25)
+    clean = oracle.abed_fp16(x, w, s, 1e-3, 1e-3, l1=l1)
+    assert not clean["corner_bad"].any()
+    xchk = clean["xchk"].copy()
+    h0, w0, c0 = 2, 3, 5
+    oracle.flip_bit(xchk[0], (h0 * s.W + w0) * s.C + c0, 14)           # a high exponent bit of the hi part
+    r = oracle.abed_fp16(x, w, s, 1e-3, 1e-3, xchk=xchk, l1=l1)
+    # output positions whose 3x3 window (pad 1, stride 1) covers (h0, w0)
+    cover = np.zeros((s.P, s.Q), dtype=bool)
+    cover[max(h0 - 1, 0):h0 + 2, max(w0 - 1, 0):w0 + 2] = True
+    assert np.array_equal(r["corner_bad"], cover)
+    assert not r["fc_bad"].any()                                       # the real rows and their filter checksum are intact
+    assert np.array_equal(r["ic_bad"].any(axis=2), cover)              # the column check sees the bad checksum image
+    # the same for a corrupted checksum filter: every position uses every filter element (up to padding)
+    wchk = clean["wchk"].copy()
+    oracle.flip_bit(wchk[0], (1 * s.S + 1) * s.C + 2, 14)              # centre tap: used at every output position
+    r = oracle.abed_fp16(x, w, s, 1e-3, 1e-3, wchk=wchk, l1=l1)
+    assert r["corner_bad"].all() and r["fc_bad"].all() and not r["ic_bad"].any()
 
 
 def test_output_flip_detection(oracle):
