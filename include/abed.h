@@ -104,6 +104,14 @@ typedef enum {
  * C/64 in {1, 2, 4, 8} with the batch checksum; else ABED_EUNSUPPORTED. */
 #define ABED_LOCAL 0x800
 
+/* fp16 only (Sec. 7: the reduced values are compared "using a threshold", chosen by heuristics).  OR into
+ * ABED_FUSED_OCG of abed_conv_fp16: the threshold is taken relative to the sum of magnitudes of the elements that
+ * were reduced, tol = rtol * sum|y| + atol (sum over the real filters of the row for FC, over the real images for
+ * IC, of the fp32 accumulators), instead of relative to the compared values.  Rounding error of a sum grows with
+ * that norm, so sums that cancel to near zero no longer fail at atol = 0.  With int8 data or another variant:
+ * ABED_EINVAL. */
+#define ABED_L1_THRESHOLD 0x1000
+
 typedef enum { ABED_INT8 = 0, ABED_FP16 = 1 } abed_dtype_t;
 
 typedef struct {
@@ -243,9 +251,10 @@ abed_status_t abed_conv_int8_static(const abed_conv_desc_t *desc, const int8_t *
                                     const abed_inject_t *inject, void *y2, void *stream);
 
 /* Checked fp16 convolution (fp32 accumulation; Sec. 7).  As above with fp16
- * data; y is fp16 (out_fp32 == 0) or fp32.  A check fails when
- * |s - c| > rtol * max(|s|, |c|) + atol, s the reduction of the real
- * accumulators and c the checksum-path value (NaN counts as a failure). */
+ * data; y is fp16 (out_fp32 == 0) or fp32.  A check fails unless
+ * |s - c| <= rtol * max(|s|, |c|) + atol, s the reduction of the real
+ * accumulators and c the checksum-path value (with ABED_L1_THRESHOLD: rtol * sum|y| + atol);
+ * a NaN or an infinity on either side is a failure. */
 abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const void *w,
                              const void *wchk, void *xchk, int32_t compute_xchk,
                              void *y, int32_t out_fp32, int32_t variant, float rtol, float atol,

@@ -28,6 +28,7 @@ class Variant(enum.IntEnum):
 # OR one of these into a checked variant to run one scheme alone (include/abed.h)
 ONLY_FC = 0x100
 ONLY_IC = 0x200
+L1_THRESHOLD = 0x1000   # fp16: threshold relative to the sum of magnitudes of the reduced elements
 PACKED_FC = 0x400   # checksum filters in the free rows of the last block of 16 filters (wchk must follow w)
 LOCAL = 0x800       # checksums local to a workgroup: FC per filter tile, IC per batch tile, formed inside the kernel
 

@@ -65,6 +65,7 @@ struct Plan {
     int wm, wk, mb;                       // entries per wave, filter blocks per tile, entries per tile
     int kg;                               // groups of 4 waves along the reduction axis
     int variant;                          // the variant without the scheme selection bits
+    int l1;                               // fp16: threshold relative to the sum of magnitudes
     int packed;                           // digit filters in the free rows of the last real filter block
     int grid_m, grid_b, grid_n;
     // workspace offsets in bytes (-1 = unused)
@@ -176,14 +177,17 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return ABED_EINVAL;
     // scheme selection bits: one of FC alone / IC alone, with a checked variant only
     const int packed = variant & ABED_PACKED_FC;
-    const int only = variant & ~0xff & ~ABED_PACKED_FC;
+    const int l1 = variant & ABED_L1_THRESHOLD;
+    const int only = variant & ~0xff & ~ABED_PACKED_FC & ~ABED_L1_THRESHOLD;
     variant &= 0xff;
     if (variant < ABED_NONE || variant > ABED_DUPLICATE) return ABED_EINVAL;
     if (only != 0 && only != ABED_ONLY_FC && only != ABED_ONLY_IC) return ABED_EINVAL;
     if (only != 0 && !(variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG)) return ABED_EINVAL;
     if (only == ABED_ONLY_FC && variant == ABED_FUSED_IOCG) return ABED_EINVAL;
     if (packed && (only == ABED_ONLY_IC || dtype != ABED_INT8 || !(variant == ABED_FUSED_OCG || variant == ABED_FUSED_IOCG))) return ABED_EINVAL;
+    if (l1 && (dtype != ABED_FP16 || variant != ABED_FUSED_OCG)) return ABED_EINVAL;
     pl.variant = variant;
+    pl.l1 = l1 ? 1 : 0;
     pl.packed = 0;
     if (dtype != ABED_INT8 && dtype != ABED_FP16) return ABED_EINVAL;
     const bool f16 = dtype == ABED_FP16;
@@ -234,8 +238,8 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
         pl.off_yfi = take((long long)pl.d_i * pl.PQ * pl.d_f * 4);
     } else if (variant == ABED_FUSED_PARTIAL_REDUCTION || variant == ABED_FUSED_OCG || variant == ABED_FUSED_IOCG) {
         const long long tiles = (long long)pl.grid_m * pl.grid_b * pl.grid_n;
-        pl.off_fc = take(tiles * pl.mb * 16 * 4 * (f16 ? 2 : 1));     // fp16 keeps sum and checksum value apart
-        pl.off_ic = take(tiles * pl.wk * 256 * 4 * (f16 ? 2 : 1));
+        pl.off_fc = take(tiles * pl.mb * 16 * 4 * (f16 ? 3 : 1));     // fp16 keeps sum, checksum value and sum of magnitudes apart
+        pl.off_ic = take(tiles * pl.wk * 256 * 4 * (f16 ? 3 : 1));
         if (variant == ABED_FUSED_IOCG) pl.off_nx = take(tiles * pl.wk * 256 * 4);
     }
     pl.ws_bytes = off;
@@ -1224,7 +1228,7 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
     ConvParams cp;
     fill_params(cp, desc, pl);
     cp.x = (const int8_t *)x; cp.w = (const int8_t *)w; cp.wchk = (const int8_t *)wchk; cp.xchk = (const int8_t *)xchk;
-    cp.y = y; cp.flags = flags; cp.out_fp32 = out_fp32 ? 1 : 0; cp.rtol = rtol; cp.atol = atol;
+    cp.y = y; cp.flags = flags; cp.out_fp32 = out_fp32 ? 1 : 0; cp.rtol = rtol; cp.atol = atol; cp.l1 = pl.l1;
     set_injection(cp, desc, pl, inject);
     const int grid = (pl.grid_m * pl.grid_b * pl.grid_n + 7) / 8 * 8;   // whole rounds over the 8 XCDs
     if (variant == ABED_NONE || variant == ABED_DUPLICATE) {

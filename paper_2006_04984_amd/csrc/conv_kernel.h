@@ -92,6 +92,7 @@ struct ConvParams {
     int dbg;          // timing experiments (builds with ABED_ENABLE_DBG only): bit 0 ends the kernel before its stores, bit 1 skips the main loop
     int out_fp32;      // fp16 path: 1 = fp32 output
     float rtol, atol;  // fp16 path: threshold of the checks
+    int l1;            // fp16 path: threshold relative to the sum of magnitudes of the reduced elements
     // FIC scheme (Sec. 3.3).  fic_ocs: per-tile sums of all accumulators [ntiles], or null.  The first
     // fic_rows_lead workgroups of the launch (the number of pieces of the input checksum, fic_parts * H *
     // ceil(C / 64), rounded up to a multiple of 8; 0 = none) make the input checksum and its partial dot
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
     constexpr int L = (NB + 3) / 4;            // direct-to-LDS loads per wave and step
     constexpr int SUB = NB * 1024;              // one 64-byte step of the tile
     constexpr int STAGE = KG * SUB;
-    constexpr int EPI_BYTES = (F16 ? 8 : 4) * WK * 1024 + 128 + (F16 ? 0 : WK * 128);   // + misc words, + the tile's scale and bias
+    constexpr int EPI_BYTES = (F16 ? 12 : 4) * WK * 1024 + 128 + (F16 ? 0 : WK * 128);   // + misc words, + the tile's scale and bias
     constexpr int RED_BYTES = (KG - 1) * 4 * WM * WK * 1024;   // accumulators of groups 1..KG-1
     constexpr int FIC_BYTES = F16 ? 0 : kFicRowsLdsBytes;      // the input checksum workgroups of the FIC scheme
     constexpr int LDS_MIN0 = EPI_BYTES > RED_BYTES ? EPI_BYTES : RED_BYTES;
@@ -547,15 +548,19 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         // ---------------- epilogue, fp16 data (Sec. 7) ----------------
         const int pix = pg * 16 + lj;
         const bool pvalid = pix < PQ;
-        float *e_ic = reinterpret_cast<float *>(lds);            // [2][4 waves][WK][64 lanes][4]: sums, checksum values
-        int *e_misc = reinterpret_cast<int *>(e_ic + 8 * WK * 256);
+        float *e_ic = reinterpret_cast<float *>(lds);            // [3][4 waves][WK][64 lanes][4]: sums, checksum values, sums of magnitudes
+        int *e_misc = reinterpret_cast<int *>(e_ic + 12 * WK * 256);
         if (tid < 4) e_misc[tid] = 0;     // [1], [2]: "last arriver" marks, read after later barriers
         uint32_t my_flag = 0;
         // a scheme that is not selected (d_f or d_i zero) has nothing to exchange
         const bool fc_local = p.grid_n == 1 || p.d_f == 0, ic_local = p.grid_b == 1 || p.d_i == 0;
         const bool checking = p.mode == MODE_CHECK;
-        auto bad = [&](float sum, float chk) {
-            return !(fabsf(sum - chk) <= p.rtol * fmaxf(fabsf(sum), fabsf(chk)) + p.atol);   // NaN counts as a mismatch
+        // The threshold is relative to the larger of the two compared values or, with p.l1, to the sum of
+        // magnitudes of what was reduced (Sec. 7 leaves its choice open).  NaN and infinity are mismatches.
+        auto bad = [&](float sum, float chk, float mag) {
+            const float tol = p.rtol * (p.l1 ? mag : fmaxf(fabsf(sum), fabsf(chk))) + p.atol;
+            return !(fabsf(sum - chk) <= tol) || !(fabsf(sum) < __builtin_inff()) || !(fabsf(chk) < __builtin_inff()) ||
+                   !(tol < __builtin_inff());
         };
         // (1) fault injection: one bit of the value rounded to fp16; the corrupted value takes the
         // accumulator's place in the reductions and in the store
@@ -577,22 +582,26 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
                 const int e = nt * MB + wave * WM + i;
-                float sum = 0.f, chk = 0.f;
+                float sum = 0.f, chk = 0.f, mag = 0.f;
 #pragma unroll
                 for (int kb = 0; kb < WK; ++kb) {
                     const int fb = kt * WK + kb;
                     const float t = (acc[i][kb][0] + acc[i][kb][1]) + (acc[i][kb][2] + acc[i][kb][3]);
-                    if (fb < p.kblk) sum += t;
-                    else if (fb == p.kblk) chk += t;      // rows 2..15 of the checksum block are zero filters
+                    if (fb < p.kblk) {
+                        sum += t;
+                        mag += (fabsf(acc[i][kb][0]) + fabsf(acc[i][kb][1])) + (fabsf(acc[i][kb][2]) + fabsf(acc[i][kb][3]));
+                    } else if (fb == p.kblk) chk += t;      // rows 2..15 of the checksum block are zero filters
                 }
                 sum += __shfl_xor(sum, 16, 64); sum += __shfl_xor(sum, 32, 64);
                 chk += __shfl_xor(chk, 16, 64); chk += __shfl_xor(chk, 32, 64);
+                mag += __shfl_xor(mag, 16, 64); mag += __shfl_xor(mag, 32, 64);
                 if (checking && fc_local) {
-                    if (bad(sum, chk)) my_flag |= (e < p.N) ? 1u : 4u;
+                    if (bad(sum, chk, mag)) my_flag |= (e < p.N) ? 1u : 4u;
                 } else if (lg == 0) {
-                    int *dst = &p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + kt) * (2 * MB * 16) + (wave * WM + i) * 16 + lj];
+                    int *dst = &p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + kt) * (3 * MB * 16) + (wave * WM + i) * 16 + lj];
                     st_dev(dst, __builtin_bit_cast(int, sum));
                     st_dev(dst + MB * 16, __builtin_bit_cast(int, chk));
+                    st_dev(dst + 2 * MB * 16, __builtin_bit_cast(int, mag));
                 }
             }
         }
@@ -606,35 +615,40 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
             if (p.d_i) {
 #pragma unroll
             for (int kb = 0; kb < WK; ++kb) {
-                f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
+                f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f}, mag = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int i = 0; i < WM; ++i) {
                     const int e = nt * MB + wave * WM + i;
-                    if (e < p.N) sum += acc[i][kb];
-                    else if (e < p.n_entries) chk += acc[i][kb];
+                    if (e < p.N) {
+                        sum += acc[i][kb];
+                        mag += f32x4{fabsf(acc[i][kb][0]), fabsf(acc[i][kb][1]), fabsf(acc[i][kb][2]), fabsf(acc[i][kb][3])};
+                    } else if (e < p.n_entries) chk += acc[i][kb];
                 }
                 *reinterpret_cast<f32x4 *>(e_ic + ((wave * WK + kb) * 64 + lane) * 4) = sum;
                 *reinterpret_cast<f32x4 *>(e_ic + 4 * WK * 256 + ((wave * WK + kb) * 64 + lane) * 4) = chk;
+                *reinterpret_cast<f32x4 *>(e_ic + 8 * WK * 256 + ((wave * WK + kb) * 64 + lane) * 4) = mag;
             }
             __syncthreads();
 #pragma unroll
             for (int c4 = 0; c4 < (WK + 3) / 4; ++c4) {
                 const int kb = 4 * c4 + wave;
                 if (kb >= WK) continue;
-                f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
+                f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f}, mag = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     sum += *reinterpret_cast<const f32x4 *>(e_ic + ((w * WK + kb) * 64 + lane) * 4);
                     chk += *reinterpret_cast<const f32x4 *>(e_ic + 4 * WK * 256 + ((w * WK + kb) * 64 + lane) * 4);
+                    mag += *reinterpret_cast<const f32x4 *>(e_ic + 8 * WK * 256 + ((w * WK + kb) * 64 + lane) * 4);
                 }
                 const int fb = kt * WK + kb;
                 if (checking && ic_local) {
-                    if (bad(sum[0], chk[0]) || bad(sum[1], chk[1]) || bad(sum[2], chk[2]) || bad(sum[3], chk[3]))
+                    if (bad(sum[0], chk[0], mag[0]) || bad(sum[1], chk[1], mag[1]) || bad(sum[2], chk[2], mag[2]) || bad(sum[3], chk[3], mag[3]))
                         my_flag |= (fb < p.kblk) ? 2u : 4u;
                 } else {
-                    int *dst = p.ws_ic + ((((long long)pg * p.grid_n + kt) * p.grid_b + nt) * 2 * WK + kb) * 256 + lane * 4;
+                    int *dst = p.ws_ic + ((((long long)pg * p.grid_n + kt) * p.grid_b + nt) * 3 * WK + kb) * 256 + lane * 4;
                     st_dev4(dst, __builtin_bit_cast(i32x4, sum));
                     st_dev4(dst + WK * 256, __builtin_bit_cast(i32x4, chk));
+                    st_dev4(dst + 2 * WK * 256, __builtin_bit_cast(i32x4, mag));
                 }
             }
             }
@@ -694,33 +708,35 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         if (e_misc[1]) {
             uint32_t late = 0;
             for (int r = tid; r < MB * 16; r += 256) {
-                float sum = 0.f, chk = 0.f;
+                float sum = 0.f, chk = 0.f, mag = 0.f;
                 for (int c = 0; c < p.grid_n; ++c) {
-                    const int *src = &p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + c) * (2 * MB * 16) + r];
+                    const int *src = &p.ws_fc[(((long long)pg * p.grid_b + nt) * p.grid_n + c) * (3 * MB * 16) + r];
                     sum += __builtin_bit_cast(float, ld_dev(src));
                     chk += __builtin_bit_cast(float, ld_dev(src + MB * 16));
+                    mag += __builtin_bit_cast(float, ld_dev(src + 2 * MB * 16));
                 }
-                if (bad(sum, chk)) late |= (nt * MB + (r >> 4) < p.N) ? 1u : 4u;
+                if (bad(sum, chk, mag)) late |= (nt * MB + (r >> 4) < p.N) ? 1u : 4u;
             }
             if (late) __hip_atomic_fetch_or(&p.flags[((long long)pg * p.grid_b + nt) * p.grid_n], late, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (tid == 0) __hip_atomic_store(&p.cnt_fc[pg * p.grid_b + nt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (e_misc[2]) {
             uint32_t late = 0;
-            // the partials of this (pixel group, filter tile): [grid_b][2][WK][256] words
+            // the partials of this (pixel group, filter tile): [grid_b][3][WK][256] words
             const __amdgpu_buffer_rsrc_t rs_ic = __builtin_amdgcn_make_buffer_rsrc(
-                (void *)(p.ws_ic + (((long long)pg * p.grid_n + kt) * p.grid_b) * 2 * WK * 256), 0, p.grid_b * 2 * WK * 1024, 0x00020000);
+                (void *)(p.ws_ic + (((long long)pg * p.grid_n + kt) * p.grid_b) * 3 * WK * 256), 0, p.grid_b * 3 * WK * 1024, 0x00020000);
             for (int idx = tid; idx < WK * 64; idx += 256) {
                 const int kb = idx >> 6, ln = idx & 63;
                 const int fb = kt * WK + kb;
-                f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f};
+                f32x4 sum = {0.f, 0.f, 0.f, 0.f}, chk = {0.f, 0.f, 0.f, 0.f}, mag = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
                 for (int b = 0; b < p.grid_b; ++b) {
-                    const int off = (((b * 2 * WK) + kb) * 256 + ln * 4) * 4;
+                    const int off = (((b * 3 * WK) + kb) * 256 + ln * 4) * 4;
                     sum += __builtin_bit_cast(f32x4, ld_dev4(rs_ic, off));
                     chk += __builtin_bit_cast(f32x4, ld_dev4(rs_ic, off + WK * 1024));
+                    mag += __builtin_bit_cast(f32x4, ld_dev4(rs_ic, off + 2 * WK * 1024));
                 }
-                if (bad(sum[0], chk[0]) || bad(sum[1], chk[1]) || bad(sum[2], chk[2]) || bad(sum[3], chk[3]))
+                if (bad(sum[0], chk[0], mag[0]) || bad(sum[1], chk[1], mag[1]) || bad(sum[2], chk[2], mag[2]) || bad(sum[3], chk[3], mag[3]))
                     late |= (fb < p.kblk) ? 2u : 4u;
             }
             if (late) __hip_atomic_fetch_or(&p.flags[((long long)pg * p.grid_b) * p.grid_n + kt], late, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

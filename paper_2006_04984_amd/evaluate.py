@@ -302,44 +302,65 @@ def cmd_fp16(args):
     wchk = torch.empty((2, s.R, s.S, s.C), dtype=torch.float16, device=DEV)
     xchk = torch.empty((2, s.H, s.W, s.C), dtype=torch.float16, device=DEV)
     abed.workspace_init(ws)
-    res = dict(layer=s.name, runs=args.trials, thresholds=[])
-    settings = [(1e-3, 0.0), (1e-3, 1e-3), (1e-3, 1e-2), (1e-3, 3e-2)]
+    res = dict(layer=s.name, runs=args.trials, thresholds=[],
+               note="a flip counts as detected only when the flag word that covers the flipped element (its pixel group and "
+                    "batch tile for FC, its pixel group and filter tile for IC) has the scheme's bit set and had it clear "
+                    "in the clean run of the same input; l1: threshold = rtol * sum|y| over the reduced elements + atol, "
+                    "otherwise rtol * max(|s|, |c|) + atol")
+    L1 = abed.L1_THRESHOLD
+    # (rtol, atol, threshold relative to the sum of magnitudes)
+    settings = [(1e-3, 0.0, False), (1e-3, 1e-3, False), (1e-3, 1e-2, False), (1e-3, 3e-2, False),
+                (1e-3, 0.0, True), (1e-4, 0.0, True), (1e-5, 0.0, True), (1e-6, 0.0, True)]
+    variant_of = lambda st: int(Variant.FUSED_OCG) | (L1 if st[2] else 0)
     clean_fp = {st: 0 for st in settings}
     tiles_fp = {st: 0 for st in settings}
+    clean_flags = {}
     for r in range(args.trials):
         xh, wh = fp16_tensors(s, seed_for(4, 0, r))
         x, w = torch.from_numpy(xh).to(DEV), torch.from_numpy(wh).to(DEV)
         abed.filter_prepare_fp16(desc, w, wchk)
-        for i, (rt, at) in enumerate(settings):
-            abed.conv_fp16(desc, x, w, wchk, xchk, i == 0, y, Variant.FUSED_OCG, rt, at, flags=flags, workspace=ws)
+        for i, st in enumerate(settings):
+            abed.conv_fp16(desc, x, w, wchk, xchk, i == 0, y, variant_of(st), st[0], st[1], flags=flags, workspace=ws)
             n = int((flags != 0).sum().item())
-            clean_fp[(rt, at)] += int(n > 0)
-            tiles_fp[(rt, at)] += n
+            clean_fp[st] += int(n > 0)
+            tiles_fp[st] += n
+            clean_flags[st] = flags.cpu().numpy().reshape(lay.grid_m, lay.grid_b, lay.grid_n).copy()
     # detection: flips of one bit of one fp16 output value, on the last input
     rng = np.random.default_rng(args.seed)
     det = {st: [0] * 16 for st in settings}
+    masked = {st: 0 for st in settings}        # flips whose covering words were already flagged in the clean run
     cnt = [0] * 16
+    PQK = s.P * s.Q * s.K
     for _ in range(args.trials):
         idx, bit = int(rng.integers(0, y.numel())), int(rng.integers(0, 16))
         cnt[bit] += 1
-        for (rt, at) in settings:
-            abed.conv_fp16(desc, x, w, wchk, xchk, False, y, Variant.FUSED_OCG, rt, at, flags=flags, workspace=ws,
+        n, rem = divmod(idx, PQK)
+        pix, k = divmod(rem, s.K)
+        fcw, icw = (pix // 16, n // lay.tile_batch, 0), (pix // 16, 0, k // lay.tile_n)
+        for st in settings:
+            abed.conv_fp16(desc, x, w, wchk, xchk, False, y, variant_of(st), st[0], st[1], flags=flags, workspace=ws,
                            inject=(1, idx, bit))
-            det[(rt, at)][bit] += int((flags != 0).any().item())
+            f = flags.cpu().numpy().reshape(lay.grid_m, lay.grid_b, lay.grid_n)
+            c = clean_flags[st]
+            fc_hit = bool(f[fcw] & 1) and not (c[fcw] & 1)
+            ic_hit = bool(f[icw] & 2) and not (c[icw] & 2)
+            det[st][bit] += int(fc_hit or ic_hit)
+            masked[st] += int(bool(c[fcw] & 1) and bool(c[icw] & 2))
     # throughput of the same layer: unchecked, checked (ICG + augmented convolution), duplicated
     stream = torch.cuda.Stream()
     y2 = torch.empty_like(y)
     t_plain = _graph_time(lambda: abed.conv_fp16(desc, x, w, None, None, False, y, Variant.NONE, 1e-3, 1e-3), stream)
     t_chk = _graph_time(lambda: abed.conv_fp16(desc, x, w, wchk, xchk, True, y, Variant.FUSED_OCG, 1e-3, 1e-3, flags=flags, workspace=ws), stream)
     t_dup = _graph_time(lambda: abed.conv_fp16(desc, x, w, None, None, False, y, Variant.DUPLICATE, 1e-3, 1e-3, flags=flags, workspace=ws, y2=y2), stream)
-    res["timing"] = dict(gflop=s.ops / 1e9, unchecked_us=t_plain * 1e6, checked_us=t_chk * 1e6, duplicate_us=t_dup * 1e6,
+    t_l1 = _graph_time(lambda: abed.conv_fp16(desc, x, w, wchk, xchk, True, y, int(Variant.FUSED_OCG) | L1, 1e-3, 0.0, flags=flags, workspace=ws), stream)
+    res["timing"] = dict(gflop=s.ops / 1e9, unchecked_us=t_plain * 1e6, checked_us=t_chk * 1e6, duplicate_us=t_dup * 1e6, checked_l1_threshold_us=t_l1 * 1e6,
                          unchecked_tflops=s.ops / t_plain / 1e12, checked_tflops=s.ops / t_chk / 1e12,
                          overhead_pct=100.0 * (t_chk / t_plain - 1.0), frac_of_fp16_peak=s.ops / t_plain / 1e12 / 2500.0)
     for st in settings:
-        res["thresholds"].append(dict(rtol=st[0], atol=st[1], clean_runs_with_a_flag=clean_fp[st],
+        res["thresholds"].append(dict(rtol=st[0], atol=st[1], l1=st[2], clean_runs_with_a_flag=clean_fp[st],
                                       flagged_tiles_per_clean_run=tiles_fp[st] / args.trials,
                                       tiles_per_run=int(lay.n_flag_words),
-                                      flips_detected=sum(det[st]), flips=args.trials,
+                                      flips_detected=sum(det[st]), flips=args.trials, flips_on_already_flagged_words=masked[st],
                                       detected_by_bit=det[st], flips_by_bit=cnt))
     print(json.dumps(res))
 

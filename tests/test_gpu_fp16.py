@@ -90,53 +90,74 @@ def test_fp16_clean(oracle, s, variant, out_fp32):
         assert flags[0] == 0 and torch.equal(g.y, g.y2)
 
 
+@pytest.mark.parametrize("rtol,atol,l1,guard", [(1e-3, 1e-2, False, 2e-3), (1e-3, 0.0, True, 2e-3), (1e-4, 0.0, True, 2e-4)],
+                         ids=["values_1e-3_floor_1e-2", "l1_1e-3", "l1_1e-4"])
 @pytest.mark.parametrize("s", [SHAPES[0], SHAPES[2]], ids=lambda s: s.name)
-def test_fp16_flip_detection_and_threshold(oracle, s):
+def test_fp16_flip_detection_and_threshold(oracle, s, rtol, atol, l1, guard):
     """Flips of one output bit: those the oracle puts clearly above the threshold must be flagged in
-    the right tile, those clearly below must not."""
+    the right tile, those clearly below must not; with the threshold relative to the compared values and
+    relative to the sum of magnitudes (no absolute floor)."""
     x, w = fp16_tensors(s, 6262)
-    g = GpuConv16(s, 4)
+    variant = 4 | (abed.L1_THRESHOLD if l1 else 0)
+    g = GpuConv16(s, variant)
     g.prepare(w)
-    g.run(x)
+    y, flags = g.run(x, rtol, atol)
     wchk, xchk = g.wchk.cpu().numpy(), g.xchk.cpu().numpy()
+    ref = oracle.abed_fp16(x, w, s, rtol, atol, wchk=wchk, xchk=xchk, l1=l1)
+    assert ref["fc_margin"].max() < -guard and ref["ic_margin"].max() < -guard and not flags.any()
     rng = np.random.default_rng(11)
-    rtol, atol = 1e-3, 1e-2
     decided = 0
     for trial in range(24):
         idx = int(rng.integers(0, s.N * s.P * s.Q * s.K))
         bit = int(rng.integers(0, 16))
         print("flip", s.name, idx, bit, flush=True)
         y, flags = g.run(x, rtol, atol, compute_xchk=False, inject=(1, idx, bit))
-        ref = oracle.abed_fp16(x, w, s, rtol, atol, wchk=wchk, xchk=xchk, acc_flip=(idx, bit))
+        ref = oracle.abed_fp16(x, w, s, rtol, atol, wchk=wchk, xchk=xchk, acc_flip=(idx, bit), l1=l1)
         f = flags.reshape(g.lay.grid_m, g.lay.grid_b, g.lay.grid_n) & 3
-        must = fold_margin(ref, s, g.lay, 2e-3)
-        may = fold_margin(ref, s, g.lay, -2e-3)
+        must = fold_margin(ref, s, g.lay, guard)
+        may = fold_margin(ref, s, g.lay, -guard)
         assert np.all((f & must) == must), "a flip above the threshold was missed"
         assert np.all((f & ~may) == 0), "a flag without a mismatch"
         decided += int(np.array_equal(must, may))
     assert decided >= 12
 
 
-def test_fp16_config4_shape_sampled(oracle):
-    """The fp16 layer of the benchmark configuration at full size: sampled outputs against the
-    oracle's single-element routine, and no flag on a clean run with a sensible absolute floor."""
+def test_fp16_nonfinite_is_a_mismatch(oracle):
+    """A flip that turns an output into an infinity or a NaN (exponent all ones) is flagged under both readings of
+    the threshold, also where a tolerance computed from the values would itself be infinite."""
+    s = SHAPES[0]
+    x, w = fp16_tensors(s, 6363)
+    ref = oracle.abed_fp16(x, w, s, 1e-3, 0.0)
+    # an element whose fp16 exponent field is 01111 (1 <= |y| < 2): flipping bit 14 gives 11111 = Inf / NaN
+    h = ref["y"].reshape(-1).view(np.uint16)
+    idx = int(np.flatnonzero(((h >> 10) & 31) == 15)[0])
+    for l1 in (False, True):
+        g = GpuConv16(s, 4 | (abed.L1_THRESHOLD if l1 else 0))
+        g.prepare(w)
+        y, flags = g.run(x, 1e-3, 1e-2, inject=(1, idx, 14))
+        assert not np.isfinite(y.reshape(-1)[idx])
+        r = oracle.abed_fp16(x, w, s, 1e-3, 1e-2, acc_flip=(idx, 14), l1=l1)
+        assert r["fc_bad"].sum() == 1 and r["ic_bad"].sum() == 1
+        f = flags.reshape(g.lay.grid_m, g.lay.grid_b, g.lay.grid_n)
+        n, rem = divmod(idx, s.P * s.Q * s.K)
+        pix, k = divmod(rem, s.K)
+        assert f[pix // 16, n // g.lay.tile_batch, 0] & 1 and f[pix // 16, 0, k // g.lay.tile_n] & 2
+
+
+def test_fp16_config4_full_tensor(oracle):
+    """The fp16 layer of the benchmark configuration at full size, whole tensor against the oracle; no flag on a
+    clean run at the stated relative threshold of 1e-3, neither with a floor of 2e-2 on the value-relative reading
+    nor with no floor at all on the magnitude-relative one, and the oracle agrees in both cases."""
     s = CONFIG4[0]
     x, w = fp16_tensors(s, 4000)
-    g = GpuConv16(s, 4)
-    g.prepare(w)
-    y, flags = g.run(x, rtol=1e-3, atol=2e-2)
-    assert not flags.any()
-    rng = np.random.default_rng(3)
-    pts = np.stack([rng.integers(0, d, 64) for d in (s.N, s.P, s.Q, s.K)], axis=1)
-    xs = np.ascontiguousarray(x[:, :, :, :], dtype=np.float64)
-    exact = np.empty(len(pts))
-    for e, (n, p, q, k) in enumerate(pts):
-        acc = 0.0
-        for r in range(3):
-            for c in range(3):
-                h, v = p - 1 + r, q - 1 + c
-                if 0 <= h < s.H and 0 <= v < s.W:
-                    acc += float(xs[n, h, v] @ w[k, r, c].astype(np.float64))
-        exact[e] = acc
-    got = y[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64)
-    assert np.all(np.abs(got - exact) <= 1e-2 * np.abs(exact) + 1e-3)
+    for l1, atol in ((False, 2e-2), (True, 0.0)):
+        print("config4", l1, flush=True)
+        g = GpuConv16(s, 4 | (abed.L1_THRESHOLD if l1 else 0))
+        g.prepare(w)
+        y, flags = g.run(x, rtol=1e-3, atol=atol)
+        ref = oracle.abed_fp16(x, w, s, 1e-3, atol, wchk=g.wchk.cpu().numpy(), xchk=g.xchk.cpu().numpy(), l1=l1)
+        check_outputs(y, ref)
+        assert np.isfinite(y).all()
+        assert not (ref["fc_bad"].any() or ref["ic_bad"].any() or ref["corner_bad"].any())
+        assert ref["fc_margin"].max() < -2e-3 and ref["ic_margin"].max() < -2e-3
+        assert not flags.any()
