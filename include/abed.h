@@ -251,7 +251,10 @@ abed_status_t abed_conv_int8_static(const abed_conv_desc_t *desc, const int8_t *
                                     const abed_inject_t *inject, void *y2, void *stream);
 
 /* Checked fp16 convolution (fp32 accumulation; Sec. 7).  As above with fp16
- * data; y is fp16 (out_fp32 == 0) or fp32.  A check fails unless
+ * data; y is fp16 (out_fp32 == 0) or fp32.  Variants ABED_NONE ... ABED_FUSED_OCG and ABED_DUPLICATE
+ * (ABED_FUSED_IOCG: ABED_EUNSUPPORTED); the variants that verify from memory keep ConvOut and the checksum
+ * fmaps as fp32 in the workspace and round the fp16 output from there.  inject: site 1 only, bit 0..15 of the
+ * value rounded to fp16.  A check fails unless
  * |s - c| <= rtol * max(|s|, |c|) + atol, s the reduction of the real
  * accumulators and c the checksum-path value (with ABED_L1_THRESHOLD: rtol * sum|y| + atol);
  * a NaN or an infinity on either side is a failure. */

@@ -185,7 +185,7 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     if (only != 0 && !(variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG)) return ABED_EINVAL;
     if (only == ABED_ONLY_FC && variant == ABED_FUSED_IOCG) return ABED_EINVAL;
     if (packed && (only == ABED_ONLY_IC || dtype != ABED_INT8 || !(variant == ABED_FUSED_OCG || variant == ABED_FUSED_IOCG))) return ABED_EINVAL;
-    if (l1 && (dtype != ABED_FP16 || variant != ABED_FUSED_OCG)) return ABED_EINVAL;
+    if (l1 && (dtype != ABED_FP16 || !(variant >= ABED_UNFUSED && variant <= ABED_FUSED_OCG))) return ABED_EINVAL;
     pl.variant = variant;
     pl.l1 = l1 ? 1 : 0;
     pl.packed = 0;
@@ -193,7 +193,7 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     const bool f16 = dtype == ABED_FP16;
     pl.esize = f16 ? 2 : 1;
     if ((d->C * pl.esize) % 16 != 0) return ABED_EUNSUPPORTED;   // 16-byte chunks of one filter tap
-    if (f16 && !(variant == ABED_NONE || variant == ABED_FUSED_OCG || variant == ABED_DUPLICATE)) return ABED_EUNSUPPORTED;
+    if (f16 && variant == ABED_FUSED_IOCG) return ABED_EUNSUPPORTED;   // fp16: no hand-over of the output's batch checksum
     const long long crs = (long long)d->C * d->R * d->S;
     if (crs > 65536) return ABED_EUNSUPPORTED;             // int32 accumulators are exact up to C*R*S = 64K (Sec. 4.1)
     // byte offsets inside a tensor are 32-bit (buffer descriptors); the largest offset marks "out of range"
@@ -1205,11 +1205,12 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
 {
     hipStream_t st = (hipStream_t)stream;
     Plan pl;
-    abed_status_t s = make_plan(desc, ABED_FP16, variant, false, pl);
+    // the variants that verify from memory keep an fp32 ConvOut in the workspace when the caller's output is fp16
+    abed_status_t s = make_plan(desc, ABED_FP16, variant, !out_fp32, pl);
     if (s != ABED_OK) return s;
     variant = pl.variant;
     if (!x || !w || !y) return ABED_EINVAL;
-    const bool checked = variant == ABED_FUSED_OCG;
+    const bool checked = variant >= ABED_UNFUSED && variant <= ABED_FUSED_OCG;
     if (checked && ((pl.d_f && !wchk) || (pl.d_i && !xchk) || !flags)) return ABED_EINVAL;
     if (checked && !(rtol >= 0.f && atol >= 0.f)) return ABED_EINVAL;
     if (variant == ABED_DUPLICATE && (!y2 || !flags)) return ABED_EINVAL;
@@ -1219,8 +1220,24 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
         if (inject->index < 0 || inject->index >= (long long)desc->N * pl.PQ * desc->K || inject->bit < 0 || inject->bit > 15)
             return ABED_EINVAL;
     }
+    if (!tile_compiled(pl.wm, pl.wk, pl.kg)) return ABED_EUNSUPPORTED;   // before anything is enqueued
     char *ws = (char *)workspace;
     auto wsp = [&](long long off) { return off < 0 ? (int32_t *)nullptr : (int32_t *)(ws + off); };
+    // an unchecked fp16 convolution of its own plan (the unfused variant's four convolutions)
+    auto plain16 = [&](const abed_conv_desc_t *d, const void *xin, const void *win, void *out, int fp32_out,
+                       const abed_inject_t *inj) -> abed_status_t {
+        Plan pp;
+        abed_status_t r = make_plan(d, ABED_FP16, ABED_NONE, false, pp);
+        if (r != ABED_OK) return r;
+        ConvParams c;
+        fill_params(c, d, pp);
+        c.x = (const int8_t *)xin; c.w = (const int8_t *)win; c.y = out; c.out_fp32 = fp32_out; c.mode = MODE_PLAIN;
+        set_injection(c, d, pp, inj);
+        const int g = (pp.grid_m * pp.grid_b * pp.grid_n + 7) / 8 * 8;
+        if (!launch_conv(true, pp.wm, pp.wk, pp.kg, c, g, st)) return ABED_EUNSUPPORTED;
+        LAUNCH_CHECK("conv_kernel (fp16, unchecked)");
+        return ABED_OK;
+    };
     if (checked && compute_xchk && pl.d_i) {
         s = abed_input_checksum_fp16(desc, x, xchk, stream);
         if (s != ABED_OK) return s;
@@ -1231,6 +1248,7 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
     cp.y = y; cp.flags = flags; cp.out_fp32 = out_fp32 ? 1 : 0; cp.rtol = rtol; cp.atol = atol; cp.l1 = pl.l1;
     set_injection(cp, desc, pl, inject);
     const int grid = (pl.grid_m * pl.grid_b * pl.grid_n + 7) / 8 * 8;   // whole rounds over the 8 XCDs
+    const long long words = (long long)pl.grid_m * pl.grid_b * pl.grid_n;
     if (variant == ABED_NONE || variant == ABED_DUPLICATE) {
         cp.mode = MODE_PLAIN;
         if (variant == ABED_DUPLICATE) fill_u32_kernel<<<1, 64, 0, st>>>(flags, 1, 0u);
@@ -1244,12 +1262,59 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
         LAUNCH_CHECK("conv_kernel (fp16, unchecked)");
         return ABED_OK;
     }
-    cp.mode = MODE_CHECK;
+    if (variant == ABED_UNFUSED || variant == ABED_FUSED_WRITE) {
+        // Sec. 4.3 applied to fp16 (Sec. 7): ConvOut and the checksum fmaps go to memory as fp32, a verify kernel
+        // reads them back, reduces and compares; the caller's fp16 output is rounded from the fp32 ConvOut last
+        const long long npqk = (long long)desc->N * pl.PQ * desc->K;
+        float *convout = out_fp32 ? (float *)y : (float *)wsp(pl.off_convout);
+        float *yf = (float *)wsp(pl.off_yf), *yi = (float *)wsp(pl.off_yi), *yfi = (float *)wsp(pl.off_yfi);
+        if (variant == ABED_UNFUSED) {
+            if ((s = plain16(desc, x, w, convout, 1, inject)) != ABED_OK) return s;
+            abed_conv_desc_t df = *desc; df.K = pl.d_f;               // x * checksum filters
+            if (pl.d_f && (s = plain16(&df, x, wchk, yf, 1, nullptr)) != ABED_OK) return s;
+            abed_conv_desc_t di = *desc; di.N = pl.d_i;               // checksum images * w
+            if (pl.d_i && (s = plain16(&di, xchk, w, yi, 1, nullptr)) != ABED_OK) return s;
+            abed_conv_desc_t dfi = di; dfi.K = pl.d_f;                // checksum images * checksum filters
+            if (pl.d_f && pl.d_i && (s = plain16(&dfi, xchk, wchk, yfi, 1, nullptr)) != ABED_OK) return s;
+        } else {
+            cp.y = convout; cp.out_fp32 = 1; cp.mode = MODE_WRITE;
+            cp.ws_yf = (int32_t *)yf; cp.ws_yi = (int32_t *)yi; cp.ws_yfi = (int32_t *)yfi;
+            if (!launch_conv(true, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
+            LAUNCH_CHECK("conv_kernel (fp16, augmented, write)");
+        }
+        VerifyF16Params vp;
+        vp.y = convout; vp.yf = yf; vp.yi = yi; vp.yfi = yfi; vp.flags = flags;
+        vp.N = desc->N; vp.PQ = pl.PQ; vp.K = desc->K; vp.d_f = pl.d_f; vp.d_i = pl.d_i;
+        vp.tile_batch = pl.mb; vp.tile_n = 16 * pl.wk; vp.grid_b = pl.grid_b; vp.grid_n = pl.grid_n;
+        vp.l1 = pl.l1; vp.rtol = rtol; vp.atol = atol;
+        fill_u32_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st>>>(flags, words, 0u);
+        LAUNCH_CHECK("fill_u32_kernel");
+        verify_f16_kernel<<<dim3(pl.PQ), dim3(256), 0, st>>>(vp);
+        LAUNCH_CHECK("verify_f16_kernel");
+        if (!out_fp32) {
+            cast_f32_f16_kernel<<<dim3((unsigned)((npqk + 255) / 256)), dim3(256), 0, st>>>(convout, (_Float16 *)y, npqk);
+            LAUNCH_CHECK("cast_f32_f16_kernel");
+        }
+        return ABED_OK;
+    }
+    cp.mode = variant == ABED_FUSED_PARTIAL_REDUCTION ? MODE_PARTIAL : MODE_CHECK;
     cp.cnt_fc = (uint32_t *)wsp(pl.off_cnt_fc);
     cp.cnt_ic = (uint32_t *)wsp(pl.off_cnt_ic);
     cp.ws_fc = wsp(pl.off_fc); cp.ws_ic = wsp(pl.off_ic);
+    if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
+        fill_u32_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st>>>(flags, words, 0u);
+        LAUNCH_CHECK("fill_u32_kernel");
+    }
     if (!launch_conv(true, pl.wm, pl.wk, pl.kg, cp, grid, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("conv_kernel (fp16, augmented)");
+    if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
+        FinishF16Params fp;
+        fp.fc = pl.d_f ? (const float *)cp.ws_fc : nullptr; fp.ic = pl.d_i ? (const float *)cp.ws_ic : nullptr; fp.flags = flags;
+        fp.N = desc->N; fp.kblk = pl.kblk; fp.tile_batch = pl.mb; fp.wk = pl.wk; fp.grid_b = pl.grid_b; fp.grid_n = pl.grid_n;
+        fp.l1 = pl.l1; fp.rtol = rtol; fp.atol = atol;
+        finish_f16_kernel<<<dim3(pl.grid_m * (pl.grid_b + pl.grid_n)), dim3(256), 0, st>>>(fp);
+        LAUNCH_CHECK("finish_f16_kernel");
+    }
     return ABED_OK;
 }
 

@@ -265,6 +265,135 @@ __global__ __launch_bounds__(256) void finish_i8_kernel(const FinishParams p)
     }
 }
 
+// fp16 data (Sec. 7): the comparison of a reduced sum with its checksum-path value.  tol is relative to the larger
+// of the two values or, with l1, to the sum of magnitudes of the reduced elements; a NaN or an infinity is a mismatch.
+__device__ __forceinline__ bool f16_check_fails(float sum, float chk, float mag, float rtol, float atol, int l1)
+{
+    const float tol = rtol * (l1 ? mag : fmaxf(fabsf(sum), fabsf(chk))) + atol;
+    return !(fabsf(sum - chk) <= tol) || !(fabsf(sum) < __builtin_inff()) || !(fabsf(chk) < __builtin_inff()) ||
+           !(tol < __builtin_inff());
+}
+
+struct VerifyF16Params {
+    const float *y;       // ConvOut, fp32 [N][PQ][K]
+    const float *yf;      // [N][PQ][d_f]   fmaps of the hi / lo checksum filters
+    const float *yi;      // [d_i][PQ][K]   fmaps of the hi / lo checksum images
+    const float *yfi;     // [d_i][PQ][d_f]
+    uint32_t *flags;      // [grid_m][grid_b][grid_n]
+    int N, PQ, K, d_f, d_i, tile_batch, tile_n, grid_b, grid_n, l1;
+    float rtol, atol;
+};
+
+__device__ __forceinline__ float wave_sum_f32(float v)
+{
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+// Variants that verify from memory (Sec. 4.3, unfused option), fp16 data: one workgroup per output pixel reads its
+// N x K block of the fp32 ConvOut twice (rows: one image per wave and pass, lanes along the filters; columns: one
+// filter per thread, images in sequence), sums in fp32 in a fixed order, and applies the threshold.  The flag words
+// must be zero on entry; bits go to the same words as in verify_i8_kernel.
+__global__ __launch_bounds__(256) void verify_f16_kernel(const VerifyF16Params p)
+{
+    __shared__ float red[4][4];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int pix = blockIdx.x, tm = pix >> 4;
+    float yf_sum = 0.f, yf_mag = 0.f, yi_sum = 0.f, yi_mag = 0.f;       // for the corner
+    if (p.d_f) {
+        for (int n = wave; n < p.N; n += 4) {
+            const float *src = p.y + ((long long)n * p.PQ + pix) * p.K;
+            float s = 0.f, m = 0.f;
+            for (int k = lane; k < p.K; k += 64) { const float v = src[k]; s += v; m += fabsf(v); }
+            s = wave_sum_f32(s); m = wave_sum_f32(m);
+            float c = 0.f;
+            for (int d = 0; d < p.d_f; ++d) c += p.yf[((long long)n * p.PQ + pix) * p.d_f + d];
+            if (lane == 0) {
+                if (f16_check_fails(s, c, m, p.rtol, p.atol, p.l1))
+                    atomicOr(&p.flags[((long long)tm * p.grid_b + n / p.tile_batch) * p.grid_n], 1u);
+                yf_sum += c; yf_mag += fabsf(c);
+            }
+        }
+    }
+    if (p.d_i) {
+        for (int k = tid; k < p.K; k += 256) {
+            float s = 0.f, m = 0.f;
+            for (int n = 0; n < p.N; ++n) { const float v = p.y[((long long)n * p.PQ + pix) * p.K + k]; s += v; m += fabsf(v); }
+            float c = 0.f;
+            for (int j = 0; j < p.d_i; ++j) c += p.yi[((long long)j * p.PQ + pix) * p.K + k];
+            if (f16_check_fails(s, c, m, p.rtol, p.atol, p.l1))
+                atomicOr(&p.flags[(long long)tm * p.grid_b * p.grid_n + k / p.tile_n], 2u);
+            yi_sum += c; yi_mag += fabsf(c);
+        }
+    }
+    if (!(p.d_f && p.d_i)) return;
+    // corner: sum_n yf and sum_k yi against conv(checksum images, checksum filters)
+    yi_sum = wave_sum_f32(yi_sum); yi_mag = wave_sum_f32(yi_mag);
+    if (lane == 0) { red[wave][0] = yf_sum; red[wave][1] = yf_mag; red[wave][2] = yi_sum; red[wave][3] = yi_mag; }
+    __syncthreads();
+    if (tid == 0) {
+        float t[4];
+        for (int q = 0; q < 4; ++q) t[q] = (red[0][q] + red[1][q]) + (red[2][q] + red[3][q]);
+        float c = 0.f;
+        for (int j = 0; j < p.d_i; ++j)
+            for (int d = 0; d < p.d_f; ++d) c += p.yfi[((long long)j * p.PQ + pix) * p.d_f + d];
+        if (f16_check_fails(t[0], c, t[1], p.rtol, p.atol, p.l1) || f16_check_fails(t[2], c, t[3], p.rtol, p.atol, p.l1))
+            atomicOr(&p.flags[(long long)tm * p.grid_b * p.grid_n], 4u);
+    }
+}
+
+struct FinishF16Params {
+    const float *fc;      // FC partials [grid_m][grid_b][grid_n][3][mb16]: sums, checksum values, sums of magnitudes
+    const float *ic;      // IC partials [grid_m][grid_n][grid_b][3][wk256]
+    uint32_t *flags;      // [grid_m][grid_b][grid_n], zero on entry
+    int N, kblk, tile_batch, wk, grid_b, grid_n, l1;
+    float rtol, atol;
+};
+
+// Partial-reduction variant, fp16 data: add the per-tile sums across tiles (in tile order) and apply the threshold.
+// Workgroups as in finish_i8_kernel.
+__global__ __launch_bounds__(256) void finish_f16_kernel(const FinishF16Params p)
+{
+    const int tid = threadIdx.x;
+    const int per_pg = p.grid_b + p.grid_n;
+    const int pg = blockIdx.x / per_pg, j = blockIdx.x - pg * per_pg;
+    const int mb16 = p.tile_batch * 16, wk256 = p.wk * 256;
+    unsigned found = 0;
+    if (j < p.grid_b) {
+        if (!p.fc) return;
+        const int nt = j;
+        const float *src = p.fc + ((long long)pg * p.grid_b + nt) * p.grid_n * 3 * mb16;
+        for (int r = tid; r < mb16; r += 256) {
+            float s = 0.f, c = 0.f, m = 0.f;
+            for (int kt = 0; kt < p.grid_n; ++kt) {
+                s += src[(kt * 3 + 0) * mb16 + r]; c += src[(kt * 3 + 1) * mb16 + r]; m += src[(kt * 3 + 2) * mb16 + r];
+            }
+            if (f16_check_fails(s, c, m, p.rtol, p.atol, p.l1)) found |= (nt * p.tile_batch + (r >> 4) < p.N) ? 1u : 4u;
+        }
+        if (found) atomicOr(&p.flags[((long long)pg * p.grid_b + nt) * p.grid_n], found);
+    } else {
+        if (!p.ic) return;
+        const int kt = j - p.grid_b;
+        const float *src = p.ic + ((long long)pg * p.grid_n + kt) * p.grid_b * 3 * wk256;
+        for (int r = tid; r < wk256; r += 256) {
+            float s = 0.f, c = 0.f, m = 0.f;
+            for (int nt = 0; nt < p.grid_b; ++nt) {
+                s += src[(nt * 3 + 0) * wk256 + r]; c += src[(nt * 3 + 1) * wk256 + r]; m += src[(nt * 3 + 2) * wk256 + r];
+            }
+            if (f16_check_fails(s, c, m, p.rtol, p.atol, p.l1)) found |= (kt * p.wk + (r >> 8) < p.kblk) ? 2u : 4u;
+        }
+        if (found) atomicOr(&p.flags[(long long)pg * p.grid_b * p.grid_n + kt], found);
+    }
+}
+
+// fp32 ConvOut -> fp16 output (the unfused variants keep the fp32 values for the verify kernel)
+__global__ void cast_f32_f16_kernel(const float *src, _Float16 *dst, long long total)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < total) dst[i] = (_Float16)src[i];
+}
+
 // Separate epilog (Sec. 4.3): ConvOut int32 -> int8, 4 elements per thread.
 __global__ void epilog_i8_kernel(const int32_t *acc, int8_t *out, const float *scale, const float *bias,
                                  int relu, long long total, int K)

@@ -578,7 +578,8 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                         }
         }
         // (2) FC: sum over the real filters of every row against hi + lo of the checksum-filter fmaps
-        if (aug && p.d_f) {
+        const bool reduce = aug && p.mode != MODE_WRITE;          // sums are formed in this kernel
+        if (reduce && p.d_f) {
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
                 const int e = nt * MB + wave * WM + i;
@@ -610,7 +611,7 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
 #endif
         const bool exchange = checking && !(fc_local && ic_local);
         const long long word = ((long long)pg * p.grid_b + nt) * p.grid_n + kt;
-        if (aug) {
+        if (reduce) {
             // (3) IC: sum over the real images of every (pixel, filter) against hi + lo of the checksum-image fmaps
             if (p.d_i) {
 #pragma unroll
@@ -679,6 +680,23 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         for (int kb = 0; kb < WK; ++kb) {
             const int fb = kt * WK + kb;
             const int k = fb * 16 + lg * 4;
+            if (p.mode == MODE_WRITE && pvalid) {
+                // the checksum fmaps go to the workspace as fp32 (the verify kernel reads them back): rows of the
+                // checksum images [d_i][PQ][K], columns of the checksum filters [N][PQ][d_f], their corner [d_i][PQ][d_f]
+#pragma unroll
+                for (int i = 0; i < WM; ++i) {
+                    const int e = nt * MB + wave * WM + i;
+                    if (fb < p.kblk && e >= p.N && e < p.n_entries) {
+                        float *dst = reinterpret_cast<float *>(p.ws_yi) + ((long long)(e - p.N) * PQ + pix) * p.K + k;
+                        for (int v = 0; v < 4; ++v)
+                            if (k + v < p.K) dst[v] = acc[i][kb][v];
+                    } else if (fb == p.kblk && lg == 0 && e < p.n_entries && p.d_f) {
+                        float *dst = e < p.N ? reinterpret_cast<float *>(p.ws_yf) + ((long long)e * PQ + pix) * p.d_f
+                                             : reinterpret_cast<float *>(p.ws_yfi) + ((long long)(e - p.N) * PQ + pix) * p.d_f;
+                        for (int v = 0; v < p.d_f; ++v) dst[v] = acc[i][kb][v];
+                    }
+                }
+            }
             if (fb >= p.kblk) continue;
 #pragma unroll
             for (int i = 0; i < WM; ++i) {
