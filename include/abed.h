@@ -206,6 +206,15 @@ abed_status_t abed_input_checksum_int8(const abed_conv_desc_t *desc, const int8_
 abed_status_t abed_input_checksum_fp16(const abed_conv_desc_t *desc, const void *x, void *xchk,
                                        void *stream);
 
+/* Channel padding for layers whose channel count the kernels do not take (C must be a multiple of 16 for int8,
+ * 8 for fp16; the 3-channel first layer of a network, which the paper's own evaluation leaves out, Sec. 5.2):
+ * dst[row][0..c_pad) = src[row][0..c) followed by zeros, for `rows` rows of elements of elem_bytes (1 or 2) bytes.
+ * Use it once offline on the filters (rows = K*R*S) and per call on the activations (rows = N*H*W), then describe
+ * the layer with C = c_pad: zero channels add nothing to the convolution or to any checksum, so outputs and checks
+ * are those of the unpadded layer.  src and dst are device pointers and must not overlap. */
+abed_status_t abed_pad_channels(const void *src, void *dst, int64_t rows, int32_t c, int32_t c_pad, int32_t elem_bytes,
+                                void *stream);
+
 /* Zero the part of a workspace that the library expects to be zero on first
  * use (arrival counters).  Call once after allocating a workspace. */
 abed_status_t abed_workspace_init(void *workspace, size_t workspace_bytes, void *stream);

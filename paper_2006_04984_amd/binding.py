@@ -73,7 +73,7 @@ class Ic2Layout(ctypes.Structure):
 EXPORTS = ["abed_fic_inloop_get_layout", "abed_fic_inloop_filter_prepare_int8", "abed_fic_inloop_conv_int8", "abed_fic_verify", "abed_ic2_get_layout", "abed_ic2_conv_int8", "abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
            "abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_local_int8", "abed_filter_prepare_fp16",
            "abed_input_checksum_int8", "abed_input_checksum_fp16", "abed_workspace_init",
-           "abed_conv_int8", "abed_conv_int8_static", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error", "abed_probe"]
+           "abed_conv_int8", "abed_conv_int8_static", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error", "abed_probe", "abed_pad_channels"]
 
 
 def lib_path():
@@ -175,6 +175,13 @@ def input_checksum_int8(desc, x, xchk, stream=None):
 def workspace_init(workspace, stream=None):
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().abed_workspace_init(_p(workspace), nbytes, _stream(stream)))
+
+
+def pad_channels(src, dst, c, c_pad, stream=None):
+    """abed_pad_channels: dst[..., :c] = src, dst[..., c:] = 0 for tensors whose last axis is the channels."""
+    rows = src.numel() // c
+    _check(lib().abed_pad_channels(_p(src), _p(dst), ctypes.c_int64(rows), int(c), int(c_pad), int(src.element_size()),
+                                   _stream(stream)))
 
 
 def conv_int8(desc, x, w, wchk, xchk, compute_xchk, y, variant, flags=None, epilogue=None, xchk_next=None,

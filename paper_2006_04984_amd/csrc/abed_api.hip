@@ -1197,6 +1197,18 @@ abed_status_t abed_conv_int8_static(const abed_conv_desc_t *desc, const int8_t *
                           ptr, (size_t)ABED_STATIC_SCRATCH_BYTES, inject, y2, stream);
 }
 
+abed_status_t abed_pad_channels(const void *src, void *dst, int64_t rows, int32_t c, int32_t c_pad, int32_t elem_bytes,
+                                void *stream)
+{
+    if (!src || !dst || rows < 1 || c < 1 || c_pad < c || (elem_bytes != 1 && elem_bytes != 2)) return ABED_EINVAL;
+    if (rows * (long long)c_pad >= (1LL << 40)) return ABED_EUNSUPPORTED;
+    const long long total = rows * c_pad;
+    pad_channels_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream>>>(
+        (const unsigned char *)src, (unsigned char *)dst, rows, c, c_pad, elem_bytes);
+    LAUNCH_CHECK("pad_channels_kernel");
+    return ABED_OK;
+}
+
 abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const void *w,
                              const void *wchk, void *xchk, int32_t compute_xchk,
                              void *y, int32_t out_fp32, int32_t variant, float rtol, float atol,

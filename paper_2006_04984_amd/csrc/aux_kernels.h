@@ -394,6 +394,18 @@ __global__ void cast_f32_f16_kernel(const float *src, _Float16 *dst, long long t
     if (i < total) dst[i] = (_Float16)src[i];
 }
 
+// Channel padding: dst[row][0..c_pad) = src[row][0..c) followed by zeros, elements of eb bytes.  One thread per
+// output byte quad would be wasteful for rows this short; one thread per output element is enough (the 3-channel
+// first layer of a network is padded once per call, its filters once offline).
+__global__ void pad_channels_kernel(const unsigned char *src, unsigned char *dst, long long rows, int c, int c_pad, int eb)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;     // output element
+    if (i >= rows * c_pad) return;
+    const long long row = i / c_pad;
+    const int ch = (int)(i - row * c_pad);
+    for (int b = 0; b < eb; ++b) dst[i * eb + b] = ch < c ? src[(row * c + ch) * eb + b] : (unsigned char)0;
+}
+
 // Separate epilog (Sec. 4.3): ConvOut int32 -> int8, 4 elements per thread.
 __global__ void epilog_i8_kernel(const int32_t *acc, int8_t *out, const float *scale, const float *bias,
                                  int relu, long long total, int K)
