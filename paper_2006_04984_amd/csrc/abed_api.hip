@@ -284,6 +284,7 @@ struct BoxPlan {
     int fb, fbr, xch;          // filter blocks per tile incl. the digit block, real ones, chunks of the batch checksum (0 = none)
     bool fc, ic;
     int boxes_x, boxes_y, grid_n, nranges, range_len;
+    int eh;                    // 2: workgroups of 8 waves, batches of 8 entries; 1: of 4 waves and 4 entries, two per CU
 };
 
 // Shapes the box kernel takes: 3x3, stride 1, padding below 3, channels in chunks of 64, filters in tiles of 64.
@@ -317,26 +318,30 @@ abed_status_t make_box_plan(const abed_conv_desc_t *d, bool want_fc, bool want_i
     if (!want_ic && d->K % 128 == 0 && (long long)nboxes * (d->K / 128) * ((d->N + 7) / 8) >= 256) bp.fbr = 8;
     bp.fbr = env_int("ABED_BOX_FBR", bp.fbr);
     if (bp.fbr != 4 && bp.fbr != 8) return ABED_EUNSUPPORTED;
+    bp.eh = env_int("ABED_BOX_EH", 2);
+    if (bp.eh != 1 && bp.eh != 2) return ABED_EUNSUPPORTED;
+    const int eb = 4 * bp.eh;                                  // entries per batch
     if (d->K % (16 * bp.fbr) != 0) return ABED_EUNSUPPORTED;
     bp.fb = bp.fbr + (want_fc ? 1 : 0);
     bp.grid_n = d->K / (16 * bp.fbr);
-    if (!box_compiled(bp.fb, want_fc, bp.xch)) return ABED_EUNSUPPORTED;
+    if (!box_compiled(bp.fb, want_fc, bp.xch, bp.eh)) return ABED_EUNSUPPORTED;
     // Entry ranges: a range is a whole number of batches of 8 (at most 256 entries: the checksum's 16-bit
     // fields and two digits).  Longer ranges make the digit batch cheaper (it costs about half a batch),
     // shorter ones fill the chip; pick the best product of the two.
     const long long base = (long long)nboxes * bp.grid_n;
-    int best_len = 8; double best = -1.0;
-    for (int len = 8; len <= 256; len += 8) {
+    int best_len = eb; double best = -1.0;
+    const double slots = 256.0 * (3 - bp.eh);                  // workgroups the chip holds at once
+    for (int len = eb; len <= 256; len += eb) {
         const int nr = (d->N + len - 1) / len;
         const long long tiles = base * nr;
-        const double fill = (double)tiles / (256.0 * (double)((tiles + 255) / 256));
-        const double nb = len / 8.0;
+        const double fill = (double)tiles / (slots * (double)((tiles + (long long)slots - 1) / (long long)slots));
+        const double nb = len / (double)eb;
         const double score = fill * (want_ic ? nb / (nb + 0.5) : 1.0) * (1.0 - 0.02 / nb);
         if (score > best + 1e-9) { best = score; best_len = len; }
         if (len >= d->N) break;
     }
     bp.range_len = env_int("ABED_BOX_RANGE", best_len);
-    if (bp.range_len < 8 || bp.range_len > 256 || bp.range_len % 8 != 0) return ABED_EUNSUPPORTED;
+    if (bp.range_len < eb || bp.range_len > 256 || bp.range_len % eb != 0) return ABED_EUNSUPPORTED;
     bp.nranges = (d->N + bp.range_len - 1) / bp.range_len;
     return ABED_OK;
 }
@@ -358,9 +363,10 @@ abed_status_t launch_box_conv(const abed_conv_desc_t *d, const BoxPlan &bp, cons
         const int tile_n = 16 * bp.fbr, rel = n % bp.range_len;
         p.inj_on = 1;
         p.inj_box = (oy / 8) * bp.boxes_x + ox / 8; p.inj_range = n / bp.range_len; p.inj_kt = (int)(k / tile_n);
-        p.inj_batch = rel / 8;
-        const int pgrp = ((oy % 8) / 4) * 2 + (ox % 8) / 4, eh = (rel % 8) / 4;
-        p.inj_wave = pgrp * 2 + eh; p.inj_i = rel % 4;
+        const int eb = 4 * bp.eh;
+        p.inj_batch = rel / eb;
+        const int pgrp = ((oy % 8) / 4) * 2 + (ox % 8) / 4, eh = (rel % eb) / 4;
+        p.inj_wave = pgrp * bp.eh + eh; p.inj_i = rel % 4;
         p.inj_fb = (int)((k % tile_n) / 16);
         p.inj_lane = (int)((k % 16) / 4) * 16 + (oy % 4) * 4 + ox % 4; p.inj_v = (int)(k % 4);
         p.inj_mask = 1u << inject->bit;
@@ -370,7 +376,7 @@ abed_status_t launch_box_conv(const abed_conv_desc_t *d, const BoxPlan &bp, cons
     { const char *v = getenv("ABED_DBG_PTR"); p.dbg_ts = (v && *v) ? (long long *)strtoull(v, nullptr, 0) : nullptr; }
 #endif
     const int tiles = bp.boxes_x * bp.boxes_y * bp.nranges * bp.grid_n;
-    if (!launch_box(bp.fb, bp.fc, bp.xch, p, (tiles + 7) / 8 * 8, st)) return ABED_EUNSUPPORTED;
+    if (!launch_box(bp.fb, bp.fc, bp.xch, bp.eh, p, (tiles + 7) / 8 * 8, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("box_conv_kernel");
     return ABED_OK;
 }

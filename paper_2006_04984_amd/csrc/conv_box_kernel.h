@@ -3,7 +3,8 @@
 // except the offline filter checksums, no workgroup waits for another, and there is no separate input
 // checksum kernel.
 //
-// Work split.  A workgroup (512 threads, 8 waves, one per CU) owns
+// Work split.  A workgroup (512 threads, 8 waves, one per CU; template parameter EH = 1: 256 threads, 4 waves, two
+// per CU, batches of 4) owns
 //   - a box of 8x8 output pixels of the image plane (4 groups of 4x4 pixels),
 //   - a range of batch entries, walked in batches of 8,
 //   - a tile of 16*FBR filters, plus (FC) one block of 16 filters whose rows 0,1 are the two int8 digit
@@ -58,10 +59,7 @@ struct BoxParams {
 constexpr int kBox = 8;                       // output pixels per box side
 constexpr int kHalo = kBox + 2;               // input pixels per side that a 3x3 window over the box touches
 constexpr int kSlots = kHalo * kHalo;         // 100 input pixels per entry and chunk
-constexpr int kEB = 8;                        // entries per batch
 constexpr int kAEntry = kSlots * 64;          // bytes of one entry's staged chunk
-constexpr int kAStage = kEB * kAEntry;        // 51200
-constexpr int kAInstr = kAStage / 1024;       // 50 one-KB loads per stage
 
 // s_waitcnt vmcnt(n) for a wave-uniform run-time n (the instruction takes an immediate): the largest
 // compiled limit that does not exceed n, found by a short tree of scalar branches.  Waiting for a smaller
@@ -103,20 +101,30 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 // FB: filter blocks per tile incl. the digit block; FC: the last block is the digit block; XCH: 0 = no
 // batch checksum, else the number of 64-channel chunks (== p.nch), one set of sum registers per chunk;
-// NBR: sub-stages of the filter ring in LDS (2 or 3).
-template <int FB, bool FC, int XCH, int NBR>
-__global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
+// NBR: sub-stages of the filter ring in LDS (2 or 3); EH: entry halves = groups of four waves.  EH = 2: 8 waves,
+// batches of 8 entries, one workgroup per CU.  EH = 1: 4 waves, batches of 4 entries, at most 80 KB of LDS and 256
+// registers, so that two workgroups share a CU and one's loads, barriers and stores overlap the other's matrix work.
+template <int FB, bool FC, int XCH, int NBR, int EH = 2>
+__global__ __launch_bounds__(256 * EH, 2 / EH) void box_conv_kernel(const BoxParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int FBR = FB - (FC ? 1 : 0);
     constexpr bool IC = XCH > 0;
-    constexpr int B_SUB = FB * 16 * 192;          // one filter row of taps: [16 FB filters][3 taps][64 B]
-    constexpr int B_INSTR = B_SUB / 1024;         // 3 * FB
-    constexpr int LB = (B_INSTR + 7) / 8;
-    constexpr int LA = (kAInstr + 7) / 8;
-    constexpr int A_OFF = 0, B_OFF = 2 * kAStage, MISC_OFF = B_OFF + NBR * B_SUB;
+    constexpr int NW = 4 * EH;                    // waves
+    constexpr int kEB = 4 * EH;                   // entries per batch
+    constexpr int kAStage = kEB * kAEntry;        // 51200 / 25600
+    constexpr int kAInstr = kAStage / 1024;       // one-KB loads per stage
+    // one filter row of taps: [16 FB filters][3 taps][64 B].  With EH = 1 the digit block keeps 1 KB (its rows 0, 1
+    // are the digit filters, rows 2..4 zeros); the fragment reads of its rows 5..15 run into what follows and give
+    // values nobody uses (only the lanes of filters 0..3 of the digit block are ever looked at)
+    constexpr bool SHORT_DIGIT = FC && EH == 1;
+    constexpr int B_SUB = SHORT_DIGIT ? FBR * 16 * 192 + 1024 : FB * 16 * 192;
+    constexpr int B_INSTR = B_SUB / 1024;
+    constexpr int LB = (B_INSTR + NW - 1) / NW;
+    constexpr int LA = (kAInstr + NW - 1) / NW;
+    constexpr int A_OFF = 0, B_OFF = 2 * kAStage, MISC_OFF = B_OFF + NBR * B_SUB + (SHORT_DIGIT ? 2048 : 0);
     constexpr int LDS_BYTES = MISC_OFF + 256 + 2 * FBR * 16 * 4;
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+    static_assert(LDS_BYTES <= 160 * 1024 / (3 - EH), "LDS");
     __shared__ __attribute__((aligned(1024))) int8_t lds[LDS_BYTES];
 
 #ifdef ABED_ENABLE_DBG
@@ -125,7 +133,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lg = lane >> 4, lj = lane & 15;
-    const int pg = wave >> 1, eh = wave & 1;
+    const int pg = wave / EH, eh = wave % EH;
 
     // ---- block index -> (box, range, filter tile); blocks b, b+8, ... share an XCD and take a contiguous eighth
     const int nboxes = p.boxes_x * p.boxes_y;
@@ -156,7 +164,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     int a_cnt = 0;            // instructions this wave issues per stage (wave-uniform)
 #pragma unroll
     for (int j = 0; j < LA; ++j) {
-        const int instr = j * 8 + wave;
+        const int instr = j * NW + wave;
         a_off[j] = kMasked;
         if (instr < kAInstr) {
             ++a_cnt;
@@ -175,7 +183,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     int b_cnt = 0;
 #pragma unroll
     for (int j = 0; j < LB; ++j) {
-        const int instr = j * 8 + wave;
+        const int instr = j * NW + wave;
         b_off[j] = OOB;
         if (instr < B_INSTR) {
             ++b_cnt;
@@ -197,13 +205,13 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     unsigned msk_b = 0, msk_a0 = 0, msk_a1 = 0;
 #pragma unroll
     for (int j = 0; j < LB; ++j)
-        if (j * 8 + wave < B_INSTR) msk_b |= 1u << (1 + 4 * j);
+        if (j * NW + wave < B_INSTR) msk_b |= 1u << (1 + 4 * j);
 #pragma unroll
     for (int j = 0; j < LA; ++j)
-        if (j * 8 + wave < kAInstr) { if (j < 4) msk_a0 |= 1u << (2 + 2 * j); else msk_a1 |= 1u << (2 + 2 * (j - 4)); }
+        if (j * NW + wave < kAInstr) { if (j < 4) msk_a0 |= 1u << (2 + 2 * j); else msk_a1 |= 1u << (2 + 2 * (j - 4)); }
     static_assert(1 + 4 * (LB - 1) < 3 * FB && 2 + 2 * 3 < 3 * FB && LA <= 8, "load slots");
     // the digit block's rows can only be in this wave's last filter instruction
-    const bool last_chk = FC && (LB - 1) * 8 + wave >= FBR * 3;
+    const bool last_chk = FC && (LB - 1) * NW + wave >= FBR * 3;
     const __amdgpu_buffer_rsrc_t rs_blast = last_chk ? rs_wc : rs_w;
 
     // Vector-memory instructions (loads, LDS DMA, stores) complete in issue order, so "everything issued
@@ -215,7 +223,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     auto issue_b = [&](int slot, int chunk, int r) {
         static_for<0, LB>([&](auto j_tag) {
             constexpr int J = decltype(j_tag)::value;
-            const int instr = J * 8 + wave;
+            const int instr = J * NW + wave;
             if (instr < B_INSTR) {
                 __attribute__((address_space(3))) void *dst = (__attribute__((address_space(3))) void *)(lds + B_OFF + slot * B_SUB + instr * 1024);
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(J == LB - 1 ? rs_blast : rs_w, dst, 16, b_off[J], r * 3 * p.C + chunk * 64, 0, 0);
@@ -225,7 +233,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     auto issue_a = [&](int buf, int batch, int chunk) {
         static_for<0, LA>([&](auto j_tag) {
             constexpr int J = decltype(j_tag)::value;
-            const int instr = J * 8 + wave;
+            const int instr = J * NW + wave;
             if (instr < kAInstr) {
                 __attribute__((address_space(3))) void *dst = (__attribute__((address_space(3))) void *)(lds + A_OFF + buf * kAStage + instr * 1024);
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, dst, 16, a_off[J] + (n0 + batch * kEB) * HWC, chunk * 64, 0, 0);
@@ -244,14 +252,18 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
     const int pix = oy * p.Q + ox;
 
     // ---- batch checksum state: this thread's 16 bytes (piece) of every entry's staged chunk
-    const bool x_on = IC && tid < kSlots * 4;
-    const int x_piece = tid * 16;            // byte offset of the piece inside an entry's stage
+    // (EH = 2: 400 pieces on 512 threads, one each, its eight entries added over sub-steps r = 1, 2;  EH = 1: 256
+    // threads, piece tid in r = 1 and piece 256 + tid, for the first 144 threads, in r = 2, four entries each)
+    constexpr int NP = IC ? 3 - EH : 1;      // pieces per thread
+    const int x_piece = tid * 16;            // byte offset of the (first) piece inside an entry's stage
     constexpr int XR = IC ? XCH : 1;
-    unsigned xs_lo[XR][4], xs_hi[XR][4];
+    unsigned xs_lo[XR][NP][4], xs_hi[XR][NP][4];
 #pragma unroll
     for (int c = 0; c < XR; ++c)
 #pragma unroll
-        for (int d = 0; d < 4; ++d) xs_lo[c][d] = xs_hi[c][d] = 0u;
+        for (int q = 0; q < NP; ++q)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) xs_lo[c][q][d] = xs_hi[c][q][d] = 0u;
 
     unsigned xt_lo[4] = {0u, 0u, 0u, 0u}, xt_hi[4] = {0u, 0u, 0u, 0u};
     i32x4 x_next = {0, 0, 0, 0};
@@ -392,7 +404,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
         int bsl = bslot + NBR - 1; if (bsl >= NBR) bsl -= NBR;
         const int8_t *b_dst = lds + B_OFF + bsl * B_SUB + wave * 1024;
         const int b_soff = pf_r * 3 * p.C + pf_chunk * 64;
-        const int8_t *a_dst = lds + A_OFF + (abuf ^ 1) * kAStage + wave * 1024 + (r == 1 ? 4 * 8192 : 0);
+        const int8_t *a_dst = lds + A_OFF + (abuf ^ 1) * kAStage + wave * 1024 + (r == 1 ? 4 * NW * 1024 : 0);
         const int a_soff = ((chunk + 1 == p.nch) ? 0 : chunk + 1) * 64;
         int a_voff[4];
         if (more_a) {
@@ -405,11 +417,11 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
             if constexpr (K % 4 == 1 && (K - 1) / 4 < LB) {
                 constexpr int J = (K - 1) / 4;
                 if (m & (1u << K))
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(J == LB - 1 ? rs_blast : rs_w, (__attribute__((address_space(3))) void *)(b_dst + J * 8192), 16, b_off[J], b_soff, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(J == LB - 1 ? rs_blast : rs_w, (__attribute__((address_space(3))) void *)(b_dst + J * NW * 1024), 16, b_off[J], b_soff, 0, 0);
             } else if constexpr (K % 2 == 0 && K >= 2 && K <= 8) {
                 constexpr int J = (K - 2) / 2;
                 if (m & (1u << K))
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (__attribute__((address_space(3))) void *)(a_dst + J * 8192), 16, a_voff[J], a_soff, 0, 0);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_x, (__attribute__((address_space(3))) void *)(a_dst + J * NW * 1024), 16, a_voff[J], a_soff, 0, 0);
             }
         };
         ABED_TS();
@@ -417,7 +429,10 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
         // load slots that sub-steps r == 1 and r == 2 leave free (one entry per slot, requested one slot ahead), so
         // the additions hide behind the matrix instructions.  xt_*: the step's sums, folded into the chunk's
         // registers at the end of r == 2.
-        const int8_t *x_src = lds + A_OFF + abuf * kAStage + x_piece;
+        // the piece this sub-step adds, and whether this thread has it
+        const int x_pc = EH == 1 ? r - 1 : 0;
+        const bool x_on = IC && (EH == 1 ? (r >= 1 && tid + 256 * x_pc < kSlots * 4) : tid < kSlots * 4);
+        const int8_t *x_src = lds + A_OFF + abuf * kAStage + x_piece + (EH == 1 ? x_pc * 4096 : 0);
         auto x_add = [&](const i32x4 v) {
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
@@ -430,11 +445,12 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
             constexpr int K = decltype(k_tag)::value;
             mid(k_tag);
             if constexpr (IC && !digit) {
-                // slots 0, 3, 7, 10 of r == 1 take entries 0..3, the same slots of r == 2 entries 4..7
+                // slots 0, 3, 7, 10 of r == 1 take entries 0..3, the same slots of r == 2 entries 4..7 (EH = 1: the
+                // four entries of the second piece)
                 constexpr int Q = K == 0 ? 0 : K == 3 ? 1 : K == 7 ? 2 : K == 10 ? 3 : -1;
                 if constexpr (Q >= 0) {
                     if (r >= 1 && x_on) {
-                        const int e = (r - 1) * 4 + Q;
+                        const int e = EH == 1 ? Q : (r - 1) * 4 + Q;
                         x_add(x_next);                          // entry e, requested one slot earlier
                         if (e + 1 < kEB) x_next = *reinterpret_cast<const i32x4 *>(x_src + (e + 1) * kAEntry);
                     }
@@ -442,7 +458,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
             }
         };
         if constexpr (IC && !digit) {
-            if (r == 1 && x_on) {
+            if ((r == 1 || (EH == 1 && r == 2)) && x_on) {
 #pragma unroll
                 for (int d = 0; d < 4; ++d) xt_lo[d] = xt_hi[d] = 0u;
                 x_next = *reinterpret_cast<const i32x4 *>(x_src);
@@ -454,7 +470,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
 #ifdef ABED_ENABLE_DBG
         if (!(p.dbg & 2)) {
 #endif
-        if constexpr (digit) mfma_row(std::integral_constant<int, 1>{}, abuf, bslot, r, eh, mid_all);
+        if constexpr (digit) mfma_row(std::integral_constant<int, 3 - EH>{}, abuf, bslot, r, EH == 1 ? 0 : eh, mid_all);
         else mfma_row(std::integral_constant<int, 4>{}, abuf, bslot, r, eh * 4, mid_all);
 #ifdef ABED_ENABLE_DBG
         }
@@ -466,43 +482,52 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
         ++usub;
 
         if constexpr (IC) {
-            if (r == 2 && x_on) {
-                if constexpr (!digit) {
+            if constexpr (!digit) {
+                // fold the sub-step's sums into the chunk's registers (EH = 2: after r == 2; EH = 1: a piece per sub-step)
+                if ((r == 2 || (EH == 1 && r == 1)) && x_on) {
                     static_for<0, XR>([&](auto c_tag) {
                         constexpr int CT = decltype(c_tag)::value;
-                        if (chunk == CT) {
+                        static_for<0, NP>([&](auto q_tag) {
+                            constexpr int QT = decltype(q_tag)::value;
+                            if (chunk == CT && x_pc == QT) {
 #pragma unroll
-                            for (int d = 0; d < 4; ++d) { xs_lo[CT][d] += xt_lo[d]; xs_hi[CT][d] += xt_hi[d]; }
-                        }
+                                for (int d = 0; d < 4; ++d) { xs_lo[CT][QT][d] += xt_lo[d]; xs_hi[CT][QT][d] += xt_hi[d]; }
+                            }
+                        });
                     });
                 }
-                // the next step is a digit step: its chunk's sums are complete; split them into two int8 digit
-                // images (Sec. 4.1) and put them into the free A buffer as entries 0 and 1
-                if (stepi + 1 >= nsteps_real && stepi + 1 < nsteps) {
-                    const int cn = (chunk + 1 == p.nch) ? 0 : chunk + 1;     // chunk of step stepi + 1
-                    unsigned lo[4], hi[4];
-                    static_for<0, XR>([&](auto c_tag) {
-                        constexpr int CT = decltype(c_tag)::value;
-                        if (cn == CT) {
+            }
+            // the next step is a digit step: its chunk's sums are complete; split them into two int8 digit
+            // images (Sec. 4.1) and put them into the free A buffer as entries 0 and 1
+            if (r == 2 && stepi + 1 >= nsteps_real && stepi + 1 < nsteps) {
+                const int cn = (chunk + 1 == p.nch) ? 0 : chunk + 1;     // chunk of step stepi + 1
+                static_for<0, NP>([&](auto q_tag) {
+                    constexpr int QT = decltype(q_tag)::value;
+                    if (tid + 256 * QT < kSlots * 4) {
+                        unsigned lo[4], hi[4];
+                        static_for<0, XR>([&](auto c_tag) {
+                            constexpr int CT = decltype(c_tag)::value;
+                            if (cn == CT) {
 #pragma unroll
-                            for (int d = 0; d < 4; ++d) { lo[d] = xs_lo[CT][d]; hi[d] = xs_hi[CT][d]; }
+                                for (int d = 0; d < 4; ++d) { lo[d] = xs_lo[CT][QT][d]; hi[d] = xs_hi[CT][QT][d]; }
+                            }
+                        });
+                        const int bias = 128 * nbatch * kEB;     // every staged entry added 128 per byte (zero-filled ones too)
+                        i32x4 d0, d1;
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            int s0 = (int)(lo[d] & 0xffffu) - bias, s1 = (int)(hi[d] & 0xffffu) - bias;
+                            int s2 = (int)(lo[d] >> 16) - bias, s3 = (int)(hi[d] >> 16) - bias;
+                            const unsigned dl = ((unsigned)next_digit(s0) & 0xffu) | (((unsigned)next_digit(s1) & 0xffu) << 8) |
+                                                (((unsigned)next_digit(s2) & 0xffu) << 16) | (((unsigned)next_digit(s3) & 0xffu) << 24);
+                            const unsigned dh = ((unsigned)s0 & 0xffu) | (((unsigned)s1 & 0xffu) << 8) | (((unsigned)s2 & 0xffu) << 16) | (((unsigned)s3 & 0xffu) << 24);
+                            d0[d] = (int)dl; d1[d] = (int)dh;
                         }
-                    });
-                    const int bias = 128 * nbatch * kEB;     // every staged entry added 128 per byte (zero-filled ones too)
-                    i32x4 d0, d1;
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        int s0 = (int)(lo[d] & 0xffffu) - bias, s1 = (int)(hi[d] & 0xffffu) - bias;
-                        int s2 = (int)(lo[d] >> 16) - bias, s3 = (int)(hi[d] >> 16) - bias;
-                        const unsigned dl = ((unsigned)next_digit(s0) & 0xffu) | (((unsigned)next_digit(s1) & 0xffu) << 8) |
-                                            (((unsigned)next_digit(s2) & 0xffu) << 16) | (((unsigned)next_digit(s3) & 0xffu) << 24);
-                        const unsigned dh = ((unsigned)s0 & 0xffu) | (((unsigned)s1 & 0xffu) << 8) | (((unsigned)s2 & 0xffu) << 16) | (((unsigned)s3 & 0xffu) << 24);
-                        d0[d] = (int)dl; d1[d] = (int)dh;
+                        int8_t *dst = lds + A_OFF + (abuf ^ 1) * kAStage + x_piece + QT * 4096;
+                        *reinterpret_cast<i32x4 *>(dst) = d0;
+                        *reinterpret_cast<i32x4 *>(dst + kAEntry) = d1;
                     }
-                    int8_t *dst = lds + A_OFF + (abuf ^ 1) * kAStage + x_piece;
-                    *reinterpret_cast<i32x4 *>(dst) = d0;
-                    *reinterpret_cast<i32x4 *>(dst + kAEntry) = d1;
-                }
+                });
             }
         }
         // (5) end of a step / of a batch
@@ -575,29 +600,45 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
 
     // ---- final comparisons
     if constexpr (IC) {
-        // digit batch results sit in acc[0], acc[1] of the even waves; corner: the digit images' rows under FC
         int *red = reinterpret_cast<int *>(lds);              // [4 pixel groups][FB][64 lanes][4]: the odd waves' sums
         ABED_WAIT_VMCNT(0);
         __syncthreads();                                      // all fragment reads are done; LDS is free
-        // the digit batch left, in acc[0], the fmaps of digit image 0 (even waves) / digit image 1 (odd waves)
-        if (FC) {
-            if (fc_residual(0) != 0) my_flag |= 4u;           // corner: a digit image's row under FC
-        }
-        if (eh == 1) {
-#pragma unroll
-            for (int fb = 0; fb < FB; ++fb) {
-                i32x4 c = icsum[fb];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) c[v] -= (int)((unsigned)acc[0][fb][v] << 8);
-                *reinterpret_cast<i32x4 *>(red + ((pg * FB + fb) * 64 + lane) * 4) = c;
+        // a lane of the digit block counts only if it holds the digit filters' columns (with the short digit block
+        // the other lanes multiplied bytes that are not filters)
+        auto counts = [&](int fb) { return !(SHORT_DIGIT && fb == FB - 1 && lg != 0); };
+        if constexpr (EH == 2) {
+            // the digit batch left, in acc[0], the fmaps of digit image 0 (even waves) / digit image 1 (odd waves)
+            if (FC) {
+                if (fc_residual(0) != 0) my_flag |= 4u;           // corner: a digit image's row under FC
             }
-        }
-        __syncthreads();
-        if (eh == 0) {
+            if (eh == 1) {
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb) {
+                    i32x4 c = icsum[fb];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) c[v] -= (int)((unsigned)acc[0][fb][v] << 8);
+                    *reinterpret_cast<i32x4 *>(red + ((pg * FB + fb) * 64 + lane) * 4) = c;
+                }
+            }
+            __syncthreads();
+            if (eh == 0) {
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb) {
+                    const i32x4 c = icsum[fb] + *reinterpret_cast<const i32x4 *>(red + ((pg * FB + fb) * 64 + lane) * 4) - acc[0][fb];
+                    if ((c[0] | c[1] | c[2] | c[3]) != 0 && counts(fb)) my_flag |= (FC && fb == FB - 1) ? 4u : 2u;
+                }
+            }
+        } else {
+            // one wave per pixel group: the digit batch left the fmaps of digit image 0 in acc[0], of digit image 1 in acc[1]
+            if (FC) {
+                if (fc_residual(0) != 0 || fc_residual(1) != 0) my_flag |= 4u;
+            }
 #pragma unroll
             for (int fb = 0; fb < FB; ++fb) {
-                const i32x4 c = icsum[fb] + *reinterpret_cast<const i32x4 *>(red + ((pg * FB + fb) * 64 + lane) * 4) - acc[0][fb];
-                if ((c[0] | c[1] | c[2] | c[3]) != 0) my_flag |= (FC && fb == FB - 1) ? 4u : 2u;
+                i32x4 c = icsum[fb] - acc[0][fb];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) c[v] -= (int)((unsigned)acc[1][fb][v] << 8);
+                if ((c[0] | c[1] | c[2] | c[3]) != 0 && counts(fb)) my_flag |= (FC && fb == FB - 1) ? 4u : 2u;
             }
         }
     }
@@ -609,7 +650,7 @@ __global__ __launch_bounds__(512) void box_conv_kernel(const BoxParams p)
         if (tid == 0) {
             uint32_t f = 0;
 #pragma unroll
-            for (int w8 = 0; w8 < 8; ++w8) f |= (uint32_t)misc[w8];
+            for (int w8 = 0; w8 < NW; ++w8) f |= (uint32_t)misc[w8];
             p.flags[(box * p.nranges + range) * p.grid_n + kt] = f;
         }
     }

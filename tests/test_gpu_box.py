@@ -82,12 +82,20 @@ def expected_local_flags(oracle, x, w, s, lay, acc_flip=None, wchk=None):
 
 
 @pytest.mark.parametrize("variant", [V_BOTH, V_FC, V_IC], ids=["fc_ic", "fc", "ic"])
-@pytest.mark.parametrize("rng_len", [0, 8], ids=["autorange", "range8"])
+@pytest.mark.parametrize("rng_len,eh", [(0, 2), (8, 2), (0, 1), (4, 1)], ids=["autorange", "range8", "halfwg_autorange", "halfwg_range4"])
 @pytest.mark.parametrize("s", SHAPES, ids=lambda s: s.name)
-def test_box_clean_and_flips(oracle, monkeypatch, s, rng_len, variant):
-    print("case", s.name, rng_len, hex(variant), flush=True)
+def test_box_clean_and_flips(oracle, monkeypatch, s, rng_len, eh, variant):
+    """eh = 1: workgroups of four waves and batches of four entries, two workgroups per CU."""
+    print("case", s.name, rng_len, eh, hex(variant), flush=True)
     if rng_len:
         monkeypatch.setenv("ABED_BOX_RANGE", str(rng_len))
+    monkeypatch.setenv("ABED_BOX_EH", str(eh))
+    if eh == 1 and variant != V_FC and s.C > 128:
+        # the batch checksum of the half-size workgroups keeps at most two chunks of sums in registers
+        with pytest.raises(abed.AbedError) as e:
+            abed.get_layout(abed.desc_from_shape(s), 0, variant)
+        assert e.value.status == 2
+        return
     x, w = int8_tensors(s, 7100 + s.N)
     g = BoxConv(s, variant)
     g.prepare(w)
@@ -129,14 +137,16 @@ def test_box_filter_flip_is_caught_by_fc(oracle):
 def test_box_unchecked_matches_oracle(oracle, monkeypatch):
     """The unchecked convolution routed to the box kernel (both filter tile widths)."""
     monkeypatch.setenv("ABED_BOX", "1")
-    for s, fbr in ((SHAPES[1], 4), (SHAPES[2], 4), (SHAPES[2], 8), (SHAPES[4], 4)):
+    for s, fbr, eh in ((SHAPES[1], 4, 2), (SHAPES[2], 4, 2), (SHAPES[2], 8, 2), (SHAPES[4], 4, 2),
+                       (SHAPES[1], 4, 1), (SHAPES[2], 4, 1), (SHAPES[4], 4, 1)):
         monkeypatch.setenv("ABED_BOX_FBR", str(fbr))
+        monkeypatch.setenv("ABED_BOX_EH", str(eh))
         x, w = int8_tensors(s, 7400)
         desc = abed.desc_from_shape(s)
         y = torch.full((s.N, s.P, s.Q, s.K), -9, dtype=torch.int32, device=DEV)
         abed.conv_int8(desc, torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV), None, None, False, y, 0)
         torch.cuda.synchronize()
-        assert np.array_equal(y.cpu().numpy(), oracle.conv_int(x, w, s).astype(np.int32)), (s.name, fbr)
+        assert np.array_equal(y.cpu().numpy(), oracle.conv_int(x, w, s).astype(np.int32)), (s.name, fbr, eh)
 
 
 def test_box_epilog_int8(oracle):
