@@ -206,6 +206,38 @@ abed_status_t abed_input_checksum_int8(const abed_conv_desc_t *desc, const int8_
 abed_status_t abed_input_checksum_fp16(const abed_conv_desc_t *desc, const void *x, void *xchk,
                                        void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * The traditional ABFT technique at the GEMM level: the comparison system of Sec. 5.3 (results: Sec. 6.3), with
+ * the row + column checksums that Sec. 2.1 recalls.  C[M][Ng] = A[M][Kg] . B[Ng][Kg]^T, int8 operands, int32
+ * result (a convolution lowered to a GEMM has M = N*P*Q, Kg = C*R*S, Ng = K).  The call performs the paper's tasks
+ * (2)-(6): copy A and B into larger buffers in the workspace, generate the column checksum of A and the checksum
+ * over the rows of B as int8 digit rows (Sec. 4.1), run the larger GEMM (the library's unchecked 1x1 convolution),
+ * verify the larger output by reading it once along its rows and once along its columns, copy the result to C.
+ * `tasks` selects which of them run (0 = all; for timing them one by one, as the paper's breakdown does).
+ * flags (8 words, device): [0] bit 0 a row sum disagrees, bit 1 a column sum, bit 2 the corner; [1], [2] numbers of
+ * bad rows and columns; [3], [4] the largest bad row and column index (one bad row and one bad column locate a
+ * single wrong element, the correction capability of the classical scheme).  inject: site 2 only, index =
+ * row * ld_c + column of the larger output, flipped between tasks 4 and 5.  Kg must be a multiple of 16.
+ * ------------------------------------------------------------------------------------------ */
+#define ABED_ABFT_TASK_COPY_IN 1
+#define ABED_ABFT_TASK_CHECKSUMS 2
+#define ABED_ABFT_TASK_GEMM 4
+#define ABED_ABFT_TASK_VERIFY 8
+#define ABED_ABFT_TASK_COPY_OUT 16
+#define ABED_ABFT_ALL_TASKS 31
+typedef struct {
+    int32_t d_a, d_b;            /* digit rows of A's column checksum, of the checksum over B's rows */
+    int32_t ld_c, reserved_;     /* columns of the larger output (Ng + d_b rounded up to a multiple of 4) */
+    int64_t rows_padded;         /* rows of the larger A and of the larger output (M + d_a rounded up to a multiple of 256) */
+    uint64_t workspace_bytes;    /* the larger A, B and output, and the sums */
+    uint64_t c_offset;           /* byte offset of the larger output inside the workspace (for tests) */
+} abed_abft_layout_t;
+/* Host only. */
+abed_status_t abed_abft_gemm_get_layout(int64_t M, int32_t Ng, int32_t Kg, abed_abft_layout_t *out);
+abed_status_t abed_abft_gemm_int8(int64_t M, int32_t Ng, int32_t Kg, const int8_t *A, const int8_t *B, int32_t *C,
+                                  uint32_t *flags, void *workspace, size_t workspace_bytes, int32_t tasks,
+                                  const abed_inject_t *inject, void *stream);
+
 /* Channel padding for layers whose channel count the kernels do not take (C must be a multiple of 16 for int8,
  * 8 for fp16; the 3-channel first layer of a network, which the paper's own evaluation leaves out, Sec. 5.2):
  * dst[row][0..c_pad) = src[row][0..c) followed by zeros, for `rows` rows of elements of elem_bytes (1 or 2) bytes.

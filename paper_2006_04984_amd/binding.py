@@ -73,7 +73,7 @@ class Ic2Layout(ctypes.Structure):
 EXPORTS = ["abed_fic_inloop_get_layout", "abed_fic_inloop_filter_prepare_int8", "abed_fic_inloop_conv_int8", "abed_fic_verify", "abed_ic2_get_layout", "abed_ic2_conv_int8", "abed_fic_get_layout", "abed_fic_filter_prepare_int8", "abed_fic_input_checksum_int8", "abed_fic_conv_int8",
            "abed_get_layout", "abed_filter_prepare_int8", "abed_filter_prepare_local_int8", "abed_filter_prepare_fp16",
            "abed_input_checksum_int8", "abed_input_checksum_fp16", "abed_workspace_init",
-           "abed_conv_int8", "abed_conv_int8_static", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error", "abed_probe", "abed_pad_channels"]
+           "abed_conv_int8", "abed_conv_int8_static", "abed_conv_fp16", "abed_status_string", "abed_last_hip_error", "abed_probe", "abed_pad_channels", "abed_abft_gemm_get_layout", "abed_abft_gemm_int8"]
 
 
 def lib_path():
@@ -175,6 +175,29 @@ def input_checksum_int8(desc, x, xchk, stream=None):
 def workspace_init(workspace, stream=None):
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().abed_workspace_init(_p(workspace), nbytes, _stream(stream)))
+
+
+class AbftLayout(ctypes.Structure):
+    _fields_ = [("d_a", ctypes.c_int32), ("d_b", ctypes.c_int32), ("ld_c", ctypes.c_int32), ("reserved_", ctypes.c_int32),
+                ("rows_padded", ctypes.c_int64), ("workspace_bytes", ctypes.c_uint64), ("c_offset", ctypes.c_uint64)]
+
+
+ABFT_TASKS = {"copy_in": 1, "checksums": 2, "gemm": 4, "verify": 8, "copy_out": 16}
+
+
+def abft_gemm_get_layout(M, Ng, Kg):
+    out = AbftLayout()
+    _check(lib().abed_abft_gemm_get_layout(ctypes.c_int64(M), int(Ng), int(Kg), ctypes.byref(out)))
+    return out
+
+
+def abft_gemm_int8(M, Ng, Kg, A, B, C, flags, workspace, tasks=0, inject=None, stream=None):
+    """abed_abft_gemm_int8: the traditional ABFT-GEMM baseline.  inject = (2, index in the larger output, bit) or None."""
+    inj = None
+    if inject is not None:
+        inj = ctypes.byref(_Inject(int(inject[0]), int(inject[1]), int(inject[2])))
+    _check(lib().abed_abft_gemm_int8(ctypes.c_int64(M), int(Ng), int(Kg), _p(A), _p(B), _p(C), _p(flags), _p(workspace),
+                                     ctypes.c_size_t(workspace.numel() * workspace.element_size()), int(tasks), inj, _stream(stream)))
 
 
 def pad_channels(src, dst, c, c_pad, stream=None):

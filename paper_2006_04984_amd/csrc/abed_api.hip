@@ -11,6 +11,7 @@
 #include "aux_kernels.h"
 #include "fic_kernels.h"
 #include "ic2_kernels.h"
+#include "abft_gemm_kernels.h"
 #include "conv_launch.h"
 #include "conv_box_launch.h"
 
@@ -1201,6 +1202,127 @@ abed_status_t abed_conv_int8_static(const abed_conv_desc_t *desc, const int8_t *
     LAUNCH_CHECK("fill_u32_kernel (static scratch)");
     return abed_conv_int8(desc, x, w, wchk, xchk, compute_xchk, y, epi, variant, flags, xchk_next,
                           ptr, (size_t)ABED_STATIC_SCRATCH_BYTES, inject, y2, stream);
+}
+
+// ---- traditional ABFT at the GEMM level (Sec. 5.3): the comparison system
+namespace {
+constexpr int kAbftParts = 2048;      // blocks of the row pass (each leaves one partial sum)
+struct AbftPlan {
+    long long M, m_pad;          // data rows; rows of the larger A' and C' (a multiple of 256: the GEMM runs as a 1x1 convolution over 16x16 planes)
+    int Ng, Kg, d_a, d_b, ld;    // ld: columns of C' and rows of B' = Ng + d_b rounded up to a multiple of 4 (16-byte rows)
+    long long off_a, off_b, off_c, off_sums, bytes;
+};
+abed_status_t make_abft_plan(int64_t M, int32_t Ng, int32_t Kg, AbftPlan &ap)
+{
+    if (M < 1 || Ng < 1 || Kg < 1) return ABED_EINVAL;
+    if (Kg % 16 != 0 || Kg > 65536) return ABED_EUNSUPPORTED;            // 16-byte pieces; exact int32 accumulation (Sec. 4.1)
+    ap.M = M; ap.Ng = Ng; ap.Kg = Kg;
+    ap.d_a = digits_for_count(M); ap.d_b = digits_for_count(Ng);
+    if (ap.d_a > 4 || ap.d_b > 4) return ABED_ERANGE;
+    ap.m_pad = (M + ap.d_a + 255) / 256 * 256;
+    ap.ld = (Ng + ap.d_b + 3) / 4 * 4;
+    if (ap.m_pad * (long long)Kg >= 0x7ffffff0LL || ap.m_pad * (long long)ap.ld >= (1LL << 29) || (long long)ap.ld * Kg >= 0x7ffffff0LL) return ABED_EUNSUPPORTED;
+    long long off = 0;
+    auto take = [&](long long bytes) { long long o = off; off = align256(off + bytes); return o; };
+    ap.off_a = take(ap.m_pad * (long long)Kg);
+    ap.off_b = take((long long)ap.ld * Kg);
+    ap.off_c = take(ap.m_pad * (long long)ap.ld * 4);
+    ap.off_sums = take(((long long)Kg * 2 + ap.ld + kAbftParts + (Ng + 255) / 256 + 8) * 4);   // column sums of A, of B's rows, of C'; partial sums for the corner
+    ap.bytes = off;
+    return ABED_OK;
+}
+}  // namespace
+
+abed_status_t abed_abft_gemm_get_layout(int64_t M, int32_t Ng, int32_t Kg, abed_abft_layout_t *out)
+{
+    if (!out) return ABED_EINVAL;
+    AbftPlan ap;
+    abed_status_t s = make_abft_plan(M, Ng, Kg, ap);
+    if (s != ABED_OK) return s;
+    memset(out, 0, sizeof(*out));
+    out->d_a = ap.d_a; out->d_b = ap.d_b; out->rows_padded = ap.m_pad; out->ld_c = ap.ld;
+    out->workspace_bytes = (uint64_t)ap.bytes; out->c_offset = (uint64_t)ap.off_c;
+    return ABED_OK;
+}
+
+abed_status_t abed_abft_gemm_int8(int64_t M, int32_t Ng, int32_t Kg, const int8_t *A, const int8_t *B, int32_t *C,
+                                  uint32_t *flags, void *workspace, size_t workspace_bytes, int32_t tasks,
+                                  const abed_inject_t *inject, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    AbftPlan ap;
+    abed_status_t s = make_abft_plan(M, Ng, Kg, ap);
+    if (s != ABED_OK) return s;
+    if (!A || !B || !C || !flags) return ABED_EINVAL;
+    if (!workspace || (long long)workspace_bytes < ap.bytes) return ABED_EWORKSPACE;
+    if (tasks == 0) tasks = ABED_ABFT_ALL_TASKS;
+    if (inject && inject->site != 0) {
+        if (inject->site != 2) return ABED_EUNSUPPORTED;                  // a bit of the stored larger output, between tasks 4 and 5
+        if (inject->index < 0 || inject->index >= (M + ap.d_a) * (long long)ap.ld || inject->bit < 0 || inject->bit > 31) return ABED_EINVAL;
+    }
+    char *ws = (char *)workspace;
+    int8_t *Ap = (int8_t *)(ws + ap.off_a), *Bp = (int8_t *)(ws + ap.off_b);
+    int *Cp = (int *)(ws + ap.off_c), *sums = (int *)(ws + ap.off_sums);
+    int *sumA = sums, *sumB = sums + Kg, *sumC = sums + 2 * Kg, *row_part = sumC + ap.ld, *col_part = row_part + kAbftParts;
+    // about 512 blocks per launch: each ends with one global atomic per column, and atomics on one address are served one after the other
+    auto chunk_rows = [](long long rows, int col_blocks) { long long r = (rows * col_blocks + 511) / 512; return (int)(r < 32 ? 32 : r); };
+    const long long a_bytes = M * (long long)Kg, b_bytes = (long long)Ng * Kg;
+    // the larger GEMM as a 1x1 convolution: m_pad / 256 images of 16x16 pixels, Kg channels, Ng + d_b filters
+    abed_conv_desc_t gd;
+    gd.N = (int32_t)(ap.m_pad / 256); gd.H = 16; gd.W = 16; gd.C = Kg; gd.K = ap.ld; gd.R = gd.S = 1;
+    gd.stride_h = gd.stride_w = 1; gd.pad_h = gd.pad_w = 0;
+    {
+        Plan pl;
+        if ((s = make_plan(&gd, ABED_INT8, ABED_NONE, false, pl)) != ABED_OK) return s;
+        if (!tile_compiled(pl.wm, pl.wk, pl.kg)) return ABED_EUNSUPPORTED;
+    }
+    if (tasks & ABED_ABFT_TASK_COPY_IN) {
+        // task 2: the operands into their larger buffers; the rows behind the checksum rows are zeros
+        abft_copy_rows_kernel<<<dim3((unsigned)((a_bytes / 16 + 255) / 256)), dim3(256), 0, st>>>((const unsigned char *)A, (unsigned char *)Ap, 1, a_bytes, a_bytes, a_bytes);
+        abft_copy_rows_kernel<<<dim3((unsigned)((b_bytes / 16 + 255) / 256)), dim3(256), 0, st>>>((const unsigned char *)B, (unsigned char *)Bp, 1, b_bytes, b_bytes, b_bytes);
+        const long long tail = (ap.m_pad - M) * (long long)Kg / 4, tail_b = (ap.ld - Ng) * (long long)Kg / 4;
+        fill_u32_kernel<<<dim3((unsigned)((tail + 255) / 256)), dim3(256), 0, st>>>((uint32_t *)(Ap + a_bytes), tail, 0u);
+        fill_u32_kernel<<<dim3((unsigned)((tail_b + 255) / 256)), dim3(256), 0, st>>>((uint32_t *)(Bp + b_bytes), tail_b, 0u);
+        LAUNCH_CHECK("abft copy in");
+    }
+    if (tasks & ABED_ABFT_TASK_CHECKSUMS) {
+        // task 3: column checksum of A, checksum over the rows of B, as int8 digit rows behind the data
+        const long long nsum = (long long)Kg * 2;
+        fill_u32_kernel<<<dim3((unsigned)((nsum + 255) / 256)), dim3(256), 0, st>>>((uint32_t *)sums, nsum, 0u);
+        const int units = Kg / 16, cb = (units + 255) / 256;
+        const int rpb_a = chunk_rows(M, cb), rpb_b = chunk_rows(Ng, cb);
+        abft_colsum_kernel<1><<<dim3(cb, (unsigned)((M + rpb_a - 1) / rpb_a)), dim3(256), 0, st>>>((const unsigned char *)Ap, M, units, Kg, rpb_a, sumA);
+        abft_colsum_kernel<1><<<dim3(cb, (unsigned)((Ng + rpb_b - 1) / rpb_b)), dim3(256), 0, st>>>((const unsigned char *)Bp, Ng, units, Kg, rpb_b, sumB);
+        abft_digits_kernel<<<dim3((Kg + 255) / 256), dim3(256), 0, st>>>(sumA, Kg, ap.d_a, Ap + a_bytes);
+        abft_digits_kernel<<<dim3((Kg + 255) / 256), dim3(256), 0, st>>>(sumB, Kg, ap.d_b, Bp + b_bytes);
+        LAUNCH_CHECK("abft checksums");
+    }
+    if (tasks & ABED_ABFT_TASK_GEMM) {
+        if ((s = plain_conv(&gd, Ap, Bp, Cp, nullptr, nullptr, st)) != ABED_OK) return s;       // task 4
+    }
+    if (inject && inject->site == 2) flip_bit_u32_kernel<<<1, 1, 0, st>>>((uint32_t *)Cp, inject->index, 1u << inject->bit);
+    if (tasks & ABED_ABFT_TASK_VERIFY) {
+        // task 5: the output read once along its rows and once along its columns
+        fill_u32_kernel<<<1, 64, 0, st>>>(flags, 8, 0u);
+        fill_u32_kernel<<<dim3((unsigned)((ap.ld + 255) / 256)), dim3(256), 0, st>>>((uint32_t *)sumC, ap.ld, 0u);
+        long long row_blocks = (M + 3) / 4; if (row_blocks > kAbftParts) row_blocks = kAbftParts;
+        abft_row_check_kernel<<<dim3((unsigned)row_blocks), dim3(256), 0, st>>>(Cp, M, Ng, ap.d_b, ap.ld, flags, row_part);
+        const int units = ap.ld / 4, cb = (units + 255) / 256, rpb = chunk_rows(M, cb);
+        abft_colsum_kernel<4><<<dim3(cb, (unsigned)((M + rpb - 1) / rpb)), dim3(256), 0, st>>>((const unsigned char *)Cp, M, units, (long long)ap.ld * 4, rpb, sumC);
+        const int col_blocks = (Ng + 255) / 256;
+        abft_col_check_kernel<<<dim3(col_blocks), dim3(256), 0, st>>>(Cp, M, Ng, ap.d_a, ap.ld, sumC, flags, col_part);
+        abft_corner_kernel<<<1, 256, 0, st>>>(Cp, M, Ng, ap.d_a, ap.d_b, ap.ld, row_part, (int)row_blocks, col_part, col_blocks, flags);
+        LAUNCH_CHECK("abft verify");
+    }
+    if (tasks & ABED_ABFT_TASK_COPY_OUT) {
+        // task 6: the result without its checksum rows and columns, in 16-byte pieces where the widths allow
+        if (Ng % 4 == 0)
+            abft_copy_rows_kernel<<<dim3((unsigned)((M * (Ng / 4) + 255) / 256)), dim3(256), 0, st>>>((const unsigned char *)Cp, (unsigned char *)C, M, (long long)ap.ld * 4, (long long)Ng * 4, (long long)Ng * 4);
+        else
+            abft_copy_words_kernel<<<dim3((unsigned)((M * Ng + 255) / 256)), dim3(256), 0, st>>>(Cp, C, M, ap.ld, Ng);
+        LAUNCH_CHECK("abft copy out");
+    }
+    return ABED_OK;
 }
 
 abed_status_t abed_pad_channels(const void *src, void *dst, int64_t rows, int32_t c, int32_t c_pad, int32_t elem_bytes,

@@ -1,6 +1,7 @@
 """Evaluation runs on one GPU, beside bench.py (which covers the headline 3x3 configuration):
 
   python -m paper_2006_04984_amd.evaluate layers   --config 3      per-layer table of a configuration
+  python -m paper_2006_04984_amd.evaluate abft                      the traditional ABFT-GEMM baseline, task by task (Sec. 5.3)
   python -m paper_2006_04984_amd.evaluate fp16                      false-positive / detection rates (fp16 layer)
   python -m paper_2006_04984_amd.evaluate detect                    int8 single-bit detection rates
   python -m paper_2006_04984_amd.evaluate resnet50 --batch 128      the 53 convolution layers back to back
@@ -535,6 +536,66 @@ def cmd_resnet50(args):
     print(json.dumps(result))
 
 
+def cmd_abft(args):
+    """The traditional ABFT technique at the GEMM level (Sec. 5.3 / 6.3): run time of its tasks (copy into the larger
+    operands, checksum generation, the larger GEMM, verification by rows and by columns, copy back) against the plain
+    GEMM, on the GEMM shapes of the configured layers (M = N*P*Q, Kg = C*R*S, Ng = K; the operand of a 3x3 layer's
+    GEMM is a synthetic matrix of the lowered shape), next to the FC + IC and FIC overheads of the same layers."""
+    from synth import CONFIG2, CONFIG3
+    stream = torch.cuda.Stream()
+    rows = []
+    for cfg, layers in ((3, CONFIG3), (2, CONFIG2)):
+        for li, s in enumerate(layers):
+            M, Kg, Ng = s.N * s.P * s.Q, s.C * s.R * s.S, s.K
+            g = torch.Generator(device="cpu").manual_seed(900 + 10 * cfg + li)
+            A = torch.randint(-128, 128, (M, Kg), dtype=torch.int8, generator=g).to(DEV)
+            B = torch.randint(-128, 128, (Ng, Kg), dtype=torch.int8, generator=g).to(DEV)
+            lay = abed.abft_gemm_get_layout(M, Ng, Kg)
+            ws = torch.zeros((lay.workspace_bytes,), dtype=torch.uint8, device=DEV)
+            C = torch.empty((M, Ng), dtype=torch.int32, device=DEV)
+            flags = torch.zeros((8,), dtype=torch.int32, device=DEV)
+            run = lambda tasks=0: abed.abft_gemm_int8(M, Ng, Kg, A, B, C, flags, ws, tasks=tasks)
+            run(); torch.cuda.synchronize()
+            assert int(flags[0].item()) == 0
+            # the plain GEMM: the same product without checksums, as a 1x1 convolution over 16x16 planes
+            from synth import ConvShape
+            mp = (M + 255) // 256 * 256
+            Ap = torch.zeros((mp, Kg), dtype=torch.int8, device=DEV); Ap[:M].copy_(A)
+            gd = abed.desc_from_shape(ConvShape(mp // 256, 16, 16, Kg, Ng, 1, 1, 1, 1, 0, 0, "gemm"))
+            Cg = torch.empty((mp, Ng), dtype=torch.int32, device=DEV)
+            t_plain = _graph_time(lambda: abed.conv_int8(gd, Ap, B, None, None, False, Cg, Variant.NONE), stream)
+            assert torch.equal(Cg[:M], C)
+            t = {name: _graph_time(lambda bit=bit: run(bit), stream) for name, bit in abed.ABFT_TASKS.items()}
+            t_all = _graph_time(lambda: run(0), stream)
+            row = dict(config=cfg, layer=s.name, M=M, Kg=Kg, Ng=Ng, gemm_us=t_plain * 1e6, abft_total_us=t_all * 1e6,
+                       abft_overhead_pct=100.0 * (t_all / t_plain - 1.0),
+                       tasks_us={k: v * 1e6 for k, v in t.items()},
+                       larger_gemm_overhead_pct=100.0 * (t["gemm"] / t_plain - 1.0))
+            # the paper's schemes on the same layer, same protocol
+            t_conv = {}
+            for name, variant in (("unchecked", Variant.NONE), ("fc_ic", Variant.FUSED_OCG), ("fc_only", Variant.FUSED_OCG | abed.ONLY_FC)):
+                L = Int8Layer(s, seed_for_layer(cfg, li), variant)
+                t_conv[name] = _graph_time(L.run, stream)
+                del L
+            F = FicLayer(s, seed_for_layer(cfg, li), Variant.FUSED_OCG)
+            t_conv["fic"] = _graph_time(F.run, stream)
+            del F
+            row.update(conv_unchecked_us=t_conv["unchecked"] * 1e6,
+                       fc_ic_overhead_pct=100.0 * (t_conv["fc_ic"] / t_conv["unchecked"] - 1.0),
+                       fc_only_overhead_pct=100.0 * (t_conv["fc_only"] / t_conv["unchecked"] - 1.0),
+                       fic_overhead_pct=100.0 * (t_conv["fic"] / t_conv["unchecked"] - 1.0))
+            rows.append(row)
+            print(json.dumps(row), flush=True)
+            del ws, A, B, C, Ap, Cg
+            torch.cuda.empty_cache()
+    print(json.dumps(dict(abft_gemm=rows)))
+
+
+def seed_for_layer(cfg, li):
+    from synth import seed_for
+    return seed_for(cfg, li)
+
+
 def cmd_ksweep(args):
     """Filter-count sweep on one layer (Sec. 6.2's tile-boundary study): 3x3, C=64, stride 1, pad 1 on a
     112x112 input, K from 8 upwards in steps of 8; unchecked, the filter checksum scheme alone (its extra
@@ -571,6 +632,7 @@ def main():
     sub = ap.add_subparsers(dest="cmd", required=True)
     a = sub.add_parser("layers"); a.add_argument("--config", type=int, default=3, choices=[2, 3]); a.add_argument("--batch", type=int, default=0)
     a = sub.add_parser("detect"); a.add_argument("--trials", type=int, default=1000); a.add_argument("--clean", type=int, default=100); a.add_argument("--seed", type=int, default=1)
+    sub.add_parser("abft")
     a = sub.add_parser("fp16"); a.add_argument("--trials", type=int, default=1000); a.add_argument("--seed", type=int, default=1)
     a = sub.add_parser("resnet50"); a.add_argument("--batch", type=int, default=128)
     a = sub.add_parser("ksweep"); a.add_argument("--batch", type=int, default=16); a.add_argument("--kmax", type=int, default=144)
@@ -579,7 +641,7 @@ def main():
         print("no GPU visible", file=sys.stderr)
         sys.exit(1)
     abed.lib()
-    {"layers": cmd_layers, "detect": cmd_detect, "fp16": cmd_fp16, "resnet50": cmd_resnet50, "ksweep": cmd_ksweep}[args.cmd](args)
+    {"layers": cmd_layers, "detect": cmd_detect, "fp16": cmd_fp16, "resnet50": cmd_resnet50, "ksweep": cmd_ksweep, "abft": cmd_abft}[args.cmd](args)
 
 
 if __name__ == "__main__":

@@ -192,3 +192,16 @@ def test_static_scratch_entry_point_rejects_large_workspace(L):
     st = L.abed_conv_int8_static(ctypes.byref(desc), None, None, None, None, 1, None, None, int(Variant.UNFUSED),
                                  None, None, None, None, None)
     assert st == 3
+
+
+def test_abft_gemm_layout(L):
+    """Host logic of the traditional ABFT-GEMM baseline: digits, padded sizes, limits."""
+    lay = abed.abft_gemm_get_layout(100352, 64, 576)
+    assert (lay.d_a, lay.d_b) == (4, 2) and lay.ld_c == 68 and lay.rows_padded == 100608
+    assert lay.workspace_bytes >= 100608 * 576 + 68 * 576 + 100608 * 68 * 4
+    lay = abed.abft_gemm_get_layout(70, 40, 32)
+    assert (lay.d_a, lay.d_b, lay.ld_c, lay.rows_padded) == (2, 2, 44, 256)
+    for bad, status in (((0, 4, 16), 1), ((4, 4, 24), 2), ((4, 4, 65536 + 16), 2)):
+        with pytest.raises(AbedError) as e:
+            abed.abft_gemm_get_layout(*bad)
+        assert e.value.status == status
