@@ -127,3 +127,42 @@ def test_resnet50_layers_with_epilog(oracle, i):
         assert variant == 0 or not flags.any()
         del g, y
         torch.cuda.empty_cache()
+
+
+def _distinct_resnet_layers():
+    seen, out = set(), []
+    for i, s in enumerate(resnet50_layers(128)):
+        key = (s.H, s.W, s.C, s.K, s.R, s.S, s.stride_h, s.stride_w, s.pad_h, s.pad_w)
+        if key not in seen:
+            seen.add(key)
+            out.append(i)
+    return out
+
+
+@pytest.mark.parametrize("i", _distinct_resnet_layers())
+def test_resnet50_every_distinct_layer_whole_tensor(oracle, i):
+    """Every distinct layer shape of the 53-layer network at its evaluation batch of 128 (the other layers repeat
+    these shapes), FusedOCG with the fused int8 epilog: the WHOLE output tensor against the oracle's convolution and
+    epilog, flags clear.  The 3-channel first layer goes through the library's channel padding."""
+    from gpu_helpers import GpuConv
+    s = resnet50_layers(128)[i]
+    print("case", i, s.name, flush=True)
+    x, w = int8_tensors(s, 5000 + i)
+    scale, bias = requant_params(s, 5000 + i)
+    exp = oracle.epilog_int8(oracle.conv_int(x, w, s).astype(np.int32), scale, bias, True)
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    sg = s
+    if s.C % 16:
+        sg = dataclasses.replace(s, C=16)
+        xp = torch.empty((s.N, s.H, s.W, 16), dtype=torch.int8, device=DEV)
+        wp = torch.empty((s.K, s.R, s.S, 16), dtype=torch.int8, device=DEV)
+        abed.pad_channels(xd, xp, s.C, 16)
+        abed.pad_channels(wd, wp, s.C, 16)
+        xd, wd = xp, wp
+    g = GpuConv(sg, 4, int8_out=True)
+    g.prepare(wd)
+    y, flags = g.run(xd, epilogue=(scale, bias, True))
+    assert np.array_equal(y, exp)
+    assert not flags.any()
+    del g, y
+    torch.cuda.empty_cache()
