@@ -410,7 +410,8 @@ def abed_fp16(x, w, shape, rtol, atol, wchk=None, xchk=None, acc_flip=None, out_
     the reduced elements (rs_abs over the filters for FC, cs_abs over the batch for IC; for the corner
     the same norms of the checksum fmaps).
     Returns y (out_dtype), yf, yi, yfi, rs, cs (float64), fc_bad, ic_bad,
-    corner_bad, and the signed margins  |s-c| - tol  of both checks."""
+    corner_bad, the signed margins  |s-c| - tol  of both checks, and xchk_next (the hi/lo batch checksum of
+    the fp16 outputs, for the next layer)."""
     x = np.asarray(x, dtype=np.float16)
     w = np.asarray(w, dtype=np.float16)
     if wchk is None:
@@ -431,6 +432,10 @@ def abed_fp16(x, w, shape, rtol, atol, wchk=None, xchk=None, acc_flip=None, out_
 
     res = dict(y=y.astype(out_dtype), y_exact=y, yf=yf, yi=yi, yfi=yfi, rs=rs, cs=cs, rs_abs=rs_abs, cs_abs=cs_abs,
                wchk=wchk, xchk=xchk)
+    # the next layer's batch checksum, generated with the output (Sec. 4.3, the option that also generates the next
+    # layer's input checksum): the sum over the batch of the values the next layer will read, i.e. of the outputs
+    # rounded to fp16, stored as a hi/lo pair like every fp16 checksum (Sec. 7)
+    res["xchk_next"] = split_hi_lo(y.astype(np.float16).astype(np.float64).sum(axis=0))
     res["fc_margin"] = threshold_margin(rs, yf, rtol, atol, rs_abs if l1 else None)
     res["ic_margin"] = threshold_margin(cs, yi, rtol, atol, cs_abs if l1 else None)
     res["fc_bad"] = threshold_bad(rs, yf, rtol, atol, rs_abs if l1 else None)

@@ -155,3 +155,27 @@ def test_output_flip_detection(oracle):
     assert r["ic_bad"][2, 3, 4] and r["ic_bad"].sum() == 1
     r = oracle.abed_fp16(x, w, s, 1e-3, 1e-3, acc_flip=(idx, 0))
     assert not r["fc_bad"].any() and not r["ic_bad"].any()
+
+
+def test_next_layer_checksum_chains(oracle):
+    """The batch checksum handed to the next layer (Sec. 4.3) is the checksum that layer would make from its own
+    input: chaining two layers, layer 2's default input checksum equals layer 1's xchk_next bit for bit, and a
+    clean second layer raises no flag with it."""
+    s1 = ConvShape(5, 6, 6, 8, 16, 3, 3, 1, 1, 1, 1, "l1")
+    s2 = ConvShape(5, 6, 6, 16, 8, 1, 1, 1, 1, 0, 0, "l2")
+    x, w1 = fp16_tensors(s1, 31)
+    _, w2 = fp16_tensors(s2, 32)
+    r1 = oracle.abed_fp16(x, w1, s1, 1e-3, 1e-3)
+    nxt = r1["xchk_next"]
+    assert nxt.dtype == np.float16 and nxt.shape == (2, s1.P, s1.Q, s1.K)
+    total = r1["y"].astype(np.float64).sum(axis=0)
+    assert np.all(np.abs(nxt.astype(np.float64).sum(0) - total) <= np.abs(total) * 2.0 ** -21 + 2.0 ** -25)
+    r2_own = oracle.abed_fp16(r1["y"], w2, s2, 1e-3, 1e-3)
+    assert np.array_equal(r2_own["xchk"].view(np.uint16), nxt.view(np.uint16))
+    r2 = oracle.abed_fp16(r1["y"], w2, s2, 1e-3, 1e-3, xchk=nxt)
+    assert not (r2["fc_bad"].any() or r2["ic_bad"].any() or r2["corner_bad"].any())
+    # an output of layer 1 corrupted after its checksum was handed on shows in layer 2's batch check
+    ybad = r1["y"].copy()
+    oracle.flip_bit(ybad, ((2 * s1.P + 3) * s1.Q + 1) * s1.K + 4, 13)
+    r2b = oracle.abed_fp16(ybad, w2, s2, 1e-3, 1e-3, xchk=nxt)
+    assert r2b["ic_bad"][3, 1].any() and not np.delete(r2b["ic_bad"].reshape(36, -1), 3 * 6 + 1, axis=0).any()
