@@ -292,8 +292,9 @@ abed_status_t abed_conv_int8_static(const abed_conv_desc_t *desc, const int8_t *
                                     const abed_inject_t *inject, void *y2, void *stream);
 
 /* Checked fp16 convolution (fp32 accumulation; Sec. 7).  As above with fp16
- * data; y is fp16 (out_fp32 == 0) or fp32.  Variants ABED_NONE ... ABED_FUSED_OCG and ABED_DUPLICATE
- * (ABED_FUSED_IOCG: ABED_EUNSUPPORTED); the variants that verify from memory keep ConvOut and the checksum
+ * data; y is fp16 (out_fp32 == 0) or fp32.  All variants; with ABED_FUSED_IOCG y2 takes the next layer's
+ * checksum images, fp16 [2][P][Q][K]: the hi/lo pair of the batch sum of the outputs rounded to fp16 (with
+ * ABED_DUPLICATE y2 is the second output); the variants that verify from memory keep ConvOut and the checksum
  * fmaps as fp32 in the workspace and round the fp16 output from there.  inject: site 1 only, bit 0..15 of the
  * value rounded to fp16.  A check fails unless
  * |s - c| <= rtol * max(|s|, |c|) + atol, s the reduction of the real

@@ -366,8 +366,9 @@ def split_hi_lo(s):
     """A high-precision checksum stored as two fp16 tensors: hi = fp16(s),
     lo = fp16(s - hi)  ("multiple fp16 values", Sec. 7)."""
     s = np.asarray(s, dtype=np.float64)
-    hi = s.astype(np.float16)
-    lo = (s - hi.astype(np.float64)).astype(np.float16)
+    with np.errstate(invalid="ignore", over="ignore"):       # a non-finite sum stays non-finite in both parts
+        hi = s.astype(np.float16)
+        lo = (s - hi.astype(np.float64)).astype(np.float16)
     return np.stack([hi, lo])
 
 

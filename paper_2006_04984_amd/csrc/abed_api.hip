@@ -186,7 +186,7 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     if (only != 0 && !(variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG)) return ABED_EINVAL;
     if (only == ABED_ONLY_FC && variant == ABED_FUSED_IOCG) return ABED_EINVAL;
     if (packed && (only == ABED_ONLY_IC || dtype != ABED_INT8 || !(variant == ABED_FUSED_OCG || variant == ABED_FUSED_IOCG))) return ABED_EINVAL;
-    if (l1 && (dtype != ABED_FP16 || !(variant >= ABED_UNFUSED && variant <= ABED_FUSED_OCG))) return ABED_EINVAL;
+    if (l1 && (dtype != ABED_FP16 || !(variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG))) return ABED_EINVAL;
     pl.variant = variant;
     pl.l1 = l1 ? 1 : 0;
     pl.packed = 0;
@@ -194,7 +194,6 @@ abed_status_t make_plan(const abed_conv_desc_t *d, int dtype, int variant, bool 
     const bool f16 = dtype == ABED_FP16;
     pl.esize = f16 ? 2 : 1;
     if ((d->C * pl.esize) % 16 != 0) return ABED_EUNSUPPORTED;   // 16-byte chunks of one filter tap
-    if (f16 && variant == ABED_FUSED_IOCG) return ABED_EUNSUPPORTED;   // fp16: no hand-over of the output's batch checksum
     const long long crs = (long long)d->C * d->R * d->S;
     if (crs > 65536) return ABED_EUNSUPPORTED;             // int32 accumulators are exact up to C*R*S = 64K (Sec. 4.1)
     // byte offsets inside a tensor are 32-bit (buffer descriptors); the largest offset marks "out of range"
@@ -1350,9 +1349,10 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
     if (s != ABED_OK) return s;
     variant = pl.variant;
     if (!x || !w || !y) return ABED_EINVAL;
-    const bool checked = variant >= ABED_UNFUSED && variant <= ABED_FUSED_OCG;
+    const bool checked = variant >= ABED_UNFUSED && variant <= ABED_FUSED_IOCG;
     if (checked && ((pl.d_f && !wchk) || (pl.d_i && !xchk) || !flags)) return ABED_EINVAL;
     if (checked && !(rtol >= 0.f && atol >= 0.f)) return ABED_EINVAL;
+    if (variant == ABED_FUSED_IOCG && !y2) return ABED_EINVAL;        // y2 takes the next layer's checksum images
     if (variant == ABED_DUPLICATE && (!y2 || !flags)) return ABED_EINVAL;
     if (checked && (!workspace || (long long)workspace_bytes < pl.ws_bytes)) return ABED_EWORKSPACE;
     if (inject && inject->site != 0) {
@@ -1437,10 +1437,11 @@ abed_status_t abed_conv_fp16(const abed_conv_desc_t *desc, const void *x, const 
         }
         return ABED_OK;
     }
-    cp.mode = variant == ABED_FUSED_PARTIAL_REDUCTION ? MODE_PARTIAL : MODE_CHECK;
+    cp.mode = variant == ABED_FUSED_PARTIAL_REDUCTION ? MODE_PARTIAL : (variant == ABED_FUSED_IOCG ? MODE_CHECK_NEXT : MODE_CHECK);
     cp.cnt_fc = (uint32_t *)wsp(pl.off_cnt_fc);
     cp.cnt_ic = (uint32_t *)wsp(pl.off_cnt_ic);
-    cp.ws_fc = wsp(pl.off_fc); cp.ws_ic = wsp(pl.off_ic);
+    cp.ws_fc = wsp(pl.off_fc); cp.ws_ic = wsp(pl.off_ic); cp.ws_nx = wsp(pl.off_nx);
+    if (variant == ABED_FUSED_IOCG) cp.xchk_next = (int8_t *)y2;
     if (variant == ABED_FUSED_PARTIAL_REDUCTION) {
         fill_u32_kernel<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st>>>(flags, words, 0u);
         LAUNCH_CHECK("fill_u32_kernel");

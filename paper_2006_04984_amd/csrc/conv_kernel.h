@@ -554,7 +554,19 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         uint32_t my_flag = 0;
         // a scheme that is not selected (d_f or d_i zero) has nothing to exchange
         const bool fc_local = p.grid_n == 1 || p.d_f == 0, ic_local = p.grid_b == 1 || p.d_i == 0;
-        const bool checking = p.mode == MODE_CHECK;
+        const bool checking = p.mode == MODE_CHECK || p.mode == MODE_CHECK_NEXT;
+        const bool want_next = p.mode == MODE_CHECK_NEXT && p.xchk_next != nullptr;
+        // the hi/lo pair of a batch sum of fp16 outputs, into the next layer's checksum images [2][PQ][K]
+        auto store_next = [&](const f32x4 s4, int fb) {
+            if (!pvalid || fb >= p.kblk) return;
+            _Float16 *dst = reinterpret_cast<_Float16 *>(p.xchk_next) + (long long)pix * p.K + fb * 16 + lg * 4;
+            for (int v = 0; v < 4; ++v)
+                if (fb * 16 + lg * 4 + v < p.K) {
+                    const _Float16 hi = (_Float16)s4[v];
+                    dst[v] = hi;
+                    dst[(long long)PQ * p.K + v] = (_Float16)(s4[v] - (float)hi);
+                }
+        };
         // The threshold is relative to the larger of the two compared values or, with p.l1, to the sum of
         // magnitudes of what was reduced (Sec. 7 leaves its choice open).  NaN and infinity are mismatches.
         auto bad = [&](float sum, float chk, float mag) {
@@ -652,6 +664,31 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                     st_dev4(dst + 2 * WK * 256, __builtin_bit_cast(i32x4, mag));
                 }
             }
+            }
+            if (want_next) {
+                // (3b) the next layer's batch checksum (Sec. 4.3): the sum over the real images of the outputs as the
+                // next layer will read them (rounded to fp16), in fp32; a second pass through the LDS area of (3)
+                __syncthreads();
+#pragma unroll
+                for (int kb = 0; kb < WK; ++kb) {
+                    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int i = 0; i < WM; ++i)
+                        if (nt * MB + wave * WM + i < p.N)
+                            sum += f32x4{(float)(_Float16)acc[i][kb][0], (float)(_Float16)acc[i][kb][1], (float)(_Float16)acc[i][kb][2], (float)(_Float16)acc[i][kb][3]};
+                    *reinterpret_cast<f32x4 *>(e_ic + ((wave * WK + kb) * 64 + lane) * 4) = sum;
+                }
+                __syncthreads();
+#pragma unroll
+                for (int c4 = 0; c4 < (WK + 3) / 4; ++c4) {
+                    const int kb = 4 * c4 + wave;
+                    if (kb >= WK) continue;
+                    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) sum += *reinterpret_cast<const f32x4 *>(e_ic + ((w * WK + kb) * 64 + lane) * 4);
+                    if (p.grid_b == 1) store_next(sum, kt * WK + kb);
+                    else st_dev4(p.ws_nx + ((((long long)pg * p.grid_n + kt) * p.grid_b + nt) * WK + kb) * 256 + lane * 4, __builtin_bit_cast(i32x4, sum));
+                }
             }
             if (checking) {
                 // (4) flags of this tile; when sums span several tiles, count this tile's arrival (the
@@ -758,6 +795,27 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                     late |= (fb < p.kblk) ? 2u : 4u;
             }
             if (late) __hip_atomic_fetch_or(&p.flags[((long long)pg * p.grid_b) * p.grid_n + kt], late, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (want_next) {
+                // the batch tiles' sums of the fp16 outputs, added in tile order: [grid_b][WK][256] words
+                const __amdgpu_buffer_rsrc_t rs_nx = __builtin_amdgcn_make_buffer_rsrc(
+                    (void *)(p.ws_nx + (((long long)pg * p.grid_n + kt) * p.grid_b) * WK * 256), 0, p.grid_b * WK * 1024, 0x00020000);
+                for (int idx = tid; idx < WK * 64; idx += 256) {
+                    const int kb = idx >> 6, ln = idx & 63;
+                    f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+                    for (int b = 0; b < p.grid_b; ++b) sum += __builtin_bit_cast(f32x4, ld_dev4(rs_nx, ((b * WK + kb) * 256 + ln * 4) * 4));
+                    // (this thread's lane position may differ from ln: recompute the pixel and filter from ln)
+                    const int px = pg * 16 + (ln & 15), fb = kt * WK + kb;
+                    if (px < PQ && fb < p.kblk) {
+                        _Float16 *dst = reinterpret_cast<_Float16 *>(p.xchk_next) + (long long)px * p.K + fb * 16 + (ln >> 4) * 4;
+                        for (int v = 0; v < 4; ++v)
+                            if (fb * 16 + (ln >> 4) * 4 + v < p.K) {
+                                const _Float16 hi = (_Float16)sum[v];
+                                dst[v] = hi;
+                                dst[(long long)PQ * p.K + v] = (_Float16)(sum[v] - (float)hi);
+                            }
+                    }
+                }
+            }
             if (tid == 0) __hip_atomic_store(&p.cnt_ic[pg * p.grid_n + kt], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     } else {

@@ -26,6 +26,8 @@ class GpuConv16:
         self.lay = abed.get_layout(self.desc, 1, variant)
         self.y = torch.empty((s.N, s.P, s.Q, s.K), dtype=torch.float32 if out_fp32 else torch.float16, device=DEV)
         self.y2 = torch.empty_like(self.y) if variant == 6 else None
+        if (variant & 0xff) == 5:          # the next layer's checksum images come back through y2
+            self.y2 = torch.full((2, s.P, s.Q, s.K), 7.0, dtype=torch.float16, device=DEV)
         self.flags = torch.full((max(1, self.lay.n_flag_words),), -1, dtype=torch.int32, device=DEV)
         self.ws = torch.zeros((max(256, self.lay.workspace_bytes),), dtype=torch.uint8, device=DEV)
         abed.workspace_init(self.ws)
@@ -68,7 +70,7 @@ def check_outputs(y, ref):
 
 
 @pytest.mark.parametrize("out_fp32", [False, True])
-@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 6])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("s", SHAPES, ids=lambda s: s.name)
 def test_fp16_clean(oracle, s, variant, out_fp32):
     print("case", s.name, variant, out_fp32, flush=True)
@@ -77,7 +79,7 @@ def test_fp16_clean(oracle, s, variant, out_fp32):
     g.prepare(w)
     y, flags = g.run(x, rtol=1e-3, atol=1e-2)
     wchk, xchk = g.wchk.cpu().numpy(), g.xchk.cpu().numpy()
-    checked = 1 <= variant <= 4
+    checked = 1 <= variant <= 5
     ref = oracle.abed_fp16(x, w, s, 1e-3, 1e-2, wchk=wchk if checked else None, xchk=xchk if checked else None)
     check_outputs(y, ref)
     if checked:
@@ -88,13 +90,20 @@ def test_fp16_clean(oracle, s, variant, out_fp32):
         assert np.all(np.abs(xchk.astype(np.float64).sum(0) - xsum) <= 2.0 ** -18 * np.abs(xsum) + 1e-6)
         assert ref["fc_margin"].max() < -5e-3 and ref["ic_margin"].max() < -5e-3
         assert not flags.any()
+    if variant == 5:
+        # the handed-on batch checksum: hi + lo against the oracle's sum of the fp16 outputs (the kernel sums in fp32
+        # and may round an output the other way where the exact value lies on a rounding boundary: one fp16 ulp of slack)
+        nxt = g.y2.cpu().numpy().astype(np.float64).sum(0)
+        want = ref["xchk_next"].astype(np.float64).sum(0)
+        ulp = np.abs(ref["y"].astype(np.float64)).max(axis=0) * 2.0 ** -10
+        assert np.all(np.abs(nxt - want) <= np.abs(want) * 2.0 ** -18 + 1e-5 + ulp)
     if variant == 6:
         assert flags[0] == 0 and torch.equal(g.y, g.y2)
 
 
 @pytest.mark.parametrize("rtol,atol,l1,guard", [(1e-3, 1e-2, False, 2e-3), (1e-3, 0.0, True, 2e-3), (1e-4, 0.0, True, 2e-4)],
                          ids=["values_1e-3_floor_1e-2", "l1_1e-3", "l1_1e-4"])
-@pytest.mark.parametrize("base", [4, 1, 2, 3], ids=["ocg", "unfused", "write", "partial"])
+@pytest.mark.parametrize("base", [4, 1, 2, 3, 5], ids=["ocg", "unfused", "write", "partial", "iocg"])
 @pytest.mark.parametrize("s", [SHAPES[0], SHAPES[2]], ids=lambda s: s.name)
 def test_fp16_flip_detection_and_threshold(oracle, s, rtol, atol, l1, guard, base):
     """Flips of one output bit: those the oracle puts clearly above the threshold must be flagged in
@@ -164,3 +173,31 @@ def test_fp16_config4_full_tensor(oracle):
         assert not (ref["fc_bad"].any() or ref["ic_bad"].any() or ref["corner_bad"].any())
         assert ref["fc_margin"].max() < -2e-3 and ref["ic_margin"].max() < -2e-3
         assert not flags.any()
+
+
+def test_fp16_iocg_chain(oracle):
+    """Two layers chained through the handed-on checksum (Sec. 4.3): layer 2 runs with compute_xchk = 0 on the images
+    layer 1 emitted, raises no flag on clean data and flags a layer-1 output corrupted in memory between the layers."""
+    s1 = ConvShape(40, 9, 9, 32, 64, 3, 3, 1, 1, 1, 1, "l1")      # several batch tiles: the sums span tiles
+    s2 = ConvShape(40, 9, 9, 64, 48, 1, 1, 1, 1, 0, 0, "l2")
+    x, w1 = fp16_tensors(s1, 6464)
+    _, w2 = fp16_tensors(s2, 6465)
+    g1 = GpuConv16(s1, 5)
+    assert g1.lay.grid_b > 1
+    g1.prepare(w1)
+    y1, f1 = g1.run(x, 1e-3, 1e-2)
+    assert not f1.any()
+    g2 = GpuConv16(s2, 4)
+    g2.prepare(w2)
+    g2.xchk = g1.y2
+    y2, f2 = g2.run(g1.y, 1e-3, 1e-2, compute_xchk=False)
+    ref2 = oracle.abed_fp16(y1, w2, s2, 1e-3, 1e-2, wchk=g2.wchk.cpu().numpy(), xchk=g1.y2.cpu().numpy())
+    check_outputs(y2, ref2)
+    assert ref2["ic_margin"].max() < -2e-3 and not f2.any()
+    ybad = g1.y.clone()
+    idx = ((7 * s1.P + 4) * s1.Q + 2) * s1.K + 9
+    ybad.view(-1).view(torch.int16)[idx] ^= 1 << 13
+    _, f3 = g2.run(ybad, 1e-3, 1e-2, compute_xchk=False)
+    pix = 4 * s1.Q + 2
+    f3 = f3.reshape(g2.lay.grid_m, g2.lay.grid_b, g2.lay.grid_n)
+    assert (f3[pix // 16, 0, :] & 2).any() and not (np.delete(f3, pix // 16, axis=0) & 2).any()
