@@ -20,7 +20,8 @@ UNITS = [("abed_api.hip", [], "abed_api.o"),
          ("conv_dispatch.hip", [], "conv_dispatch.o")] + \
         [("conv_inst.hip", ["-DINST_WK=%d" % wk, "-DINST_KG=%d" % kg], "conv_wk%d_kg%d.o" % (wk, kg))
          for kg in (1, 2, 4) for wk in (9, 8, 5, 4, 1)] + \
-        [("conv_box_inst.hip", ["-DBOX_XCH=%d" % x], "conv_box_x%d.o" % x) for x in (8, 4, 2, 1, 0)]
+        [("conv_box_inst.hip", ["-DBOX_XCH=%d" % x], "conv_box_x%d.o" % x) for x in (8, 4, 2, 1, 0)] + \
+        [("conv_img_inst.hip", [], "conv_img.o")]
 
 
 def _compile(unit):

@@ -14,6 +14,8 @@
 #include "abft_gemm_kernels.h"
 #include "conv_launch.h"
 #include "conv_box_launch.h"
+#include "conv_img_kernel.h"
+#include "conv_img_launch.h"
 
 using namespace abed;
 
@@ -395,6 +397,66 @@ bool box_preferred_plain(const abed_conv_desc_t *d)
     return tiles >= 192;
 }
 
+// ---------------------------------------------------------------------------
+// The one-wave-per-SIMD kernel (conv_img_kernel.h): 3x3 stride-1 layers, unchecked, int32 ConvOut; opt-in (ABED_IMG=1)
+// ---------------------------------------------------------------------------
+struct ImgPlan {
+    int iw, RW, RH, rx, ry, ngroups, group_len, tiles;
+};
+
+// Region shape: among the rectangles whose positions fit the wave's 4 / iw blocks of 32 and whose input positions,
+// times the images of a batch, fit an activation stage, the one that leaves the fewest block lanes empty over the
+// image plane (ties: the least input staged per output position).  Image groups: the split with the fewest rounds of
+// 256 workgroups times (batches per group + 2) (ties: the shorter groups).
+abed_status_t make_img_plan(const abed_conv_desc_t *d, ImgPlan &ip)
+{
+    if (!box_shape_ok(d)) return ABED_EUNSUPPORTED;
+    const int P = d->H + 2 * d->pad_h - 2, Q = d->W + 2 * d->pad_w - 2;
+    double best = -1.0, best_halo = 0.0;
+    ip.iw = 0;
+    for (int iw = 1; iw <= 2; ++iw) {
+        const int maxpos = 32 * (4 / iw), maxslots = kImgPlane / (4 * iw);
+        for (int rw = 1; rw <= Q && rw <= maxpos; ++rw)
+            for (int rh = 1; rh <= P && rh * rw <= maxpos; ++rh) {
+                if ((rh + 2) * (rw + 2) > maxslots) continue;
+                const int rx = (Q + rw - 1) / rw, ry = (P + rh - 1) / rh;
+                const double eff = (double)P * Q / ((double)rx * ry * maxpos);
+                const double halo = (double)(rh + 2) * (rw + 2) / (rh * rw);
+                if (eff > best + 1e-9 || (eff > best - 1e-9 && halo < best_halo - 1e-9)) {
+                    best = eff; best_halo = halo; ip.iw = iw; ip.RW = rw; ip.RH = rh; ip.rx = rx; ip.ry = ry;
+                }
+            }
+    }
+    if (!ip.iw || !img_compiled(ip.iw)) return ABED_EUNSUPPORTED;
+    const int eb = 4 * ip.iw;
+    const long long base = (long long)ip.rx * ip.ry * (d->K / 64);
+    long long best_cost = -1;
+    for (int len = eb; ; len += eb) {
+        const int ng = (d->N + len - 1) / len;
+        const long long tiles = base * ng;
+        // a round of workgroups costs its batches plus a start and an end worth about two more
+        const long long cost = ((tiles + 255) / 256) * (len / eb + 2);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; ip.group_len = len; ip.ngroups = ng; }
+        if (len >= d->N) break;
+    }
+    ip.tiles = (int)(base * ip.ngroups);
+    return ABED_OK;
+}
+
+abed_status_t launch_img_conv(const abed_conv_desc_t *d, const ImgPlan &ip, const int8_t *x, const int8_t *w, void *y, hipStream_t st)
+{
+    ImgParams p;
+    memset(&p, 0, sizeof(p));
+    p.x = x; p.w = w; p.y = y;
+    p.N = d->N; p.H = d->H; p.W = d->W; p.C = d->C; p.K = d->K; p.ph = d->pad_h; p.pw = d->pad_w;
+    p.P = d->H + 2 * d->pad_h - 2; p.Q = d->W + 2 * d->pad_w - 2;
+    p.RW = ip.RW; p.RH = ip.RH; p.rx = ip.rx; p.ry = ip.ry; p.nch = d->C / 64; p.nft = d->K / 64;
+    p.ngroups = ip.ngroups; p.group_len = ip.group_len;
+    if (!launch_img(ip.iw, p, (ip.tiles + 7) / 8 * 8, st)) return ABED_EUNSUPPORTED;
+    LAUNCH_CHECK("img_conv_kernel");
+    return ABED_OK;
+}
+
 // An unchecked convolution with its own tile plan (the baseline, and the checksum
 // convolutions of the unfused variant).
 abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_t *w, void *y,
@@ -403,6 +465,10 @@ abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_
     Plan pl;
     abed_status_t s = make_plan(d, ABED_INT8, ABED_NONE, false, pl);
     if (s != ABED_OK) return s;
+    if (!epi && !(inject && inject->site) && env_int("ABED_IMG", 0) == 1) {
+        ImgPlan ip;
+        if (make_img_plan(d, ip) == ABED_OK) return launch_img_conv(d, ip, x, w, y, st);
+    }
     if (box_preferred_plain(d)) {
         BoxPlan bp;
         if (make_box_plan(d, false, false, bp) == ABED_OK) return launch_box_conv(d, bp, x, w, nullptr, y, epi, nullptr, inject, st);
