@@ -452,6 +452,10 @@ abed_status_t launch_img_conv(const abed_conv_desc_t *d, const ImgPlan &ip, cons
     p.P = d->H + 2 * d->pad_h - 2; p.Q = d->W + 2 * d->pad_w - 2;
     p.RW = ip.RW; p.RH = ip.RH; p.rx = ip.rx; p.ry = ip.ry; p.nch = d->C / 64; p.nft = d->K / 64;
     p.ngroups = ip.ngroups; p.group_len = ip.group_len;
+#ifdef ABED_ENABLE_DBG
+    p.dbg = env_int("ABED_DBG", 0);
+    { const char *v = getenv("ABED_DBG_PTR"); p.dbg_clk = (v && *v) ? (long long *)strtoull(v, nullptr, 0) : nullptr; }
+#endif
     if (!launch_img(ip.iw, p, (ip.tiles + 7) / 8 * 8, st)) return ABED_EUNSUPPORTED;
     LAUNCH_CHECK("img_conv_kernel");
     return ABED_OK;

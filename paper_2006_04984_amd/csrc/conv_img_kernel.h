@@ -41,6 +41,11 @@ struct ImgParams {
     int RW, RH, rx, ry;          // region size (output positions), regions per row / column of the image plane
     int nch, nft;                // C / 64, K / 64
     int ngroups, group_len;      // image groups; group_len is a multiple of the batch size
+    // builds with ABED_ENABLE_DBG only.  dbg_clk: workgroup 0 leaves the main loop's length in shader-clock ticks and in
+    // ticks of the 100 MHz real-time counter there (their ratio is the shader clock under this kernel's load);
+    // dbg bit 0: the loop's activation loads fetch nothing, bit 1: its filter loads (timing experiments, wrong outputs)
+    long long *dbg_clk;
+    int dbg;
 };
 
 constexpr int kImgPlane = 832;                   // image x position slots of an activation stage at most
@@ -189,8 +194,16 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
         // addresses of this sub-step's refill loads and of the next sub-step's first fragments (scalar work; it runs while the
         // first matrix instructions execute)
         const int bslot_new = (u + 3) & 3;
+#ifdef ABED_ENABLE_DBG
+        const int b_soff = (u + 3 < nsub && !(p.dbg & 2)) ? pf_r * 3 * p.C + pf_chunk * 64 : kMasked;
+#else
         const int b_soff = (u + 3 < nsub) ? pf_r * 3 * p.C + pf_chunk * 64 : kMasked;
+#endif
+#ifdef ABED_ENABLE_DBG
+        const bool more_a = step + 1 < nsteps && !(p.dbg & 1);
+#else
         const bool more_a = step + 1 < nsteps;
+#endif
         const int nc = chunk + 1 == p.nch ? 0 : chunk + 1;
         const int a_vbase = more_a ? (n0 + (nc == 0 ? batch + 1 : batch) * EB) * HWC : kMasked;
         const int a_soff = nc * 64;
@@ -279,11 +292,20 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
         }
         ++batch;
     };
+#ifdef ABED_ENABLE_DBG
+    const long long ck0 = (long long)__builtin_amdgcn_s_memtime(), rt0 = (long long)__builtin_amdgcn_s_memrealtime();
+#endif
 #pragma unroll 1
     for (int b2 = 0; b2 < nbatch; b2 += 2) {
         one_batch(I0{});
         if (b2 + 1 < nbatch) one_batch(I1{});
     }
+#ifdef ABED_ENABLE_DBG
+    if (p.dbg_clk && blockIdx.x == 0 && tid == 0) {
+        p.dbg_clk[0] = (long long)__builtin_amdgcn_s_memtime() - ck0;
+        p.dbg_clk[1] = (long long)__builtin_amdgcn_s_memrealtime() - rt0;
+    }
+#endif
     // stores of the last batch
     auto store_all = [&](auto par_tag) {
         constexpr int PAR = decltype(par_tag)::value;

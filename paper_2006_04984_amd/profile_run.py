@@ -28,7 +28,20 @@ def main():
                          "fic: the scalar scheme (abed_fic_conv_int8); fic_inloop: the same with its input side formed in the main loop (abed_fic_inloop_conv_int8); ic2: IC option 2, K values (abed_ic2_conv_int8)")
     ap.add_argument("--batch", type=int, default=0, help="override the configuration's batch size")
     ap.add_argument("--local", action="store_true", help="checksums local to a workgroup (ABED_LOCAL, with --variant 4)")
+    ap.add_argument("--img", action="store_true", help="unchecked 3x3 layers through the one-wave-per-SIMD kernel (sets ABED_IMG=1)")
+    ap.add_argument("--img-clock", type=int, default=-1, metavar="DBG",
+                    help="library built with ABED_ENABLE_DBG=1 only: run the --img kernel with ABED_DBG=<DBG> (0: as is, 1: the loop's "
+                         "activation loads fetch nothing, 2: its filter loads, 3: both) and print the main loop's length in shader-clock "
+                         "ticks and in real time, i.e. the shader clock under that load")
     args = ap.parse_args()
+    if args.img or args.img_clock >= 0:
+        import os
+        os.environ["ABED_IMG"] = "1"
+    clk = None
+    if args.img_clock >= 0:
+        clk = torch.zeros((2,), dtype=torch.int64, device="cuda:0")
+        os.environ["ABED_DBG"] = str(args.img_clock)
+        os.environ["ABED_DBG_PTR"] = str(clk.data_ptr())
     from synth import CONFIG2, CONFIG3, seed_for
     s = {2: CONFIG2, 3: CONFIG3}[args.config][args.layer]
     if args.batch:
@@ -50,6 +63,16 @@ def main():
     for _ in range(args.reps):
         L.run()
     torch.cuda.synchronize()
+    if clk is not None:
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record()
+        for _ in range(args.reps):
+            L.run()
+        t1.record()
+        torch.cuda.synchronize()
+        ticks, rt = (int(v) for v in clk.cpu())
+        print("main loop of workgroup 0: %d shader-clock ticks in %.2f us -> %.3f GHz; %.1f us per launch (events, eager launches)"
+              % (ticks, rt / 100.0, ticks / (rt * 10.0), t0.elapsed_time(t1) * 1e3 / args.reps))
     if args.copy_mb:
         a = torch.empty((args.copy_mb << 20,), dtype=torch.uint8, device="cuda:0")
         b = torch.empty_like(a)
