@@ -39,6 +39,8 @@ struct ImgParams {
     void *y;                     // int32 [N][P][Q][K]
     int N, H, W, C, K, P, Q, ph, pw;
     int RW, RH, rx, ry;          // region size (output positions), regions per row / column of the image plane
+    int PW;                      // pitch of the position numbering inside a region (>= RW; lanes with column >= RW idle)
+    int swz;                     // LDS swizzle constant c: channel group g of input position (hy, hx) sits in part g ^ ((hx >> 1) + c hy)
     int nch, nft;                // C / 64, K / 64
     int ngroups, group_len;      // image groups; group_len is a multiple of the batch size
     // builds with ABED_ENABLE_DBG only.  dbg_clk: workgroup 0 leaves the main loop's length in shader-clock ticks and in
@@ -76,7 +78,6 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
     const int ryi = region / p.rx, rxi = region - ryi * p.rx;
     const int y0 = ryi * p.RH, x0 = rxi * p.RW;
     const int rh = min(p.RH, p.P - y0), rw = min(p.RW, p.Q - x0);
-    const int npos = rh * rw;
     const int HP = p.RW + 2;
     const int slots = (p.RH + 2) * HP;
     const int n0 = group * p.group_len;
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, p.K * crsb, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.N * PQK4, 0x00020000);
 
-    // ---- activation stage: piece q = (e * slots + slot) * 4 + part'; the channel group fetched into part' is part' ^ ((hx >> 1) & 3)
+    // ---- activation stage: piece q = (e * slots + slot) * 4 + part'; the channel group fetched into part' is part' ^ (((hx >> 1) + c hy) & 3)
     // ---- filter sub-stage: piece q = f * 12 + sx * 4 + part'; fetched group = part' ^ ((f >> 1) & 3)
     int b_off[LB];
 #pragma unroll
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
         b_off[jj] = (ft * 64 + f) * crsb + sx * p.C + ((part ^ ((f >> 1) & 3)) << 4);
     }
     // (small non-negative integers divided in floating point: exact, the quotient's distance to an integer is at least 1/(2d))
-    const float r_slots = 1.0f / (float)slots, r_hp = 1.0f / (float)HP, r_rw = 1.0f / (float)rw;
+    const float r_slots = 1.0f / (float)slots, r_hp = 1.0f / (float)HP, r_pw = 1.0f / (float)p.PW;
     auto fdiv = [](int a, float rd) { return (int)(((float)a + 0.5f) * rd); };
     int a_off[LA];
 #pragma unroll
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
         const int iy = y0 - p.ph + hy, ix = x0 - p.pw + hx;
         a_off[jj] = kMasked;
         if (e < EB && (unsigned)iy < (unsigned)p.H && (unsigned)ix < (unsigned)p.W)
-            a_off[jj] = ((e * p.H + iy) * p.W + ix) * p.C + ((part ^ ((hx >> 1) & 3)) << 4);
+            a_off[jj] = ((e * p.H + iy) * p.W + ix) * p.C + ((part ^ (((hx >> 1) + p.swz * hy) & 3)) << 4);
     }
     auto b_slot_off = [](int s) { return s == 0 ? kImgAStage : 118784 + (s - 1) * kImgBSub; };
 
@@ -145,20 +146,23 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
     // ---- fragment addresses (k32-step t = 0; t = 1 is the same address with bit 5 flipped)
     const int zf = (lj >> 1) & 3;
     const int bfr0 = lj * 192 + (((lh ^ (zf & 1)) | (zf & 2)) << 4);
-    int afr[MB][3], out_off[MB];
+    int afr[MB][3][3], out_off[MB];      // [slot][tap column][filter row]
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
         const int iw = m / NB, b = m % NB;
         const int e = wave * IW + iw;
-        int pos = b * 32 + lj;
-        const bool valid = pos < npos;
-        if (!valid) pos = 0;
-        const int yy = fdiv(pos, r_rw), xx = pos - yy * rw;
+        const int pos = b * 32 + lj;
+        int yy = fdiv(pos, r_pw), xx = pos - yy * p.PW;
+        const bool valid = yy < rh && xx < rw;
+        // idle lanes read what a neighbour reads (the same address is served once): nothing of theirs is stored
+        yy = min(yy, rh - 1); xx = min(xx, rw - 1);
 #pragma unroll
-        for (int sx = 0; sx < 3; ++sx) {
-            const int hx = xx + sx, z = (hx >> 1) & 3;
-            afr[m][sx] = (e * slots + yy * HP + hx) * 64 + (((lh ^ (z & 1)) | (z & 2)) << 4);
-        }
+        for (int sx = 0; sx < 3; ++sx)
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                const int hx = xx + sx, hy = yy + r, z = ((hx >> 1) + p.swz * hy) & 3;
+                afr[m][sx][r] = (e * slots + hy * HP + hx) * 64 + (((lh ^ (z & 1)) | (z & 2)) << 4);
+            }
         out_off[m] = valid ? (((e * p.P + y0 + yy) * p.Q + x0 + xx) * p.K + ft * 64 + lh * 4) * 4 : kImgOOB;
     }
 
@@ -166,16 +170,16 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
     __builtin_amdgcn_s_barrier();
 
     // one fragment read; order 0..5: fa0, fb0, fa1, fb1, fb2, fb3 (the order the matrix instructions need them)
-    auto fetch_one = [&](auto it, int set, int bbase, int abase, int sx, int t) {
-        constexpr int I = decltype(it)::value;
+    auto fetch_one = [&](auto it, int set, int bbase, int abase, auto r_tag, int sx, int t) {
+        constexpr int I = decltype(it)::value, FR = decltype(r_tag)::value;
         if constexpr (I == 0) fa[set][0] = *reinterpret_cast<const i32x4 *>(lds + ((bfr0 + bbase + sx * 64) ^ (t * 32)));
         else if constexpr (I == 2) fa[set][1] = *reinterpret_cast<const i32x4 *>(lds + ((bfr0 + bbase + sx * 64) ^ (t * 32)) + 32 * 192);
         else {
             constexpr int M = I == 1 ? 0 : I - 2;
-            fb[set][M] = *reinterpret_cast<const i32x4 *>(lds + ((afr[M][sx] + abase) ^ (t * 32)));
+            fb[set][M] = *reinterpret_cast<const i32x4 *>(lds + ((afr[M][sx][FR] + abase) ^ (t * 32)));
         }
     };
-    static_for<0, 6>([&](auto it) { fetch_one(it, 0, b_slot_off(0), 0, 0, 0); });
+    static_for<0, 6>([&](auto it) { fetch_one(it, 0, b_slot_off(0), 0, std::integral_constant<int, 0>{}, 0, 0); });
 
     int st_off[MB];     // previous batch's output offsets (its stores are issued during this batch)
 #pragma unroll
@@ -209,8 +213,8 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
         const int a_soff = nc * 64;
         const int a_buf = (step + 1) & 1;
         const int cur_b = b_slot_off(u & 3), nxt_b = b_slot_off((u + 1) & 3);
-        const int cur_a = (step & 1) * kImgA1 + R * HP * 64;
-        const int nxt_a = R == 2 ? ((step + 1) & 1) * kImgA1 : (step & 1) * kImgA1 + (R + 1) * HP * 64;
+        const int cur_a = (step & 1) * kImgA1;
+        const int nxt_a = R == 2 ? ((step + 1) & 1) * kImgA1 : cur_a;
         const int wait_n = prev2_after + prev_all;
         // (3) multiply: 6 k32-steps of 8 matrix instructions; behind instruction i < 6 of a k32-step comes one fragment read of the
         // next k32-step, behind instructions 6 and 7 the refill loads and the stores
@@ -232,8 +236,8 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
                     acc[PAR][M][A] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[cur][A], fb[cur][M], acc[PAR][M][A], 0, 0, 0);
                 }
                 if constexpr (I < 6) {
-                    if constexpr (KS < 5) fetch_one(it, cur ^ 1, cur_b, cur_a, (KS + 1) >> 1, (KS + 1) & 1);
-                    else fetch_one(it, cur ^ 1, nxt_b, nxt_a, 0, 0);
+                    if constexpr (KS < 5) fetch_one(it, cur ^ 1, cur_b, cur_a, r_tag, (KS + 1) >> 1, (KS + 1) & 1);
+                    else fetch_one(it, cur ^ 1, nxt_b, nxt_a, std::integral_constant<int, (R + 1) % 3>{}, 0, 0);
                     if constexpr (KS == 0 && I == 1) {
                         // the filters of sub-step u + 1 have landed (issued in sub-step u - 2), and everybody is done with sub-step
                         // u - 1: its filter slot and, at R == 0, the activation buffer of the step before can be refilled
