@@ -248,6 +248,13 @@ def main():
     Lc, Ln = make_set(big, fused_form), make_set(big, lambda s: int(Variant.NONE))
     n256_rows = layer_rows(big, 2, Lc, Ln)
     assert_clean(Lc, "FusedOCG, 256 images")
+    # the same unchecked layers through the library's second 3x3 main loop (one wave per SIMD; opt-in, ABED_IMG=1)
+    os.environ["ABED_IMG"] = "1"
+    for row, L in zip(n256_rows, Ln):
+        t_img = event_time(L.run)
+        row["unchecked_img_kernel_us"] = t_img * 1e6
+        row["unchecked_img_kernel_tops"] = L.s.ops / t_img / 1e12
+    os.environ.pop("ABED_IMG")
     n256 = dict(note="the four layers at 256 images (8x the work per launch), same protocol", layers=n256_rows,
                 unchecked_tops=sum(s.ops for s in big) / sum(r["unchecked_us"] for r in n256_rows) / 1e6,
                 checked_tops=sum(s.ops for s in big) / sum(r["checked_total_us"] for r in n256_rows) / 1e6,
