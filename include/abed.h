@@ -177,10 +177,15 @@ typedef struct {
  *          the row+column scheme: the filter-sum of a checksum-image fmap or the batch-sum
  *          of a checksum-filter fmap differs from the fmap of checksum image x checksum
  *          filter); reported on some word of group tm.
+ *   bit 3: not a checksum mismatch: an arrival counter of the workspace was not zero when the call started
+ *          (abed_workspace_init not called on this workspace, or two calls used it at once), so some comparison
+ *          that spans tiles was made early or not at all; the call's other flag bits cannot be trusted.
+ *          Only variants 3..5 whose sums span tiles use the counters.
  * Every word is written on every checked call. */
 #define ABED_FLAG_FC 1u
 #define ABED_FLAG_IC 2u
 #define ABED_FLAG_CORNER 4u
+#define ABED_FLAG_WORKSPACE 8u
 
 /* Host only.  Fills *out; ABED_EINVAL / ABED_EUNSUPPORTED / ABED_ERANGE as above. */
 abed_status_t abed_get_layout(const abed_conv_desc_t *desc, int32_t dtype, int32_t variant,

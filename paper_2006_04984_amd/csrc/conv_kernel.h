@@ -704,10 +704,15 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
                     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                     __syncthreads();
                     if (tid == 0) {
+                        // a count at or beyond the number of tiles that share the counter: the workspace did not start at zero
+                        // (abed_workspace_init not called, or calls overlapped); some cross-tile comparison was then made
+                        // early or not at all, which the caller must learn
+                        bool stale = false;
                         if (!fc_local)
-                            e_misc[1] = __hip_atomic_fetch_add(&p.cnt_fc[pg * p.grid_b + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_n - 1);
+                            { const unsigned c = __hip_atomic_fetch_add(&p.cnt_fc[pg * p.grid_b + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); e_misc[1] = c == (unsigned)(p.grid_n - 1); stale |= c >= (unsigned)p.grid_n; }
                         if (!ic_local)
-                            e_misc[2] = __hip_atomic_fetch_add(&p.cnt_ic[pg * p.grid_n + kt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_b - 1);
+                            { const unsigned c = __hip_atomic_fetch_add(&p.cnt_ic[pg * p.grid_n + kt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); e_misc[2] = c == (unsigned)(p.grid_b - 1); stale |= c >= (unsigned)p.grid_b; }
+                        if (stale) __hip_atomic_fetch_or(&p.flags[word], 8u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
                 }
             }
@@ -1100,10 +1105,15 @@ __global__ __launch_bounds__(256 * KG) void conv_kernel(const ConvParams p)
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         if (tid == 0) {
+            // a count at or beyond the number of tiles that share the counter: the workspace did not start at zero
+            // (abed_workspace_init not called, or calls overlapped); some cross-tile comparison was then made early or
+            // not at all, which the caller must learn
+            bool stale = false;
             if (!fc_local)
-                e_misc[1] = __hip_atomic_fetch_add(&p.cnt_fc[pg * p.grid_b + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_n - 1);
+                { const unsigned c = __hip_atomic_fetch_add(&p.cnt_fc[pg * p.grid_b + nt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); e_misc[1] = c == (unsigned)(p.grid_n - 1); stale |= c >= (unsigned)p.grid_n; }
             if (!ic_local)
-                e_misc[2] = __hip_atomic_fetch_add(&p.cnt_ic[pg * p.grid_n + kt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (unsigned)(p.grid_b - 1);
+                { const unsigned c = __hip_atomic_fetch_add(&p.cnt_ic[pg * p.grid_n + kt], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); e_misc[2] = c == (unsigned)(p.grid_b - 1); stale |= c >= (unsigned)p.grid_b; }
+            if (stale) __hip_atomic_fetch_or(&p.flags[tile], 8u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     };
 
