@@ -59,7 +59,24 @@ def test_unsupported_descriptor(L):
     assert e.value.status == 2
 
 
-@pytest.mark.parametrize("s", CONFIG1 + CONFIG2 + CONFIG3 + resnet50_layers(128)[1:], ids=lambda s: s.name)
+def _other_shapes():
+    """Shapes outside the configured networks: filter counts that are no powers of two (also beyond 257: three digit
+    filters), single images and small batches, batches beyond 257 (three digit images), strides, full-HD-sized planes."""
+    from synth import ConvShape
+    return [ConvShape(1, 17, 23, 48, 40, 3, 3, 1, 1, 1, 1, "n1_k40"),
+            ConvShape(8, 135, 240, 32, 24, 3, 3, 2, 2, 1, 1, "n8_fullhd_eighth_stride2_k24"),
+            ConvShape(8, 68, 120, 96, 200, 1, 1, 1, 1, 0, 0, "n8_1x1_k200"),
+            ConvShape(3, 9, 9, 16, 272, 3, 3, 1, 1, 1, 1, "n3_k272_three_digit_filters"),
+            ConvShape(300, 7, 7, 64, 64, 3, 3, 1, 1, 1, 1, "n300_three_digit_images"),
+            ConvShape(2, 540, 960, 16, 16, 3, 3, 1, 1, 1, 1, "n2_quarter_fullhd_plane"),
+            ConvShape(5, 31, 31, 80, 112, 5, 5, 2, 2, 2, 2, "n5_5x5_stride2_k112")]
+
+
+def _digits(count):
+    return 1 if count <= 1 else 2 if count <= 257 else 3
+
+
+@pytest.mark.parametrize("s", CONFIG1 + CONFIG2 + CONFIG3 + resnet50_layers(128)[1:] + _other_shapes(), ids=lambda s: s.name)
 def test_layout_consistency(L, s):
     d = abed.desc_from_shape(s)
     for v in Variant:
@@ -72,7 +89,7 @@ def test_layout_consistency(L, s):
         assert lay.grid_b * lay.tile_batch >= entries > (lay.grid_b - 1) * lay.tile_batch
         assert lay.grid_n * lay.tile_n >= fblocks * 16 > (lay.grid_n - 1) * lay.tile_n
         assert lay.n_flag_words == lay.grid_m * lay.grid_b * lay.grid_n
-        assert lay.d_f == (2 if s.K <= 257 else 3) and lay.d_i == (2 if s.N > 1 else 1)
+        assert lay.d_f == _digits(s.K) and lay.d_i == _digits(s.N)
         assert lay.wchk_bytes == lay.d_f * s.R * s.S * s.C
         assert lay.xchk_bytes == lay.d_i * s.H * s.W * s.C
 
