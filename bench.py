@@ -262,6 +262,27 @@ def main():
     del Lc, Ln
     torch.cuda.empty_cache()
 
+    # ---- supplement: the same layers with the fused requantize + ReLU epilog (Sec. 4.3), int8 output: a quarter of the
+    # output bytes, so the first two layers are no longer bound by their stores ----
+    def i8_rows(shapes):
+        rows = []
+        for i, s in enumerate(shapes):
+            Lc = Int8Layer(s, seed_for(2, i), fused_form(s), epilogue=True)
+            Ln = Int8Layer(s, seed_for(2, i), int(Variant.NONE), epilogue=True)
+            t_c, t_n = event_time(Lc.run), event_time(Ln.run)
+            assert int(Lc.flags.abs().max().item()) == 0, "error flag set on a fault-free run (int8 output, %s)" % s.name
+            att = min(PEAK_INT8_TOPS, s.ops / s.min_bytes(1, 1, 1) * PEAK_HBM_GBS / 1e3) / PEAK_INT8_TOPS
+            rows.append(dict(layer=s.name, batch=s.N, form="local" if Lc.variant & abed.LOCAL else "layer",
+                             unchecked_us=t_n * 1e6, checked_total_us=t_c * 1e6, unchecked_tops=s.ops / t_n / 1e12,
+                             checked_tops=s.ops / t_c / 1e12, overhead_pct=100.0 * (t_c / t_n - 1.0),
+                             min_bytes_i8=s.min_bytes(1, 1, 1), attainable_frac_of_peak=att,
+                             unchecked_frac_of_attainable=s.ops / t_n / 1e12 / PEAK_INT8_TOPS / att))
+            del Lc, Ln
+        return rows
+    int8_out = dict(note="config-2 layers with the fused int8 epilog (int8 ConvOut), unchecked and FusedOCG in the library's form per layer",
+                    n32=i8_rows(layers), n256=i8_rows(big))
+    torch.cuda.empty_cache()
+
     # ---- the memory-bound 1x1 layers (64 images), unchecked, int32 ConvOut: achieved HBM rate on buffer sets
     # that together exceed twice the 256 MB last-level cache, so that no launch finds its operands cached ----
     c3 = []
@@ -312,7 +333,7 @@ def main():
                single_scheme=dict(note="the headline path carries FC (Sec. 3.1) and the batch-checksum IC (Sec. 3.2 option 1) together; here each alone, FusedOCG, same form per layer",
                                   fc_only_tops=total_ops / t_single["fc_only"] / 1e12, fc_only_overhead_pct=ovh(t_single["fc_only"]),
                                   ic_only_tops=total_ops / t_single["ic_only"] / 1e12, ic_only_overhead_pct=ovh(t_single["ic_only"])),
-               per_layer=per_layer, n256=n256, config3=dict(note="configs[2]: 1x1 layers, 64 images, unchecked, int32 ConvOut, rotating buffer sets", layers=c3),
+               per_layer=per_layer, n256=n256, int8_out=int8_out, config3=dict(note="configs[2]: 1x1 layers, 64 images, unchecked, int32 ConvOut, rotating buffer sets", layers=c3),
                measured_peaks=peaks, roofline=roofline)
 
     if not args.no_cpu_baseline:
