@@ -500,11 +500,13 @@ abed_status_t make_img_plan(const abed_conv_desc_t *d, ImgPlan &ip)
     return ABED_OK;
 }
 
-abed_status_t launch_img_conv(const abed_conv_desc_t *d, const ImgPlan &ip, const int8_t *x, const int8_t *w, void *y, hipStream_t st)
+abed_status_t launch_img_conv(const abed_conv_desc_t *d, const ImgPlan &ip, const int8_t *x, const int8_t *w, void *y, const abed_epilogue_t *epi,
+                              hipStream_t st)
 {
     ImgParams p;
     memset(&p, 0, sizeof(p));
     p.x = x; p.w = w; p.y = y;
+    if (epi) { p.scale = epi->scale; p.bias = epi->bias; p.relu = epi->relu; }
     p.N = d->N; p.H = d->H; p.W = d->W; p.C = d->C; p.K = d->K; p.ph = d->pad_h; p.pw = d->pad_w;
     p.P = d->H + 2 * d->pad_h - 2; p.Q = d->W + 2 * d->pad_w - 2;
     p.RW = ip.RW; p.RH = ip.RH; p.PW = ip.PW; p.swz = ip.swz; p.rx = ip.rx; p.ry = ip.ry; p.nch = d->C / 64; p.nft = d->K / 64;
@@ -526,9 +528,9 @@ abed_status_t plain_conv(const abed_conv_desc_t *d, const int8_t *x, const int8_
     Plan pl;
     abed_status_t s = make_plan(d, ABED_INT8, ABED_NONE, false, pl);
     if (s != ABED_OK) return s;
-    if (!epi && !(inject && inject->site) && env_int("ABED_IMG", 0) == 1) {
+    if (!(inject && inject->site) && env_int("ABED_IMG", 0) == 1) {
         ImgPlan ip;
-        if (make_img_plan(d, ip) == ABED_OK) return launch_img_conv(d, ip, x, w, y, st);
+        if (make_img_plan(d, ip) == ABED_OK) return launch_img_conv(d, ip, x, w, y, epi, st);
     }
     if (box_preferred_plain(d)) {
         BoxPlan bp;

@@ -573,10 +573,9 @@ __global__ __launch_bounds__(256 * EH, 2 / EH) void box_conv_kernel(const BoxPar
 #pragma unroll
                     for (int fb = 0; fb < FBR; ++fb) {
                         const int k = fb * 16 + lg * 4;
-                        unsigned pk = 0;
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) pk |= ((unsigned)requant(acc[i][fb][v], e_scale[k + v], e_bias[k + v], p.relu) & 0xffu) << (8 * v);
-                        __builtin_amdgcn_raw_buffer_store_b32(pk, rs_y, o, fb * 16, 0);
+                        const int a4[4] = {acc[i][fb][0], acc[i][fb][1], acc[i][fb][2], acc[i][fb][3]};
+                        const float s4[4] = {e_scale[k], e_scale[k + 1], e_scale[k + 2], e_scale[k + 3]}, b4[4] = {e_bias[k], e_bias[k + 1], e_bias[k + 2], e_bias[k + 3]};
+                        __builtin_amdgcn_raw_buffer_store_b32(requant_pack4(a4, s4, b4, p.relu), rs_y, o, fb * 16, 0);
                     }
                 }
             }

@@ -6,8 +6,11 @@ namespace abed {
 
 bool launch_img(int iw, const ImgParams &p, int grid, hipStream_t st)
 {
-    if (iw == 1) { img_conv_kernel<1><<<dim3(grid), dim3(256), 0, st>>>(p); return true; }
-    if (iw == 2) { img_conv_kernel<2><<<dim3(grid), dim3(256), 0, st>>>(p); return true; }
+    const bool out8 = p.scale != nullptr;
+    if (iw == 1 && !out8) { img_conv_kernel<1, false><<<dim3(grid), dim3(256), 0, st>>>(p); return true; }
+    if (iw == 2 && !out8) { img_conv_kernel<2, false><<<dim3(grid), dim3(256), 0, st>>>(p); return true; }
+    if (iw == 1 && out8) { img_conv_kernel<1, true><<<dim3(grid), dim3(256), 0, st>>>(p); return true; }
+    if (iw == 2 && out8) { img_conv_kernel<2, true><<<dim3(grid), dim3(256), 0, st>>>(p); return true; }
     return false;
 }
 

@@ -36,7 +36,9 @@ typedef int i32x16 __attribute__((ext_vector_type(16)));
 
 struct ImgParams {
     const int8_t *x, *w;
-    void *y;                     // int32 [N][P][Q][K]
+    void *y;                     // int32 [N][P][Q][K], or int8 after the epilog
+    const float *scale, *bias;   // epilog (Sec. 4.3): K floats each, or null (OUT8 = false)
+    int relu;
     int N, H, W, C, K, P, Q, ph, pw;
     int RW, RH, rx, ry;          // region size (output positions), regions per row / column of the image plane
     int PW;                      // pitch of the position numbering inside a region (>= RW; lanes with column >= RW idle)
@@ -57,7 +59,8 @@ constexpr int kImgBSub = 64 * 192;               // one filter sub-stage: 64 fil
 constexpr int kImgLds = 118784 + 3 * kImgBSub + 1024;
 constexpr int kImgOOB = 0x7ffffff0;
 
-template <int IW>
+// IW: images a wave holds at once; OUT8: the epilog of Sec. 4.3 is applied and int8 is stored
+template <int IW, bool OUT8>
 __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -84,7 +87,8 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
     const int n_end = min(p.N, n0 + p.group_len);
     const int nbatch = (n_end - n0 + EB - 1) / EB;
     const int HWC = p.H * p.W * p.C;
-    const int PQK4 = p.P * p.Q * p.K * 4;
+    constexpr int OB = OUT8 ? 1 : 4;                 // bytes of an output element
+    const int PQK4 = p.P * p.Q * p.K * OB;           // bytes of one image's output
     const int crsb = 9 * p.C;
 
     constexpr int kMasked = 0x40000000;
@@ -121,6 +125,30 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
 
     i32x16 acc[2][MB][MA];
     i32x4 fa[2][MA], fb[2][MB];
+    // the epilog's scale and bias of this tile's 64 filters (the prologue's barrier publishes them)
+    float *e_scale = reinterpret_cast<float *>(lds + kImgLds - 1024), *e_bias = e_scale + 64;
+    if constexpr (OUT8) {
+        if (tid < 128) e_scale[tid] = (tid < 64 ? p.scale : p.bias)[ft * 64 + (tid & 63)];
+    }
+    int st_off[MB];     // previous batch's output offsets (its stores are issued during this batch)
+#pragma unroll
+    for (int m = 0; m < MB; ++m) st_off[m] = kImgOOB;
+    // store number q (0..31) of accumulator set PAR: slot m = q / 8, filter block a = (q / 4) & 1, register group g = q & 3:
+    // this lane's filters a * 32 + 8 g + 4 h .. + 3 of its position: 16 bytes of int32, or 4 bytes after the epilog
+    auto store_item = [&](auto par_tag, auto q_tag) {
+        constexpr int PAR = decltype(par_tag)::value, Q = decltype(q_tag)::value;
+        constexpr int SM = Q / 8, SA = (Q / 4) & 1, SG = Q & 3;
+        if constexpr (!OUT8) {
+            const u32x4 v = {(unsigned)acc[PAR][SM][SA][4 * SG], (unsigned)acc[PAR][SM][SA][4 * SG + 1], (unsigned)acc[PAR][SM][SA][4 * SG + 2], (unsigned)acc[PAR][SM][SA][4 * SG + 3]};
+            __builtin_amdgcn_raw_buffer_store_b128(v, rs_y, st_off[SM], SA * 128 + SG * 32, 0);
+        } else {
+            const int k = SA * 32 + SG * 8 + lh * 4;
+            const f32x4 s4 = *reinterpret_cast<const f32x4 *>(e_scale + k), b4 = *reinterpret_cast<const f32x4 *>(e_bias + k);
+            const int a4[4] = {acc[PAR][SM][SA][4 * SG], acc[PAR][SM][SA][4 * SG + 1], acc[PAR][SM][SA][4 * SG + 2], acc[PAR][SM][SA][4 * SG + 3]};
+            const float sc[4] = {s4[0], s4[1], s4[2], s4[3]}, bi[4] = {b4[0], b4[1], b4[2], b4[3]};
+            __builtin_amdgcn_raw_buffer_store_b32(requant_pack4(a4, sc, bi, p.relu), rs_y, st_off[SM], SA * 32 + SG * 8, 0);
+        }
+    };
 
     const int nsteps = nbatch * p.nch;
     const int nsub = nsteps * 3;
@@ -163,7 +191,7 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
                 const int hx = xx + sx, hy = yy + r, z = ((hx >> 1) + p.swz * hy) & 3;
                 afr[m][sx][r] = (e * slots + hy * HP + hx) * 64 + (((lh ^ (z & 1)) | (z & 2)) << 4);
             }
-        out_off[m] = valid ? (((e * p.P + y0 + yy) * p.Q + x0 + xx) * p.K + ft * 64 + lh * 4) * 4 : kImgOOB;
+        out_off[m] = valid ? (((e * p.P + y0 + yy) * p.Q + x0 + xx) * p.K + ft * 64 + lh * 4) * OB : kImgOOB;
     }
 
     ABED_WAIT_VMCNT(0);
@@ -181,13 +209,11 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
     };
     static_for<0, 6>([&](auto it) { fetch_one(it, 0, b_slot_off(0), 0, std::integral_constant<int, 0>{}, 0, 0); });
 
-    int st_off[MB];     // previous batch's output offsets (its stores are issued during this batch)
-#pragma unroll
-    for (int m = 0; m < MB; ++m) st_off[m] = kImgOOB;
     int prev_all = 0, prev_after = 0, prev2_after = 0;   // vector-memory operations issued in sub-step u - 1 (all; after its last filter load) and in sub-step u - 2 after its last filter load
 
     auto wait_upto = [&](int n) {
-        if (n >= 35) ABED_WAIT_VMCNT(35); else if (n >= 32) ABED_WAIT_VMCNT(32); else if (n >= 20) ABED_WAIT_VMCNT(20); else if (n >= 16) ABED_WAIT_VMCNT(16);
+        if (n >= 35) ABED_WAIT_VMCNT(35); else if (n >= 32) ABED_WAIT_VMCNT(32); else if (n >= 24) ABED_WAIT_VMCNT(24); else if (n >= 23) ABED_WAIT_VMCNT(23);
+        else if (n >= 20) ABED_WAIT_VMCNT(20); else if (n >= 16) ABED_WAIT_VMCNT(16);
         else if (n >= 12) ABED_WAIT_VMCNT(12); else if (n >= 3) ABED_WAIT_VMCNT(3); else ABED_WAIT_VMCNT(0);
     };
 
@@ -223,7 +249,8 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
             constexpr int cur = KS & 1;
             if constexpr (R == 2 && KS == 3) {
                 // the next step's activations (last load: R == 1, k32-step 3) have landed for everybody before anyone reads them
-                if constexpr (ST) ABED_WAIT_VMCNT(26); else ABED_WAIT_VMCNT(6);
+                // (vector-memory operations issued since the last activation load, R == 0, k32-step 5)
+                if constexpr (ST && OUT8) ABED_WAIT_VMCNT(25); else if constexpr (ST) ABED_WAIT_VMCNT(26); else ABED_WAIT_VMCNT(6);
                 __builtin_amdgcn_s_barrier();
             }
             static_for<0, 8>([&](auto it) {
@@ -254,14 +281,18 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
                     if constexpr (R == 0 && SL == 1) dma_a(std::integral_constant<int, KS>{}, a_buf, a_vbase, a_soff);
                     if constexpr (R == 0 && SL == 1 && KS < 4) dma_a(std::integral_constant<int, (KS < 4 ? 9 + KS : 0)>{}, a_buf, a_vbase, a_soff);
                     if constexpr (R == 0 && SL == 0 && KS >= 3) dma_a(std::integral_constant<int, (KS >= 3 ? 3 + KS : 0)>{}, a_buf, a_vbase, a_soff);
-                    // stores of the previous batch: R == 1: k32-steps 4, 5 (stores 0..7); R == 2: every k32-step (stores 8..31)
-                    if constexpr (ST && ((R == 1 && KS >= 4) || R == 2)) {
+                    // stores of the previous batch.  int32: R == 1: k32-steps 4, 5 (stores 0..7); R == 2: every k32-step (stores 8..31),
+                    // two per side slot.  int8 (each store comes with its epilog arithmetic): one per side slot, from the
+                    // fifth side slot of R == 0 to the tenth of R == 2
+                    if constexpr (ST && !OUT8 && ((R == 1 && KS >= 4) || R == 2)) {
                         static_for<0, 2>([&](auto qt) {
                             constexpr int Q = R == 1 ? (KS - 4) * 4 + SL * 2 + decltype(qt)::value : 8 + KS * 4 + SL * 2 + decltype(qt)::value;
-                            constexpr int SM = Q / 8, SA = (Q / 4) & 1, SG = Q & 3;    // slot m, filter block a, register group g
-                            const u32x4 v = {(unsigned)acc[PAR ^ 1][SM][SA][4 * SG], (unsigned)acc[PAR ^ 1][SM][SA][4 * SG + 1], (unsigned)acc[PAR ^ 1][SM][SA][4 * SG + 2], (unsigned)acc[PAR ^ 1][SM][SA][4 * SG + 3]};
-                            __builtin_amdgcn_raw_buffer_store_b128(v, rs_y, st_off[SM], SA * 128 + SG * 32, 0);
+                            store_item(std::integral_constant<int, PAR ^ 1>{}, std::integral_constant<int, Q>{});
                         });
+                    }
+                    if constexpr (ST && OUT8) {
+                        constexpr int Q = R * 12 + KS * 2 + SL - 4;
+                        if constexpr (Q >= 0 && Q < 32) store_item(std::integral_constant<int, PAR ^ 1>{}, std::integral_constant<int, Q>{});
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -269,8 +300,13 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
         });
         // vector-memory operations of this sub-step: in all / after its last filter load
         prev2_after = prev_after;
-        prev_all = R == 0 ? 16 : R == 1 ? (ST ? 11 : 3) : (ST ? 27 : 3);
-        prev_after = R == 0 ? 9 : R == 1 ? (ST ? 8 : 0) : (ST ? 16 : 0);
+        if constexpr (ST && OUT8) {
+            prev_all = R == 0 ? 24 : 15;
+            prev_after = R == 0 ? 17 : 8;
+        } else {
+            prev_all = R == 0 ? 16 : R == 1 ? (ST ? 11 : 3) : (ST ? 27 : 3);
+            prev_after = R == 0 ? 9 : R == 1 ? (ST ? 8 : 0) : (ST ? 16 : 0);
+        }
         ++u;
         if (++pf_r == 3) { pf_r = 0; if (++pf_chunk == p.nch) pf_chunk = 0; }
         if (R == 2) { ++step; if (++chunk == p.nch) chunk = 0; }
@@ -312,16 +348,7 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
 #endif
     // stores of the last batch
     auto store_all = [&](auto par_tag) {
-        constexpr int PAR = decltype(par_tag)::value;
-#pragma unroll
-        for (int m = 0; m < MB; ++m)
-#pragma unroll
-            for (int a = 0; a < MA; ++a)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const u32x4 v = {(unsigned)acc[PAR][m][a][4 * g], (unsigned)acc[PAR][m][a][4 * g + 1], (unsigned)acc[PAR][m][a][4 * g + 2], (unsigned)acc[PAR][m][a][4 * g + 3]};
-                    __builtin_amdgcn_raw_buffer_store_b128(v, rs_y, st_off[m], a * 128 + g * 32, 0);
-                }
+        static_for<0, 32>([&](auto q_tag) { store_item(par_tag, q_tag); });
     };
     if (((nbatch - 1) & 1) == 0) store_all(I0{}); else store_all(I1{});
 #endif

@@ -1,5 +1,6 @@
-"""GPU parity for the one-wave-per-SIMD 3x3 convolution kernel (opt-in, ABED_IMG=1; unchecked, int32 ConvOut):
-whole output tensors, bit for bit, against the oracle's 7-loop convolution (Sec. 2.2), on shapes that cover
+"""GPU parity for the one-wave-per-SIMD 3x3 convolution kernel (opt-in, ABED_IMG=1; unchecked; int32 ConvOut, or int8
+after the epilog of Sec. 4.3): whole output tensors, bit for bit, against the oracle's 7-loop convolution (Sec. 2.2)
+and its requantised outputs, on shapes that cover
 both wave layouts (regions of up to 64 and up to 128 positions), ragged regions, paddings 0..2, several
 chunks of channels, several filter tiles, several batches per workgroup and a batch tail."""
 import dataclasses
@@ -9,7 +10,7 @@ import pytest
 import torch
 
 import paper_2006_04984_amd as abed
-from synth import CONFIG2, ConvShape, int8_tensors
+from synth import CONFIG2, ConvShape, int8_tensors, requant_params
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -26,11 +27,15 @@ SHAPES = [ConvShape(8, 8, 8, 64, 64, 3, 3, 1, 1, 1, 1, "n8_8x8"),
           ConvShape(1, 9, 9, 64, 192, 3, 3, 1, 1, 1, 1, "n1_three_tiles")]
 
 
-def run_plain(s, x, w):
+def run_plain(s, x, w, epilogue=None):
     desc = abed.desc_from_shape(s)
     xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
-    y = torch.full((s.N, s.P, s.Q, s.K), -3, dtype=torch.int32, device=DEV)
-    abed.conv_int8(desc, xd, wd, None, None, False, y, 0)
+    y = torch.full((s.N, s.P, s.Q, s.K), -3, dtype=torch.int8 if epilogue else torch.int32, device=DEV)
+    epi = None
+    if epilogue:
+        sc, bi = torch.from_numpy(epilogue[0]).to(DEV), torch.from_numpy(epilogue[1]).to(DEV)
+        epi = (sc, bi, epilogue[2])
+    abed.conv_int8(desc, xd, wd, None, None, False, y, 0, epilogue=epi)
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
@@ -40,7 +45,11 @@ def test_img_kernel_matches_oracle(oracle, monkeypatch, s):
     print("case", s.name, flush=True)
     monkeypatch.setenv("ABED_IMG", "1")
     x, w = int8_tensors(s, 9100 + s.N)
-    assert np.array_equal(run_plain(s, x, w), oracle.conv_int(x, w, s).astype(np.int32))
+    ref = oracle.conv_int(x, w, s)
+    assert np.array_equal(run_plain(s, x, w), ref.astype(np.int32))
+    sc, bi = requant_params(s, 9100 + s.N)
+    for relu in (True, False):
+        assert np.array_equal(run_plain(s, x, w, epilogue=(sc, bi, relu)), oracle.epilog_int8(ref, sc, bi, relu))
 
 
 @pytest.mark.parametrize("i", range(4))
@@ -50,4 +59,7 @@ def test_img_kernel_config2_layers_whole_tensor(oracle, monkeypatch, i):
     print("case", s.name, flush=True)
     monkeypatch.setenv("ABED_IMG", "1")
     x, w = int8_tensors(s, 9200 + i)
-    assert np.array_equal(run_plain(s, x, w), oracle.conv_int(x, w, s).astype(np.int32))
+    ref = oracle.conv_int(x, w, s)
+    assert np.array_equal(run_plain(s, x, w), ref.astype(np.int32))
+    sc, bi = requant_params(s, 9200 + i)
+    assert np.array_equal(run_plain(s, x, w, epilogue=(sc, bi, True)), oracle.epilog_int8(ref, sc, bi, True))
