@@ -52,7 +52,7 @@ struct ImgParams {
     int dbg;
 };
 
-constexpr int kImgPlane = 832;                   // image x position slots of an activation stage at most
+constexpr int kImgPlane = 832;                   // 64-byte slots (images of a batch x input positions of a region) of an activation stage at most
 constexpr int kImgAStage = kImgPlane * 64;       // 53248 bytes
 constexpr int kImgA1 = 65536;                    // where the second activation stage starts
 constexpr int kImgBSub = 64 * 192;               // one filter sub-stage: 64 filters x 3 taps x 64 channels
@@ -96,7 +96,6 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, p.K * crsb, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_y = __builtin_amdgcn_make_buffer_rsrc(p.y, 0, p.N * PQK4, 0x00020000);
 
-    // ---- activation stage: piece q = (e * slots + slot) * 4 + part'; the channel group fetched into part' is part' ^ (((hx >> 1) + c hy) & 3)
     // ---- filter sub-stage: piece q = f * 12 + sx * 4 + part'; fetched group = part' ^ ((f >> 1) & 3)
     int b_off[LB];
 #pragma unroll
@@ -106,6 +105,7 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
         const int sx = rem >> 2, part = rem & 3;
         b_off[jj] = (ft * 64 + f) * crsb + sx * p.C + ((part ^ ((f >> 1) & 3)) << 4);
     }
+    // ---- activation stage: piece q = (e * slots + slot) * 4 + part'; the channel group fetched into part' is part' ^ (((hx >> 1) + c hy) & 3)
     // (small non-negative integers divided in floating point: exact, the quotient's distance to an integer is at least 1/(2d))
     const float r_slots = 1.0f / (float)slots, r_hp = 1.0f / (float)HP, r_pw = 1.0f / (float)p.PW;
     auto fdiv = [](int a, float rd) { return (int)(((float)a + 0.5f) * rd); };
@@ -195,6 +195,7 @@ __global__ __launch_bounds__(256, 1) void img_conv_kernel(const ImgParams p)
     }
 
     ABED_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_waitcnt(0xc07f);          // this wave's LDS writes (scale and bias) are done: lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
 
     // one fragment read; order 0..5: fa0, fb0, fa1, fb1, fb2, fb3 (the order the matrix instructions need them)
