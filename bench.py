@@ -71,14 +71,15 @@ def main():
     stream = torch.cuda.Stream()
     V_OCG, V_LOCAL = int(Variant.FUSED_OCG), int(Variant.FUSED_OCG) | abed.LOCAL
 
-    def fused_form(s):
+    def fused_form(s, only=0):
         """The form of FusedOCG a layer takes: ABED_LOCAL where the shape is covered and the library's own
-        timing rule prefers it (abed_layout_t.local_preferred), else the layer-wide checksums."""
+        timing rule prefers it (abed_layout_t.local_preferred), else the layer-wide checksums.  only: ABED_ONLY_FC
+        or ABED_ONLY_IC (one scheme alone; the rule looks at the scheme)."""
         try:
-            lay = abed.get_layout(abed.desc_from_shape(s), 0, V_LOCAL)
+            lay = abed.get_layout(abed.desc_from_shape(s), 0, V_LOCAL | only)
         except abed.AbedError:
-            return V_OCG
-        return V_LOCAL if lay.local_preferred else V_OCG
+            return V_OCG | only
+        return (V_LOCAL if lay.local_preferred else V_OCG) | only
 
     def graph_of(fn, per_graph):
         with torch.cuda.stream(stream):
@@ -172,7 +173,7 @@ def main():
     # each of the two checksum schemes of the headline path alone (Table 1 of Sec. 3.4), same form per layer
     t_single = {}
     for name, bit in (("fc_only", abed.ONLY_FC), ("ic_only", abed.ONLY_IC)):
-        Ls = make_set(layers, lambda s: fused_form(s) | bit)
+        Ls = make_set(layers, lambda s: fused_form(s, bit))
         t_single[name] = time_steps(step_of(Ls), sub_steps, sub_warm)[0]
         assert_clean(Ls, name)
         del Ls
@@ -255,11 +256,31 @@ def main():
         row["unchecked_img_kernel_us"] = t_img * 1e6
         row["unchecked_img_kernel_tops"] = L.s.ops / t_img / 1e12
     os.environ.pop("ABED_IMG")
-    n256 = dict(note="the four layers at 256 images (8x the work per launch), same protocol", layers=n256_rows,
-                unchecked_tops=sum(s.ops for s in big) / sum(r["unchecked_us"] for r in n256_rows) / 1e6,
-                checked_tops=sum(s.ops for s in big) / sum(r["checked_total_us"] for r in n256_rows) / 1e6,
-                overhead_pct=100.0 * (sum(r["checked_total_us"] for r in n256_rows) / sum(r["unchecked_us"] for r in n256_rows) - 1.0))
     del Lc, Ln
+    torch.cuda.empty_cache()
+    # the other schemes at 256 images: FC alone (Sec. 3.1; the library's form per layer) and FIC (Sec. 3.3; fused
+    # option, its one-workgroup comparison launch included)
+    for i, (row, s) in enumerate(zip(n256_rows, big)):
+        Lf = Int8Layer(s, seed_for(2, i), fused_form(s, abed.ONLY_FC))
+        t_fc = event_time(Lf.run)
+        assert int(Lf.flags.abs().max().item()) == 0, "error flag set on a fault-free run (FC alone, 256 images, %s)" % s.name
+        del Lf
+        Lq = FicLayer(s, seed_for(2, i), Variant.FUSED_OCG)
+        t_q = event_time(Lq.run)
+        r = Lq.result.cpu().numpy()
+        assert int(Lq.flag.item()) == 0 and r[0] == r[1], "FIC mismatch on a fault-free run (256 images)"
+        del Lq
+        row.update(fc_only_us=t_fc * 1e6, fc_only_overhead_pct=100.0 * (t_fc * 1e6 / row["unchecked_us"] - 1.0),
+                   fic_fused_us=t_q * 1e6, fic_fused_overhead_pct=100.0 * (t_q * 1e6 / row["unchecked_us"] - 1.0))
+        torch.cuda.empty_cache()
+    t_plain_256 = sum(r["unchecked_us"] for r in n256_rows)
+    n256 = dict(note="the four layers at 256 images (8x the work per launch), same protocol; overhead_pct is FC + IC FusedOCG (the north-star scheme), fc_only / fic_fused the other schemes of Sec. 3",
+                layers=n256_rows,
+                unchecked_tops=sum(s.ops for s in big) / t_plain_256 / 1e6,
+                checked_tops=sum(s.ops for s in big) / sum(r["checked_total_us"] for r in n256_rows) / 1e6,
+                overhead_pct=100.0 * (sum(r["checked_total_us"] for r in n256_rows) / t_plain_256 - 1.0),
+                fc_only_overhead_pct=100.0 * (sum(r["fc_only_us"] for r in n256_rows) / t_plain_256 - 1.0),
+                fic_fused_overhead_pct=100.0 * (sum(r["fic_fused_us"] for r in n256_rows) / t_plain_256 - 1.0))
     torch.cuda.empty_cache()
 
     # ---- supplement: the same layers with the fused requantize + ReLU epilog (Sec. 4.3), int8 output: a quarter of the
