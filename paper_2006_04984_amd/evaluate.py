@@ -377,14 +377,29 @@ def cmd_resnet50(args):
     stream = torch.cuda.Stream()
     total_ops = sum(s.ops for s in layers)
     result = dict(batch=args.batch, layers=len(layers), gop=total_ops / 1e9)
+    def preferred(s, only):
+        """FusedOCG in the form the library's timing rule prefers for the layer: checksums local to a workgroup
+        (ABED_LOCAL) where the shape is covered and abed_layout_t.local_preferred says so, else layer-wide."""
+        v = int(Variant.FUSED_OCG) | only
+        try:
+            return v | abed.LOCAL if abed.get_layout(abed.desc_from_shape(s), 0, v | abed.LOCAL).local_preferred else v
+        except abed.AbedError:
+            return v
+
+    n_local = {}
     for mode, variant in (("unchecked", Variant.NONE), ("checked_iocg", Variant.FUSED_IOCG), ("checked_ocg", Variant.FUSED_OCG),
-                          ("duplicate", Variant.DUPLICATE), ("fc_only", Variant.FUSED_OCG | abed.ONLY_FC)):
+                          ("duplicate", Variant.DUPLICATE), ("fc_only", Variant.FUSED_OCG | abed.ONLY_FC),
+                          ("checked_ocg_preferred_form", None), ("fc_only_preferred_form", None)):
         objs, chained = [], []
         prev = None
+        per_layer = variant is None
         for i, s in enumerate(layers):
             if s.C % 16:      # the 3-channel stem: channels padded with zeros to 16 by the caller
                 s = ConvShape(s.N, s.H, s.W, 16, s.K, s.R, s.S, s.stride_h, s.stride_w, s.pad_h, s.pad_w, s.name)
             chain = prev is not None and s.name.split(".")[-1] in ("c2", "c3") and prev.s.name.split(".")[0] == s.name.split(".")[0]
+            if per_layer:
+                variant = preferred(s, abed.ONLY_FC if mode.startswith("fc_only") else 0)
+                n_local[mode] = n_local.get(mode, 0) + (1 if variant & abed.LOCAL else 0)
             L = Int8Layer(s, 5000 + i, variant, epilogue=True, x=prev.y if chain else None)
             objs.append(L)
             chained.append(chain)
@@ -405,6 +420,10 @@ def cmd_resnet50(args):
             assert not bad, "flags set on a clean run: %s" % bad
         t = _graph_time(step, stream, reps=2, replays=5)
         result[mode] = dict(ms=t * 1e3, tops=total_ops / t / 1e12)
+        if per_layer:
+            result[mode]["local_layers"] = n_local[mode]
+            result[mode + "_overhead_pct"] = 100.0 * (result[mode]["ms"] / result["unchecked"]["ms"] - 1.0)
+            variant = None
         del objs
         torch.cuda.empty_cache()
     # the FIC scheme (Sec. 3.3), fused option, every layer with its own input checksum generation
